@@ -1,0 +1,227 @@
+"""Pins for the CPU checker: brute force, closed forms and invariants fixed by the paper.
+
+None of these re-types a formula of oracle/gr_oracle.py: the expected values come from
+explicit LPs (Eq. opt-lp, Eq. relaxed-lp), from enumeration of all subsets (Thm 3.1) or
+all draft tuples (Eq. cases), from the outer-residual LP (Thm 6.1) and from the classic
+single-draft rule (App. A) that n = 1 must reduce to."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import brute
+from oracle import gr_oracle as G
+from paper_2511_15898_amd import workloads as W
+
+
+def _norm64(x):
+    x = np.asarray(x, np.float64)
+    return x / x.sum()
+
+
+def _random_rows(seed, count, V, alphas=(0.2, 0.5, 1.0, 3.0), mix=True):
+    rng = np.random.default_rng(seed)
+    for t in range(count):
+        a = rng.choice(alphas)
+        p = rng.dirichlet(np.full(V, a)).astype(np.float32)
+        q = rng.dirichlet(np.full(V, a)).astype(np.float32)
+        if mix and t % 3 == 0:
+            q = (0.7 * p + 0.3 * q).astype(np.float32)
+        p = np.maximum(p, np.float32(1e-20)); q = np.maximum(q, np.float32(1e-20))
+        yield (p / p.sum()).astype(np.float32), (q / q.sum()).astype(np.float32)
+
+
+# ------------------------------------------------------------------ alpha*, H*
+def test_alpha_star_equals_lp_optimum_on_tiny():
+    """Thm 3.1: alpha* = optimum of the OTLP = optimum of the relaxed OTLP, V=8, n=2."""
+    wl = W.tiny(B=16)
+    for b in range(wl.B):
+        sol = G.solve_row(wl.p[b], wl.q[b], 2, 0, tol=0.0)
+        pp, qq = _norm64(wl.p[b]), _norm64(wl.q[b])
+        assert abs(sol.alpha_star - brute.relaxed_otlp_value(pp, qq, 2)) < 1e-7
+        if b < 4:
+            assert abs(sol.alpha_star - brute.otlp_value(pp, qq, 2)) < 1e-6
+
+
+def test_alpha_star_and_hstar_equal_subset_enumeration():
+    """Thm 3.1 over all 2^V subsets; Sec. 5.1: a prefix of the ratio order attains it."""
+    for n in (2, 3, 5):
+        wl = W.tiny(B=60, n=n, seed_sub=n)
+        for b in range(wl.B):
+            sol = G.solve_row(wl.p[b], wl.q[b], n, 0, tol=0.0)
+            val, H = brute.psi_min_all_subsets(_norm64(wl.p[b]), _norm64(wl.q[b]), n)
+            assert abs(sol.alpha_star - (1.0 + val)) < 1e-12
+            if not sol.fragile:
+                assert sorted(int(t) for t in sol.order[: sol.h]) == sorted(H)
+
+
+def test_n1_reduces_to_single_draft_speculative_sampling():
+    """n = 1: alpha* = sum_i min(p_i, q_i); a drafted token i is kept with probability
+    min(1, p_i/q_i) and otherwise replaced by a draw from (p - q)_+ normalised (App. A)."""
+    for p, q in _random_rows(7, 30, 9):
+        sol = G.solve_row(p, q, 1, 0, tol=0.0)
+        pp, qq = _norm64(p), _norm64(q)
+        assert abs(sol.alpha_star - np.minimum(pp, qq).sum()) < 1e-12
+        resid = np.maximum(pp - qq, 0.0)
+        for i in range(9):
+            pi, acc = G.policy_slice(sol, p, (i,))
+            keep = min(1.0, pp[i] / qq[i])
+            assert abs(acc - keep) < 1e-9
+            expect = (1.0 - keep) * resid / resid.sum() if keep < 1.0 else np.zeros(9)
+            expect[i] += keep
+            assert np.abs(pi - expect).max() < 1e-9
+
+
+def test_acceptance_nondecreasing_in_n_and_one_when_p_equals_q():
+    wl = W.small(B=8)
+    for b in range(wl.B):
+        prev = -1.0
+        for n in (1, 2, 3, 4, 8, 16):
+            sol = G.solve_row(wl.p[b], wl.q[b], n, 32, tol=1e-2, max_T=1)  # alpha* needs no solve
+            assert sol.alpha_star >= prev - 1e-15
+            prev = sol.alpha_star
+    for p, _ in _random_rows(3, 5, 12):
+        sol = G.solve_row(p, p, 3, 0, tol=0.0)
+        assert abs(sol.alpha_star - 1.0) < 1e-12
+
+
+# ------------------------------------------------------------------ outer residuals
+def test_outer_targets_satisfy_outer_residual_lp():
+    """Thm 6.1 by brute force over every S outside H*, and sum of residuals = 1 - alpha*."""
+    for n in (2, 3):
+        for p, q in _random_rows(11 + n, 40, 7):
+            sol = G.solve_row(p, q, n, 0, tol=0.0, max_T=1)
+            pp, qq = _norm64(p), _norm64(q)
+            H = [int(t) for t in sol.order[: sol.h]]
+            p_out = {int(t): sol.target[m] for m, t in enumerate(sol.order) if m >= sol.h}
+            assert brute.outer_residual_violation(pp, qq, n, H, p_out) < 1e-7
+            assert abs(sol.rho.sum() - (1.0 - sol.alpha_star)) < 1e-12
+            assert np.all(sol.rho >= 0) and np.all(sol.target >= -1e-15)
+
+
+# ------------------------------------------------------------------ evaluators
+@pytest.mark.parametrize("slack", [0, 1])
+def test_three_evaluators_agree(slack):
+    """Definition by tuple enumeration == the paper's inclusion-exclusion grouping (App.
+    "Truncated Solver Details") == the generating-function quadrature."""
+    rng = np.random.default_rng(5 + slack)
+    for _ in range(25):
+        n = int(rng.integers(1, 5)); m = int(rng.integers(1, 6))
+        mass = rng.dirichlet(np.ones(m + 1)) * rng.uniform(0.3, 1.0)
+        ctx, q = float(mass[0]) * float(rng.integers(0, 2)), mass[1:]
+        w = np.exp(rng.normal(0, 3, size=m))
+        Re, R0e = G.routed_enum(n, ctx, slack, q, w)
+        Rg, R0g = G.routed_grouped(n, ctx, slack, q, w)
+        Rq, R0q = G.routed_quadrature(n, ctx, slack, q, w)
+        assert np.abs(Re - Rg).max() < 1e-12 and abs(R0e - R0g) < 1e-12
+        assert np.abs(Rq / Re - 1).max() < 1e-10
+        if slack:
+            assert abs(R0q / R0e - 1) < 1e-10
+        total = (ctx + q.sum()) ** n - (0.0 if slack else ctx ** n)   # columns are exactly normalised
+        assert abs(Re.sum() + R0e - total) < 1e-12
+
+
+def test_quadrature_has_converged_in_its_step():
+    rng = np.random.default_rng(9)
+    q = rng.dirichlet(np.ones(40) * 0.3) * 0.9; w = np.exp(rng.normal(2, 4, size=40))
+    for slack in (0, 1):
+        a, a0 = G.routed_quadrature(8, 0.05, slack, q, w)
+        b, b0 = G.routed_quadrature(8, 0.05, slack, q, w, step=0.1)
+        assert np.abs(a / b - 1).max() < 1e-11 and abs(a0 - b0) <= 1e-11 * max(b0, 1e-300)
+        assert abs(a.sum() + a0 - ((0.05 + q.sum()) ** 8 - (0 if slack else 0.05 ** 8))) < 1e-11
+
+
+def test_quadrature_matches_grouping_at_moderate_size():
+    rng = np.random.default_rng(10)
+    q = rng.dirichlet(np.ones(12)) * 0.8; w = np.exp(rng.normal(0, 2, size=12))
+    for slack in (0, 1):
+        Rg, R0g = G.routed_grouped(3, 0.1, slack, q, w)
+        Rq, R0q = G.routed_quadrature(3, 0.1, slack, q, w)
+        assert np.abs(Rq / Rg - 1).max() < 1e-10 and abs(R0q - R0g) < 1e-12
+
+
+# ------------------------------------------------------------------ the coupling itself
+def _check_coupling(p, q, n, k, tol, marg_tol, acc_tol):
+    sol = G.solve_row(p, q, n, k, tol=tol)
+    assert sol.status == G.STATUS_OK
+    qq = np.zeros(len(q)); sup = G.topk_support(q, k); qq[sup] = _norm64(q[sup])
+    marg, acc, norm = brute.coupling_marginals(lambda t: G.policy_slice(sol, p, t), qq, n)
+    assert norm < 1e-12                                  # every slice is a distribution
+    assert np.abs(marg - _norm64(p)).sum() < marg_tol    # output marginal equals p
+    assert abs(acc - sol.alpha_star) < acc_tol           # and the acceptance is the optimum
+    return sol
+
+
+def test_marginal_equals_p_and_acceptance_is_optimal_tiny():
+    wl = W.tiny(B=40)
+    for b in range(wl.B):
+        _check_coupling(wl.p[b], wl.q[b], 2, 0, 0.0, 1e-6, 1e-9)
+
+
+def test_marginal_with_nontrivial_outer_blocks_and_n3():
+    seen_block = 0
+    for i, (p, q) in enumerate(_random_rows(1, 120, 7)):
+        n = 2 + i % 2
+        sol = _check_coupling(p, q, n, 0, 0.0, 1e-6, 1e-9)
+        seen_block += any(b.slack == 0 and b.hi - b.lo >= 2 for b in sol.blocks)
+    assert seen_block >= 10          # the block rule was exercised
+
+
+def test_truncated_runs_respect_the_papers_bounds():
+    """Lemma 6.6 / Sec. 6.3: at most 15*tol L1 from p and 10*tol from alpha*."""
+    for tol in (1e-2, 1e-3):
+        hit = 0
+        for i, (p, q) in enumerate(_random_rows(21, 60, 8, alphas=(0.1, 0.2))):
+            n = 2 + i % 2
+            full = G.solve_row(p, q, n, 0, tol=0.0)
+            sol = _check_coupling(p, q, n, 0, tol, 15 * tol, 10 * tol)
+            hit += sum(len(b.active) for b in sol.blocks) < sum(len(b.active) for b in full.blocks)
+        assert hit >= 5               # truncation really dropped variables
+
+
+def test_topk_is_the_full_problem_with_the_restricted_draft():
+    """App. "Top-k Sampling ...": solving on V_0 with p sliced is the relaxed OTLP over
+    all of V with the top-k renormalised draft.  The LP is built over the full V."""
+    for i, (p, q) in enumerate(_random_rows(31, 12, 7, mix=False)):
+        k = 3 + i % 3
+        qq = np.zeros(7); sup = G.topk_support(q, k); qq[sup] = _norm64(q[sup])
+        assert len(sup) == k
+        sol = _check_coupling(p, q, 2, k, 0.0, 1e-6, 1e-9)
+        assert abs(sol.alpha_star - brute.relaxed_otlp_value(_norm64(p), qq, 2)) < 1e-7
+        assert sorted(int(t) for t in sol.order) == [int(t) for t in sup]
+
+
+# ------------------------------------------------------------------ sampling and statuses
+def test_inverse_cdf_reproduces_the_slice():
+    rng = np.random.default_rng(2)
+    pi = rng.dirichlet(np.ones(12) * 0.4); pi[3] = 0.0; pi /= pi.sum()
+    drafts = (7, 2, 7, 9)
+    N = 20000
+    hist = np.zeros(12); acc = 0
+    for j in range(N):
+        tok, ok, _ = G.sample_token(pi, drafts, (j + 0.5) / N)
+        hist[tok] += 1; acc += ok
+    assert np.abs(hist / N - pi).max() <= 1.0 / N + 1e-12
+    assert abs(acc / N - pi[[7, 2, 9]].sum()) <= 2.0 / N
+
+
+def test_status_codes_and_fallback():
+    wl = W.small(B=2)
+    sol = G.solve_row(wl.p[0], wl.q[0], 4, 32, tol=1e-6, max_T=4)
+    assert sol.status == G.STATUS_TRUNC_CAP
+    pi, acc = G.policy_slice(sol, wl.p[0], wl.drafts[0])
+    assert np.abs(pi - _norm64(wl.p[0])).max() < 1e-15       # valid fallback transport: sample from p
+    sol = G.solve_row(wl.p[0], wl.q[0], 4, 32, tol=1e-6, max_iter=2)
+    assert sol.status == G.STATUS_ITER_CAP
+    bad = wl.p[1].copy(); bad[5] = np.nan
+    assert G.solve_row(bad, wl.q[1], 4, 32).status == G.STATUS_BAD_ROW
+    assert G.solve_row(wl.p[1] * np.float32(0.5), wl.q[1], 4, 32).status == G.STATUS_BAD_ROW
+
+
+def test_zero_probability_tokens():
+    p = np.array([0.5, 0.0, 0.25, 0.25, 0.0, 0.0], np.float32)
+    q = np.array([0.2, 0.3, 0.0, 0.4, 0.1, 0.0], np.float32)
+    sol = _check_coupling(p, q, 2, 0, 0.0, 1e-9, 1e-9)
+    assert [int(t) for t in sol.order[:2]] == [1, 4]          # p = 0, q > 0 rank first
+    assert 2 not in sol.pos_of and 5 not in sol.pos_of        # q = 0 is never drafted
