@@ -1,0 +1,123 @@
+#!/usr/bin/env python3
+"""Benchmark of the Global Resolution verifier on one MI355X.
+
+One "step" = the whole hot path over one batch of synthetic input already resident in HBM:
+gr_solve (streaming support selection + per-row solve) followed by gr_verify.  Default workload:
+the large-vocabulary configuration (B=256 rows, V=128256, n=8 drafts, top-k 128).
+
+Prints ONE JSON line: solves/s, ms per step, the roofline of the dominant kernel (durations from
+HIP events recorded around every launch of the timed region) and the CPU checker timed on a
+bounded sample of the same rows.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64 lanes x 2 flop x 2.4 GHz)
+
+
+def cpu_baseline(wl, tol, budget_s=15.0):
+    """The CPU checker as it stands, single thread, on the first rows of the same batch."""
+    from oracle import gr_oracle as G
+    t0 = time.perf_counter(); rows = 0
+    while rows < wl.B and time.perf_counter() - t0 < budget_s:
+        sol = G.solve_row(wl.p[rows], wl.q[rows], wl.n, wl.k, tol=tol)
+        G.verify_row(sol, wl.p[rows], wl.drafts[rows], wl.uniforms[rows])
+        rows += 1
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "solves/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {rows} rows of the same batch, {dt:.1f} s, single thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--tol", type=float, default=1e-4, help="the paper's error threshold tau")
+    ap.add_argument("--workload", default="large", choices=["large", "llm", "small"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; rows shard across GPUs without exchange "
+                 "(see DESIGN.md) and no multi-GPU figure is produced.  Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2511_15898_amd import binding as gr, workloads as W
+
+    wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small}[args.workload]()
+    dev = torch.device("cuda:0")
+    p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
+    d = torch.from_numpy(wl.drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)
+    acc = torch.empty(wl.B, dtype=torch.float32, device=dev); st = torch.empty(wl.B, dtype=torch.int32, device=dev)
+    tok = torch.empty(wl.B, dtype=torch.int32, device=dev); ok = torch.empty(wl.B, dtype=torch.uint8, device=dev)
+    h = gr.gr_create(wl.B, wl.V, flags=0 if args.no_events else gr.GR_FLAG_PROFILE)
+
+    def step():
+        gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
+        gr.gr_verify(h, d, u, tok, ok)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_events:
+        gr.gr_profile_read(h)                      # drop the warm-up events
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = None if args.no_events else gr.gr_profile_read(h)
+    exp = gr.gr_policy_export(h, wl.B, dev)
+    torch.cuda.synchronize()
+    status = st.cpu().numpy(); iters = exp["iterations"].cpu().numpy()
+    gr.gr_destroy(h)
+
+    ms_per_step = dt / args.steps * 1e3
+    algo_bytes = 8.0 * wl.V * wl.B                 # one read of the p row and of the q row per solve
+    roofline = None
+    if prof and prof["steps"]:
+        kernels = {"select_kernel": prof["select_ms"], "solve_kernel": prof["solve_ms"], "verify_kernel": prof["verify_ms"]}
+        dom = max(kernels, key=kernels.get)
+        if dom == "select_kernel":
+            achieved = algo_bytes / (kernels[dom] * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+        else:
+            roofline = {"bound": "alu", "kernel": dom, "achieved": None, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": None, "traffic": None}
+        roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
+        roofline["events_steps"] = prof["steps"]
+        roofline["select_hbm_frac"] = algo_bytes / (kernels["select_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        roofline["step_hbm_frac"] = algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+    out = {
+        "metric": "verifier solves/sec",
+        "value": wl.B * args.steps / dt,
+        "unit": "solves/s",
+        "us_per_solve": dt / (wl.B * args.steps) * 1e6,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol},
+        "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],
+        "solver_evaluations_mean": float(iters.mean()), "solver_evaluations_max": int(iters.max()),
+        "roofline": roofline,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(wl, args.tol),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,121 @@
+/*
+ * gr_verify.h -- C ABI of the MI355X Global Resolution verifier.
+ *
+ * The library computes, for a batch of B decode positions, the optimal multi-draft
+ * verification distribution of "Global Resolution: Optimal Multi-Draft Speculative
+ * Sampling via Convex Minimization" (Thomas & Pal) for n i.i.d. drafts from one draft
+ * distribution q (optionally top-k restricted) against a target distribution p:
+ *
+ *   gr_solve   Alg. 1 lines 1-2 and both truncated convex programs:
+ *              top-k support (App. "Top-k Sampling for the Relaxed OTLP"), the order by
+ *              decreasing q/p and H*, alpha* = 1 + psi(H*) (Thm 3.1, Sec. 5.1), the outer
+ *              targets p_i (Thm 6.2, Lemma 6.3), the softmax weights that minimise
+ *              Theta_T (Thm 6.5) and Phi_T (Thm 6.4, solved per block of the outer system).
+ *   gr_verify  the transport slice pi(.|drafts) (Eq. "cases" / Eq. "approx-c") and one
+ *              inverse-CDF draw from it (App. A, multi-draft procedure, step 3).
+ *
+ * Conventions
+ *   - every pointer argument except `out`, `cfg` and host-side scalars is a DEVICE pointer
+ *     owned by the caller; the library never frees or keeps them beyond what is stated;
+ *   - all work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the calls do not synchronise with the host;
+ *   - return value 0 = success, negative = call-level error (see GR_E*), nothing was
+ *     enqueued in that case; per-row conditions never fail a call, they set status[b].
+ *   - calls on one handle must not overlap in time (the handle owns scratch and the
+ *     policy of the last gr_solve).
+ */
+#ifndef GR_VERIFY_H
+#define GR_VERIFY_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gr_handle_s* gr_handle;
+
+/* call-level errors */
+#define GR_OK            0
+#define GR_EINVAL       (-1)   /* bad shape / parameter, or beyond the handle's capacity */
+#define GR_ENOMEM       (-2)   /* device allocation failed */
+#define GR_ESTATE       (-3)   /* gr_verify / gr_policy_* before a successful gr_solve */
+#define GR_EHIP         (-4)   /* a HIP runtime call failed */
+#define GR_EUNSUPPORTED (-5)   /* support larger than GR_MAX_SUPPORT (e.g. no top-k on a large V) */
+
+/* per-row status written by gr_solve */
+#define GR_ROW_OK         0
+#define GR_ROW_TRUNC_CAP  1    /* a program needed more than max_T variables (App. "Truncated Solver Details") */
+#define GR_ROW_ITER_CAP   2    /* iteration cap reached before the gradient criterion (same appendix) */
+#define GR_ROW_BAD        3    /* NaN / negative entry, or a row sum further than 1e-3 from 1 */
+
+#define GR_MAX_SUPPORT  256    /* largest top-k support (|V_0|) the LDS-resident path holds */
+#define GR_MAX_T        128    /* largest number of variables of one convex program */
+#define GR_MAX_N         16    /* largest number of drafts */
+
+typedef struct {
+    int    max_iter;   /* iteration cap per convex program; <= 0 selects 1000 */
+    int    max_T;      /* cap on the variables of one program; <= 0 or > GR_MAX_T selects GR_MAX_T */
+    double rel_tol;    /* stop when every routed mass is within this relative distance of its
+                          target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-9 */
+    int    flags;      /* 0, or GR_FLAG_PROFILE */
+} gr_config;
+
+#define GR_FLAG_PROFILE 1      /* record HIP events around every kernel launch (see gr_profile_read) */
+
+/* Create a handle able to serve up to max_B rows of up to max_V tokens.  cfg may be NULL. */
+int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* cfg);
+int gr_destroy(gr_handle h);
+
+/*
+ * p, q        [B, V] float32 row-major, each row a distribution (q before top-k).
+ * n           number of i.i.d. drafts per row, 1..GR_MAX_N.
+ * k           top-k applied to q (ties: lower token id); k <= 0 or k >= V means none.
+ *             The support (tokens with q > 0 after top-k) must not exceed GR_MAX_SUPPORT,
+ *             otherwise GR_EUNSUPPORTED.
+ * tol         the paper's error threshold tau (Alg. 1), >= 0: truncation sets are the fewest
+ *             tokens by decreasing q with gamma_T <= tol (inner) / epsilon_T <= tol (outer).
+ * accept_prob [B] float32 out: alpha* (Thm 3.1).       status [B] int32 out: GR_ROW_*.
+ * The per-row policy stays inside the handle until the next gr_solve.
+ */
+int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float tol,
+             int B, int V, float* accept_prob, int* status, void* hip_stream);
+
+/*
+ * drafts   [B, n] int32 token ids drawn from the top-k renormalised q rows.
+ * uniforms [B] float32 in [0, 1): one uniform per row.
+ * token    [B] int32 out: x0 ~ pi(.|drafts); inverse-CDF entry order = distinct drafts in
+ *          order of first appearance, then all other tokens by ascending id.
+ * accepted [B] uint8 out: 1 iff token is one of the row's drafts.
+ * Rows whose status is not GR_ROW_OK draw from p itself (the valid fallback transport of
+ * App. "Multi-Step Experiments").  A draft outside the support gives token -1, accepted 0.
+ * p must be the array passed to the last gr_solve and still hold the same values.
+ */
+int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
+              int* token, unsigned char* accepted, void* hip_stream);
+
+/* Test / inspection entry points --------------------------------------------------- */
+
+/* Dense slice: pi [B, V] float32 out = pi(.|drafts);  accept_given_drafts [B] float32 out =
+ * sum of pi over the row's distinct drafts. */
+int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_given_drafts,
+                    void* hip_stream);
+
+/* Per-row policy object, each array [B, GR_MAX_SUPPORT] (entries beyond support[b] are
+ * unspecified): order = token ids by decreasing q/p; block = 0 for H*, b >= 1 for the
+ * b-th outer block; weight = e^{alpha_i} (float64); rho = p(i) - p_i (float64).
+ * support, h_size, iterations: [B] int32.  Any pointer may be NULL. */
+int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
+                     int* support, int* h_size, int* iterations, void* hip_stream);
+
+/* Measurement hook (handles created with GR_FLAG_PROFILE): average duration in milliseconds of
+ * the streaming selection kernel, the per-row solve kernel (both launched by gr_solve) and the
+ * verification kernel, over the gr_solve + gr_verify pairs issued since the last read (at most
+ * 512 are kept), from HIP events recorded on the caller's stream.  Waits for the last of them.
+ * All four outputs are HOST pointers. */
+int gr_profile_read(gr_handle h, double* select_ms, double* solve_ms, double* verify_ms, int* steps);
+
+const char* gr_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GR_VERIFY_H */

@@ -245,6 +245,41 @@ def routed(n, ctx, slack, q, w):
 
 
 # ------------------------------------------------------------------------ convex solve
+def newton_polish(n, ctx, slack, q, target, slack_target, alpha, rtol, max_iter, evaluator):
+    """Damped Newton on  routed(alpha) = target  with a finite-difference Jacobian (the Hessian
+    of Theta_T / Phi_T).  Without slack the system is singular along the common shift, so the
+    last weight is pinned.  Used when the fixed-point iteration is too slow (a token whose
+    target nearly exhausts the tuples that contain it).  Returns (alpha, evaluations, defect)."""
+    m = alpha.shape[0]
+    free = m if slack else m - 1
+    evals = 0
+
+    def defect(a):
+        R, R0 = evaluator(n, ctx, slack, q, np.exp(a))
+        f = np.log(target / R) - (math.log(slack_target / R0) if slack else math.log(target.sum() / R.sum()))
+        return R, float(np.max(np.abs(f)))
+
+    R, err = defect(alpha); evals += 1
+    while err > rtol and evals < max_iter:
+        J = np.empty((m, free))
+        for k in range(free):
+            a2 = alpha.copy(); a2[k] += 1e-6
+            J[:, k] = (evaluator(n, ctx, slack, q, np.exp(a2))[0] - R) / 1e-6
+        evals += free
+        scale = 1.0 if slack else R.sum() / target.sum()
+        step = np.linalg.solve(J[:free, :], (target * scale - R)[:free])
+        step = step * min(1.0, 2.0 / max(1e-300, float(np.max(np.abs(step)))))
+        lam = 1.0
+        while True:
+            a2 = alpha.copy(); a2[:free] += lam * step
+            R2, err2 = defect(a2); evals += 1
+            if err2 < err or lam < 1e-4:
+                break
+            lam *= 0.5
+        alpha, R, err = a2, R2, err2
+    return alpha, evals, err
+
+
 def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_iter=4000, evaluator=routed):
     """Minimise Theta_T (slack 1, Thm 6.5) or Phi_T (slack 0, Thm 6.4) over the log
     weights alpha = log w: the gradient is routed(w) - target, and the minimiser is the
@@ -254,28 +289,38 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
     (alternating minimisation, monotone).  With slack, the slack term is treated as the
     extra vertex a_0 of Lemma H.1 (weight pinned to 1, target = the system's slack
     mass) and updated with the rest, then the pin is restored.  Anderson mixing of
-    depth 8 accelerates.  Returns (w, iterations, max relative defect)."""
+    depth 8 accelerates; if a mixed step ever raises the defect a hundredfold the
+    iteration returns to its best point and takes plain steps for a while; after 400
+    evaluations a damped Newton iteration takes over from the best point.
+    Returns (w, evaluations, max relative defect)."""
     q = np.asarray(q, np.float64); target = np.asarray(target, np.float64)
     alpha = np.log(np.asarray(w0, np.float64))
     hist_a, hist_f = [], []
     err = np.inf
-    for it in range(1, max_iter + 1):
+    best_err, best_alpha, best_f, plain = np.inf, alpha, None, 0
+    for it in range(1, min(max_iter, 400) + 1):
         if slack == 0:
             alpha = alpha - alpha.max()
         R, R0 = evaluator(n, ctx, slack, q, np.exp(alpha))
         f = np.log(target / R)
         if slack:
             f = f - math.log(slack_target / R0)
-        prev, err = err, float(np.max(np.abs(f)))
+        err = float(np.max(np.abs(f)))
         if err <= rtol:
             return np.exp(alpha), it, err
-        if not np.isfinite(err):
-            return np.exp(alpha), it, np.inf
+        if not np.isfinite(err) or err > 100.0 * best_err:
+            # the mixed step went astray: back to the best point, plain (monotone) steps for a while
+            alpha, f, err = best_alpha.copy(), best_f.copy(), best_err
+            hist_a, hist_f, plain = [], [], 20
+        elif err < best_err:
+            best_err, best_alpha, best_f = err, alpha.copy(), f.copy()
         hist_a.append(alpha.copy()); hist_f.append(f.copy())
         if len(hist_a) > 9:
             hist_a.pop(0); hist_f.pop(0)
         step = f
-        if len(hist_a) > 1:
+        if plain > 0:
+            plain -= 1
+        elif len(hist_a) > 1:
             dF = np.stack([hist_f[-1] - x for x in hist_f[:-1]], axis=1)
             dA = np.stack([hist_a[-1] - x for x in hist_a[:-1]], axis=1)
             gam, *_ = np.linalg.lstsq(dF, f, rcond=1e-10)
@@ -285,6 +330,10 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
             else:
                 hist_a, hist_f = hist_a[-1:], hist_f[-1:]
         alpha = alpha + step
+    if max_iter > 400:
+        alpha, evals, err = newton_polish(n, ctx, slack, q, target, slack_target, best_alpha.copy(), rtol,
+                                          max_iter - 400, evaluator)
+        return np.exp(alpha), 400 + evals, err
     return np.exp(alpha), max_iter, err
 
 

@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libgr_verify.so: the same entry points as include/gr_verify.h.
+
+Argument marshalling only -- every step of the verifier runs in the HIP kernels.  Tensors are
+torch CUDA tensors (PyTorch is used for device memory and streams, nothing else).  There is no
+CPU fallback: if the library is missing, loading fails loudly."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+GR_MAX_SUPPORT = 256
+GR_MAX_T = 128
+GR_MAX_N = 16
+GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
+GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_verify", "gr_policy_slice", "gr_policy_export",
+           "gr_profile_read", "gr_strerror")
+GR_FLAG_PROFILE = 1
+
+
+class GrConfig(ctypes.Structure):
+    _fields_ = [("max_iter", ctypes.c_int), ("max_T", ctypes.c_int), ("rel_tol", ctypes.c_double),
+                ("flags", ctypes.c_int)]
+
+
+class GrError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library(path: str | None = None) -> ctypes.CDLL:
+    """Load the built library (no build is attempted here)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: run `python __graft_entry__.py` (or paper_2511_15898_amd/build.py) first")
+    lib = ctypes.CDLL(path)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.gr_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.POINTER(GrConfig)]
+    lib.gr_destroy.argtypes = [vp]
+    lib.gr_solve.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
+    lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
+    lib.gr_policy_export.argtypes = [vp] * 9
+    lib.gr_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    lib.gr_strerror.argtypes = [ci]
+    lib.gr_strerror.restype = ctypes.c_char_p
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().gr_strerror(int(code)).decode()
+
+
+def _ptr(t: torch.Tensor | None, dtype: torch.dtype, what: str) -> int | None:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{what}: need a contiguous CUDA tensor of {dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+
+
+def gr_create(max_B: int, max_V: int, max_iter: int = 0, max_T: int = 0, rel_tol: float = 0.0, flags: int = 0) -> int:
+    cfg = GrConfig(max_iter, max_T, rel_tol, flags)
+    h = ctypes.c_void_p()
+    rc = load_library().gr_create(ctypes.byref(h), max_B, max_V, ctypes.byref(cfg))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_create")
+    return h.value
+
+
+def gr_destroy(handle: int) -> None:
+    rc = load_library().gr_destroy(handle)
+    if rc != GR_OK:
+        raise GrError(rc, "gr_destroy")
+
+
+def gr_solve(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: int, tol: float,
+             accept_prob: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None):
+    """p, q: [B, V] float32 CUDA tensors.  Returns (accept_prob [B] float32, status [B] int32)."""
+    if p.dim() != 2 or p.shape != q.shape:
+        raise TypeError("gr_solve: p and q must both be [B, V]")
+    B, V = p.shape
+    if accept_prob is None:
+        accept_prob = torch.empty(B, dtype=torch.float32, device=p.device)
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=p.device)
+    rc = load_library().gr_solve(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), n, k, tol, B, V,
+                                 _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
+                                 _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_solve")
+    return accept_prob, status
+
+
+def gr_verify(handle: int, drafts: torch.Tensor, uniforms: torch.Tensor, token: torch.Tensor | None = None,
+              accepted: torch.Tensor | None = None, stream=None):
+    """drafts [B, n] int32, uniforms [B] float32.  Returns (token [B] int32, accepted [B] uint8)."""
+    B = drafts.shape[0]
+    if token is None:
+        token = torch.empty(B, dtype=torch.int32, device=drafts.device)
+    if accepted is None:
+        accepted = torch.empty(B, dtype=torch.uint8, device=drafts.device)
+    rc = load_library().gr_verify(handle, _ptr(drafts, torch.int32, "drafts"), _ptr(uniforms, torch.float32, "uniforms"),
+                                  _ptr(token, torch.int32, "token"), _ptr(accepted, torch.uint8, "accepted"), _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_verify")
+    return token, accepted
+
+
+def gr_policy_slice(handle: int, drafts: torch.Tensor, V: int, stream=None):
+    """Dense pi(.|drafts) [B, V] float32 and the conditional acceptance [B] float32."""
+    B = drafts.shape[0]
+    pi = torch.empty((B, V), dtype=torch.float32, device=drafts.device)
+    acc = torch.empty(B, dtype=torch.float32, device=drafts.device)
+    rc = load_library().gr_policy_slice(handle, _ptr(drafts, torch.int32, "drafts"), pi.data_ptr(), acc.data_ptr(),
+                                        _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_policy_slice")
+    return pi, acc
+
+
+def gr_profile_read(handle: int) -> dict:
+    """Average per-kernel milliseconds since the last read (handle created with GR_FLAG_PROFILE)."""
+    a, b, c, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    rc = load_library().gr_profile_read(handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(n))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_profile_read")
+    return {"select_ms": a.value, "solve_ms": b.value, "verify_ms": c.value, "steps": n.value}
+
+
+def gr_policy_export(handle: int, B: int, device, stream=None) -> dict:
+    """The per-row policy object of the last solve, as tensors (see gr_verify.h)."""
+    out = {
+        "order": torch.empty((B, GR_MAX_SUPPORT), dtype=torch.int32, device=device),
+        "block": torch.empty((B, GR_MAX_SUPPORT), dtype=torch.int32, device=device),
+        "weight": torch.empty((B, GR_MAX_SUPPORT), dtype=torch.float64, device=device),
+        "rho": torch.empty((B, GR_MAX_SUPPORT), dtype=torch.float64, device=device),
+        "support": torch.empty(B, dtype=torch.int32, device=device),
+        "h_size": torch.empty(B, dtype=torch.int32, device=device),
+        "iterations": torch.empty(B, dtype=torch.int32, device=device),
+    }
+    rc = load_library().gr_policy_export(handle, *(out[k].data_ptr() for k in
+                                                   ("order", "block", "weight", "rho", "support", "h_size", "iterations")),
+                                         _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_policy_export")
+    return out

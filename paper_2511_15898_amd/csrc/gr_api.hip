@@ -1,0 +1,219 @@
+// C ABI of the Global Resolution verifier: handle, argument checks, kernel launches.
+#include <new>
+
+#include "gr_internal.h"
+
+using namespace gr;
+
+namespace { constexpr int kProfSlots = 512; }
+
+struct gr_handle_s {
+    int max_B = 0, max_V = 0;
+    int max_iter = 1000, max_T = GR_MAX_T;
+    double rel_tol = 1e-9;
+    int device = 0;
+    // scratch of the select kernel
+    unsigned long long* cand = nullptr; int* cand_count = nullptr;
+    double* part_psum = nullptr; double* part_qsum = nullptr; int* part_bad = nullptr;
+    // policy object of the last solve
+    int* order = nullptr; int* block = nullptr; double* weight = nullptr; double* rho = nullptr; double* pnorm = nullptr;
+    RowInfo* info = nullptr;
+    // optional per-kernel timing (gr_config.flags bit 0): events around every launch, read back
+    // by gr_profile_read
+    bool profile = false;
+    hipEvent_t ev[kProfSlots][5] = {};
+    int prof_count = 0;
+    // last solve
+    bool solved = false;
+    const float* p = nullptr;
+    int B = 0, V = 0, n = 0;
+};
+
+namespace {
+
+void mark(gr_handle h, int which, hipStream_t stream) {
+    if (h->profile && h->prof_count < kProfSlots) (void)hipEventRecord(h->ev[h->prof_count][which], stream);
+}
+
+template <typename T>
+bool dev_alloc(T** ptr, size_t count) {
+    return hipMalloc(reinterpret_cast<void**>(ptr), count * sizeof(T)) == hipSuccess;
+}
+
+void free_all(gr_handle h) {
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->order, h->block,
+                    h->weight, h->rho, h->pnorm, h->info};
+    for (void* ptr : ptrs) (void)hipFree(ptr);
+    if (h->profile)
+        for (auto& slot : h->ev)
+            for (auto& e : slot)
+                if (e) (void)hipEventDestroy(e);
+}
+
+// Number of workgroups that share a row in the select kernel: enough groups to keep every CU's
+// memory pipeline busy (about 8 per CU), slices no shorter than 4 tiles.
+int choose_splits(int B, int V) {
+    int s = 2048 / (B > 0 ? B : 1);
+    if (s < 1) s = 1;
+    if (s > kMaxSplits) s = kMaxSplits;
+    while (s > 1 && V / s < 4 * kSelTile) --s;
+    return s;
+}
+
+}  // namespace
+
+extern "C" int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* cfg) {
+    if (!out || max_B <= 0 || max_V <= 0) return GR_EINVAL;
+    if (cfg && (cfg->flags & ~GR_FLAG_PROFILE) != 0) return GR_EINVAL;
+    gr_handle h = new (std::nothrow) gr_handle_s();
+    if (!h) return GR_ENOMEM;
+    h->max_B = max_B; h->max_V = max_V;
+    if (cfg) {
+        if (cfg->max_iter > 0) h->max_iter = cfg->max_iter;
+        if (cfg->max_T > 0 && cfg->max_T <= GR_MAX_T) h->max_T = cfg->max_T;
+        if (cfg->rel_tol > 0.0) h->rel_tol = cfg->rel_tol;
+    }
+    if (hipGetDevice(&h->device) != hipSuccess) { delete h; return GR_EHIP; }
+    if (solve_kernel_setup() != hipSuccess) { delete h; return GR_EHIP; }
+    const size_t rows = static_cast<size_t>(max_B);
+    bool ok = dev_alloc(&h->cand, rows * kMaxSplits * kMaxSupport) && dev_alloc(&h->cand_count, rows * kMaxSplits) &&
+              dev_alloc(&h->part_psum, rows * kMaxSplits) && dev_alloc(&h->part_qsum, rows * kMaxSplits) &&
+              dev_alloc(&h->part_bad, rows * kMaxSplits) && dev_alloc(&h->order, rows * kMaxSupport) &&
+              dev_alloc(&h->block, rows * kMaxSupport) && dev_alloc(&h->weight, rows * kMaxSupport) &&
+              dev_alloc(&h->rho, rows * kMaxSupport) && dev_alloc(&h->pnorm, rows * kMaxSupport) &&
+              dev_alloc(&h->info, rows);
+    if (!ok) { free_all(h); delete h; (void)hipGetLastError(); return GR_ENOMEM; }
+    if (cfg && (cfg->flags & GR_FLAG_PROFILE)) {
+        h->profile = true;
+        for (auto& slot : h->ev)
+            for (auto& e : slot)
+                if (hipEventCreate(&e) != hipSuccess) { free_all(h); delete h; return GR_EHIP; }
+    }
+    *out = h;
+    return GR_OK;
+}
+
+extern "C" int gr_destroy(gr_handle h) {
+    if (!h) return GR_EINVAL;
+    free_all(h);
+    delete h;
+    return GR_OK;
+}
+
+extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float tol,
+                        int B, int V, float* accept_prob, int* status, void* hip_stream) {
+    if (!h || !p || !q || !accept_prob || !status) return GR_EINVAL;
+    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
+    if (n < 1 || n > GR_MAX_N) return GR_EINVAL;
+    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
+    const int k_eff = (k <= 0 || k >= V) ? V : k;
+    if (k_eff > kMaxSupport) return GR_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int splits = choose_splits(B, V);
+    int slice_len = (V + splits - 1) / splits;
+    slice_len = (slice_len + 3) & ~3;
+    h->solved = false;
+    mark(h, 0, stream);
+    launch_select(p, q, B, V, k_eff, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
+                  h->part_bad, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    mark(h, 1, stream);
+    SolveParams sp;
+    sp.p = p; sp.q = q; sp.B = B; sp.V = V; sp.n = n; sp.k = k_eff; sp.splits = splits;
+    sp.tau = static_cast<double>(tol); sp.rel_tol = h->rel_tol; sp.max_iter = h->max_iter; sp.max_T = h->max_T;
+    sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
+    sp.part_bad = h->part_bad;
+    sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
+    sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status;
+    if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
+    mark(h, 2, stream);
+    h->solved = true; h->p = p; h->B = B; h->V = V; h->n = n;
+    return GR_OK;
+}
+
+extern "C" int gr_verify(gr_handle h, const int* drafts, const float* uniforms, int* token,
+                         unsigned char* accepted, void* hip_stream) {
+    if (!h || !drafts || !uniforms || !token || !accepted) return GR_EINVAL;
+    if (!h->solved) return GR_ESTATE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    mark(h, 3, stream);
+    launch_verify(h->p, h->B, h->V, h->n, h->order, h->block, h->weight, h->rho, h->info, drafts, uniforms,
+                  token, accepted, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    mark(h, 4, stream);
+    if (h->profile && h->prof_count < kProfSlots) ++h->prof_count;
+    return GR_OK;
+}
+
+extern "C" int gr_profile_read(gr_handle h, double* select_ms, double* solve_ms, double* verify_ms, int* steps) {
+    if (!h || !select_ms || !solve_ms || !verify_ms || !steps) return GR_EINVAL;
+    if (!h->profile) return GR_ESTATE;
+    double acc[3] = {0.0, 0.0, 0.0};
+    for (int s = 0; s < h->prof_count; ++s) {
+        if (hipEventSynchronize(h->ev[s][4]) != hipSuccess) return GR_EHIP;
+        const int pairs[3][2] = {{0, 1}, {1, 2}, {3, 4}};
+        for (int j = 0; j < 3; ++j) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, h->ev[s][pairs[j][0]], h->ev[s][pairs[j][1]]) != hipSuccess) return GR_EHIP;
+            acc[j] += ms;
+        }
+    }
+    const int cnt = h->prof_count;
+    *steps = cnt;
+    *select_ms = cnt ? acc[0] / cnt : 0.0; *solve_ms = cnt ? acc[1] / cnt : 0.0; *verify_ms = cnt ? acc[2] / cnt : 0.0;
+    h->prof_count = 0;
+    return GR_OK;
+}
+
+extern "C" int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_given_drafts,
+                               void* hip_stream) {
+    if (!h || !drafts || !pi || !accept_given_drafts) return GR_EINVAL;
+    if (!h->solved) return GR_ESTATE;
+    launch_slice(h->p, h->B, h->V, h->n, h->order, h->block, h->weight, h->rho, h->info, drafts, pi,
+                 accept_given_drafts, static_cast<hipStream_t>(hip_stream));
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_EHIP;
+}
+
+namespace {
+
+__global__ void export_kernel(const RowInfo* info, int B, int* support, int* h_size, int* iterations) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    if (support) support[b] = info[b].support;
+    if (h_size) h_size[b] = info[b].h;
+    if (iterations) iterations[b] = info[b].iterations;
+}
+
+}  // namespace
+
+extern "C" int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
+                                int* support, int* h_size, int* iterations, void* hip_stream) {
+    if (!h) return GR_EINVAL;
+    if (!h->solved) return GR_ESTATE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t cnt = static_cast<size_t>(h->B) * kMaxSupport;
+    hipError_t e = hipSuccess;
+    if (order && e == hipSuccess) e = hipMemcpyAsync(order, h->order, cnt * sizeof(int), hipMemcpyDeviceToDevice, stream);
+    if (block && e == hipSuccess) e = hipMemcpyAsync(block, h->block, cnt * sizeof(int), hipMemcpyDeviceToDevice, stream);
+    if (weight && e == hipSuccess) e = hipMemcpyAsync(weight, h->weight, cnt * sizeof(double), hipMemcpyDeviceToDevice, stream);
+    if (rho && e == hipSuccess) e = hipMemcpyAsync(rho, h->rho, cnt * sizeof(double), hipMemcpyDeviceToDevice, stream);
+    if (e != hipSuccess) return GR_EHIP;
+    if (support || h_size || iterations) {
+        hipLaunchKernelGGL(export_kernel, dim3((h->B + 255) / 256), dim3(256), 0, stream, h->info, h->B, support,
+                           h_size, iterations);
+        if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    }
+    return GR_OK;
+}
+
+extern "C" const char* gr_strerror(int code) {
+    switch (code) {
+        case GR_OK: return "ok";
+        case GR_EINVAL: return "invalid argument or beyond the handle's capacity";
+        case GR_ENOMEM: return "device allocation failed";
+        case GR_ESTATE: return "no solved policy in this handle";
+        case GR_EHIP: return "HIP runtime error";
+        case GR_EUNSUPPORTED: return "support larger than GR_MAX_SUPPORT";
+        default: return "unknown error";
+    }
+}

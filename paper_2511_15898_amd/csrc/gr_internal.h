@@ -1,0 +1,175 @@
+// Internal declarations shared by the kernels and the C ABI of the Global Resolution verifier.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gr_verify.h"
+
+namespace gr {
+
+constexpr int kThreads = 256;             // every kernel here runs 256-thread workgroups (4 wave64)
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxSupport = GR_MAX_SUPPORT;
+constexpr int kMaxT = GR_MAX_T;
+constexpr int kSelTile = kThreads * 4;    // tokens per streaming tile (one float4 per thread)
+constexpr int kSelCap = 2048;             // candidate keys held in LDS (>= kMaxSupport + kSelTile)
+constexpr int kMaxSplits = 8;             // workgroups that share one row in the select kernel
+constexpr int kHist = 9;                  // Anderson history length (current + 8)
+
+// Per-row result of the solve kernel (one per row, in HBM).
+struct RowInfo {
+    int support;        // k' = |V_0|
+    int h;              // |H*|
+    int status;         // GR_ROW_*
+    int iterations;     // fixed-point evaluations summed over the row's programs
+    double alpha_star;  // 1 + psi(H*)
+    double res_total;   // sum of residuals p(i) - p_i over tokens outside H* (= 1 - alpha*)
+    double p_total;     // float64 row sum of p
+    double q_total;     // float64 row sum of q (before top-k)
+};
+
+struct SolveParams {
+    const float* p; const float* q;
+    int B, V, n, k, splits;
+    double tau;         // the paper's error threshold, float32 value widened
+    double rel_tol;
+    int max_iter, max_T;
+    // select kernel output
+    const unsigned long long* cand;   // [B, splits, kMaxSupport] keys
+    const int* cand_count;            // [B, splits]
+    const double* part_psum;          // [B, splits]
+    const double* part_qsum;          // [B, splits]
+    const int* part_bad;              // [B, splits]
+    // policy object
+    int* order; int* block; double* weight; double* rho; double* pnorm;   // [B, kMaxSupport]
+    RowInfo* info;                    // [B]
+    float* accept_prob; int* status;  // caller's outputs [B]
+};
+
+void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
+                   unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
+                   hipStream_t stream);
+hipError_t launch_solve(const SolveParams& sp, hipStream_t stream);
+void launch_verify(const float* p, int B, int V, int n, const int* order, const int* block,
+                   const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+                   const float* uniforms, int* token, unsigned char* accepted, hipStream_t stream);
+void launch_slice(const float* p, int B, int V, int n, const int* order, const int* block,
+                  const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+                  float* pi, float* accept_given, hipStream_t stream);
+hipError_t solve_kernel_setup();
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ double wave_sum(double v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ double wave_min(double v) {
+    for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Workgroup reductions over kThreads threads.  `red` is an LDS array of at least kWaves
+// doubles; both barriers are inside, so `red` may be reused right after the call.
+__device__ __forceinline__ double block_sum(double v, double* red) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = red[0];
+    for (int w = 1; w < kWaves; ++w) t += red[w];
+    __syncthreads();
+    return t;
+}
+__device__ __forceinline__ double block_max(double v, double* red) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = red[0];
+    for (int w = 1; w < kWaves; ++w) t = fmax(t, red[w]);
+    __syncthreads();
+    return t;
+}
+__device__ __forceinline__ double block_min(double v, double* red) {
+    v = wave_min(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = red[0];
+    for (int w = 1; w < kWaves; ++w) t = fmin(t, red[w]);
+    __syncthreads();
+    return t;
+}
+__device__ __forceinline__ int block_sum_i(int v, double* red) {
+    int* r = reinterpret_cast<int*>(red);
+    v = wave_sum_i(v);
+    if ((threadIdx.x & 63) == 0) r[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int t = r[0];
+    for (int w = 1; w < kWaves; ++w) t += r[w];
+    __syncthreads();
+    return t;
+}
+
+// Candidate key: larger q first, ties to the lower token id.  q >= 0, so its bit pattern is
+// monotone; the low word holds ~id so that a plain 64-bit compare gives the order.
+__device__ __forceinline__ unsigned long long make_key(float q, int id) {
+    return (static_cast<unsigned long long>(__float_as_uint(q)) << 32) |
+           static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<unsigned>(id));
+}
+__device__ __forceinline__ int key_id(unsigned long long key) {
+    return static_cast<int>(0xFFFFFFFFu - static_cast<unsigned>(key & 0xFFFFFFFFull));
+}
+__device__ __forceinline__ float key_q(unsigned long long key) {
+    return __uint_as_float(static_cast<unsigned>(key >> 32));
+}
+
+// k-th largest of `count` distinct keys held in LDS (1 <= k <= count <= kSelCap), by
+// most-significant-digit radix selection, 8 bits per pass.  All kThreads threads call it.
+// hist: LDS int[256]; pick: LDS int[2].
+__device__ inline unsigned long long block_kth_largest(const unsigned long long* keys, int count, int k,
+                                                       int* hist, int* pick) {
+    const int tid = threadIdx.x;
+    unsigned long long prefix = 0;
+    int need = k;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        const unsigned long long mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
+        for (int i = tid; i < count; i += kThreads) {
+            const unsigned long long key = keys[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[static_cast<int>((key >> shift) & 255ull)], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane l owns digits 255-4l .. 252-4l (largest digits in lane 0)
+            int c[4]; int tot = 0;
+            for (int j = 0; j < 4; ++j) { c[j] = hist[255 - 4 * tid - j]; tot += c[j]; }
+            int incl = tot;
+            for (int o = 1; o < 64; o <<= 1) {
+                int up = __shfl_up(incl, o);
+                if (tid >= o) incl += up;
+            }
+            int excl = incl - tot;
+            if (excl < need && need <= incl) {
+                int above = excl;
+                for (int j = 0; j < 4; ++j) {
+                    if (need <= above + c[j]) { pick[0] = 255 - 4 * tid - j; pick[1] = need - above; break; }
+                    above += c[j];
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= static_cast<unsigned long long>(pick[0]) << shift;
+        need = pick[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+
+}  // namespace gr

@@ -1,0 +1,141 @@
+"""GPU edge cases through the C ABI: ragged shapes, degenerate rows, statuses, error codes."""
+import numpy as np
+import pytest
+
+from paper_2511_15898_amd import workloads as W
+from parity_util import compare_rows, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(p, q, n, k, seed=0):
+    rng = np.random.default_rng(seed)
+    p = np.ascontiguousarray(p, np.float32); q = np.ascontiguousarray(q, np.float32)
+    return W._finish("edge", p, q, n, k, rng)
+
+
+def _rows(seed, B, V, conc=0.3):
+    rng = np.random.default_rng(seed)
+    p = rng.dirichlet(np.full(V, conc), size=B).astype(np.float32)
+    q = rng.dirichlet(np.full(V, conc), size=B).astype(np.float32)
+    p = np.maximum(p, np.float32(1e-30)); q = np.maximum(q, np.float32(1e-30))
+    return (p / p.sum(1, keepdims=True)).astype(np.float32), (q / q.sum(1, keepdims=True)).astype(np.float32)
+
+
+@pytest.mark.parametrize("B,V,n,k", [(1, 8, 2, 0), (3, 1001, 3, 17), (5, 4099, 2, 256), (2, 255, 1, 0), (7, 20000, 5, 100)])
+def test_ragged_shapes(B, V, n, k):
+    """V not a multiple of the float4 width or of the tile, one-row batches, k at the support cap."""
+    p, q = _rows(B * 1000 + V, B, V, conc=0.05 if V > 500 else 0.3)
+    wl = _wl(p, q, n, k)
+    out = run_gpu(wl, 1e-6)
+    compare_rows(wl, out, range(B), 1e-6)
+
+
+def test_support_smaller_than_k_and_exact_zeros():
+    p, q = _rows(5, 6, 600, conc=0.05)
+    q[:, 40:] = 0.0; q = (q / q.sum(1, keepdims=True)).astype(np.float32)     # 40 positive entries, k = 64
+    p[:, :10] = 0.0; p = (p / p.sum(1, keepdims=True)).astype(np.float32)     # p = 0 where q > 0
+    wl = _wl(p, q, 3, 64)
+    out = run_gpu(wl, 1e-6)
+    assert np.all(out["support"] <= 40)
+    compare_rows(wl, out, range(6), 1e-6)
+
+
+def test_identical_distributions_accept_everything():
+    p, _ = _rows(6, 4, 300)
+    wl = _wl(p, p.copy(), 4, 0 if False else 64)
+    out = run_gpu(wl, 1e-6)
+    compare_rows(wl, out, range(4), 1e-6)
+    wl = _wl(p[:, :100] / p[:, :100].sum(1, keepdims=True), p[:, :100] / p[:, :100].sum(1, keepdims=True), 2, 0)
+    out = run_gpu(wl, 0.0)
+    assert np.all(np.abs(out["accept_prob"] - 1.0) < 1e-5)
+    assert np.all(out["accepted"] == 1)
+
+
+def test_bad_rows_get_a_status_not_an_error():
+    p, q = _rows(8, 5, 512)
+    p[1, 7] = np.nan; q[2, 9] = -0.25; p[3] *= np.float32(0.9)
+    wl = _wl(np.nan_to_num(p, nan=0.0), np.abs(q), 2, 16)        # drafts drawn from a clean copy
+    wl.p[:] = p; wl.q[:] = q
+    out = run_gpu(wl, 1e-6)
+    assert list(out["status"]) == [0, 3, 3, 3, 0]
+    assert np.isnan(out["accept_prob"][1]) and out["token"][2] == -1 and out["accepted"][3] == 0
+    compare_rows(wl, out, [0, 4], 1e-6)
+
+
+def test_status_caps_and_fallback_transport():
+    """Hitting the variable cap or the iteration cap sets the row status, and verification falls
+    back to sampling from p (App. "Multi-Step Experiments")."""
+    wl = W.small(B=16)
+    out = run_gpu(wl, 1e-6, max_T=4)
+    assert np.all(out["status"] == 1)
+    compare_rows(wl, out, range(16), 1e-6, max_T=4)
+    out = run_gpu(wl, 1e-6, max_iter=1)
+    assert np.all(out["status"] == 2)
+    compare_rows(wl, out, range(4), 1e-6, max_iter=1)
+
+
+def test_drafts_outside_the_support():
+    wl = W.small(B=4)
+    drafts = wl.drafts.copy(); drafts[1, 2] = -5; drafts[2, 0] = wl.V + 3
+    worst = int(np.argmin(wl.q[3])); drafts[3, 1] = worst          # valid id, not in the top-k support
+    out = run_gpu(wl, 1e-6, drafts=drafts)
+    assert list(out["token"][1:]) == [-1, -1, -1] and list(out["accepted"][1:]) == [0, 0, 0]
+    assert np.all(out["pi"][1:] == 0)
+    compare_rows(wl, out, [0], 1e-6)
+
+
+def test_results_are_deterministic():
+    wl = W.llm_shaped(B=48, V=8192, n=4, k=64, seed_sub=77)
+    a = run_gpu(wl, 1e-6); b = run_gpu(wl, 1e-6)
+    for key in ("accept_prob", "token", "accepted", "status", "h_size"):
+        assert np.array_equal(a[key], b[key]), key
+    kk = a["support"]
+    for r in range(wl.B):
+        assert np.array_equal(a["order"][r, :kk[r]], b["order"][r, :kk[r]])
+        assert np.array_equal(a["weight"][r, :kk[r]], b["weight"][r, :kk[r]])
+
+
+def test_call_level_errors():
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    dev = torch.device("cuda:0")
+    h = gr.gr_create(4, 1024)
+    try:
+        p = torch.full((4, 1024), 1.0 / 1024, device=dev); d = torch.zeros((4, 2), dtype=torch.int32, device=dev)
+        u = torch.zeros(4, device=dev)
+        with pytest.raises(gr.GrError) as e:
+            gr.gr_verify(h, d, u)
+        assert e.value.code == gr.GR_ESTATE
+        for bad in (dict(n=0), dict(n=17), dict(tol=-1.0), dict(tol=1.5)):
+            args = dict(n=2, k=8, tol=1e-6); args.update(bad)
+            with pytest.raises(gr.GrError) as e:
+                gr.gr_solve(h, p, p, args["n"], args["k"], args["tol"])
+            assert e.value.code == gr.GR_EINVAL
+        with pytest.raises(gr.GrError) as e:
+            gr.gr_solve(h, p, p, 2, 0, 1e-6)          # no top-k on V = 1024: support beyond the cap
+        assert e.value.code == gr.GR_EUNSUPPORTED
+        big = torch.full((8, 1024), 1.0 / 1024, device=dev)
+        with pytest.raises(gr.GrError) as e:
+            gr.gr_solve(h, big, big, 2, 8, 1e-6)      # beyond the handle's max_B
+        assert e.value.code == gr.GR_EINVAL
+        with pytest.raises(TypeError):
+            gr.gr_solve(h, p.double(), p, 2, 8, 1e-6)
+    finally:
+        gr.gr_destroy(h)
+
+
+def test_full_vocab_support_is_refused():
+    """Config 5's 'top-k = full V' cells need a support of 128256 tokens; this build keeps the
+    support in LDS (at most 256 tokens) and says so instead of answering approximately."""
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    dev = torch.device("cuda:0")
+    h = gr.gr_create(2, 128256)
+    try:
+        p = torch.full((2, 128256), 1.0 / 128256, device=dev)
+        with pytest.raises(gr.GrError) as e:
+            gr.gr_solve(h, p, p, 4, 128256, 1e-6)
+        assert e.value.code == gr.GR_EUNSUPPORTED
+    finally:
+        gr.gr_destroy(h)
