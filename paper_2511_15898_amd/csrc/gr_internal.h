@@ -14,7 +14,7 @@ constexpr int kMaxT = GR_MAX_T;
 constexpr int kSelTile = kThreads * 4;    // tokens per streaming tile (one float4 per thread)
 constexpr int kSelCap = 2048;             // candidate keys held in LDS (>= kMaxSupport + kSelTile)
 constexpr int kMaxSplits = 8;             // workgroups that share one row in the select kernel
-constexpr int kHist = 9;                  // Anderson history length (current + 8)
+constexpr int kHist = 6;                  // Anderson history length (current + 5)
 
 // Per-row result of the solve kernel (one per row, in HBM).
 struct RowInfo {
@@ -76,42 +76,45 @@ __device__ __forceinline__ int wave_sum_i(int v) {
     return v;
 }
 
-// Workgroup reductions over kThreads threads.  `red` is an LDS array of at least kWaves
-// doubles; both barriers are inside, so `red` may be reused right after the call.
+// Workgroup reductions over NW waves.  `red` is an LDS array of at least NW doubles; both barriers are inside, so `red` may be reused right after the call.
+template <int NW = kWaves>
 __device__ __forceinline__ double block_sum(double v, double* red) {
     v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = red[0];
-    for (int w = 1; w < kWaves; ++w) t += red[w];
+    for (int w = 1; w < NW; ++w) t += red[w];
     __syncthreads();
     return t;
 }
+template <int NW = kWaves>
 __device__ __forceinline__ double block_max(double v, double* red) {
     v = wave_max(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = red[0];
-    for (int w = 1; w < kWaves; ++w) t = fmax(t, red[w]);
+    for (int w = 1; w < NW; ++w) t = fmax(t, red[w]);
     __syncthreads();
     return t;
 }
+template <int NW = kWaves>
 __device__ __forceinline__ double block_min(double v, double* red) {
     v = wave_min(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = red[0];
-    for (int w = 1; w < kWaves; ++w) t = fmin(t, red[w]);
+    for (int w = 1; w < NW; ++w) t = fmin(t, red[w]);
     __syncthreads();
     return t;
 }
+template <int NW = kWaves>
 __device__ __forceinline__ int block_sum_i(int v, double* red) {
     int* r = reinterpret_cast<int*>(red);
     v = wave_sum_i(v);
     if ((threadIdx.x & 63) == 0) r[threadIdx.x >> 6] = v;
     __syncthreads();
     int t = r[0];
-    for (int w = 1; w < kWaves; ++w) t += r[w];
+    for (int w = 1; w < NW; ++w) t += r[w];
     __syncthreads();
     return t;
 }
@@ -130,18 +133,19 @@ __device__ __forceinline__ float key_q(unsigned long long key) {
 }
 
 // k-th largest of `count` distinct keys held in LDS (1 <= k <= count <= kSelCap), by
-// most-significant-digit radix selection, 8 bits per pass.  All kThreads threads call it.
+// most-significant-digit radix selection, 8 bits per pass.  All NT threads of the workgroup call it.
 // hist: LDS int[256]; pick: LDS int[2].
+template <int NT = kThreads>
 __device__ inline unsigned long long block_kth_largest(const unsigned long long* keys, int count, int k,
                                                        int* hist, int* pick) {
     const int tid = threadIdx.x;
     unsigned long long prefix = 0;
     int need = k;
     for (int shift = 56; shift >= 0; shift -= 8) {
-        hist[tid] = 0;
+        if (tid < 256) hist[tid] = 0;
         __syncthreads();
         const unsigned long long mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
-        for (int i = tid; i < count; i += kThreads) {
+        for (int i = tid; i < count; i += NT) {
             const unsigned long long key = keys[i];
             if ((key & mask) == prefix) atomicAdd(&hist[static_cast<int>((key >> shift) & 255ull)], 1);
         }

@@ -20,11 +20,19 @@ namespace gr {
 namespace {
 
 constexpr int KS = kMaxSupport;
+constexpr int kST = 256;             // threads of the solve workgroup (one wave per SIMD: each may use all 512 registers)
+constexpr int kSW = kST / 64;
 constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation error ~1e-8 relative)
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
+constexpr int kNewtonMax = 32;       // largest program the Newton fallback takes
+constexpr int kMixBudget = 60;       // evaluations given to the mixed fixed-point iteration before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
+
+#ifdef GR_DEBUG
+__device__ long long g_dbg[8];
+#endif
 
 struct Lds {
     // support, in ratio order
@@ -34,13 +42,20 @@ struct Lds {
     double P[KS + 1]; double S[KS + 1]; double Q[KS + 1]; double F[KS + 2]; double G0[KS + 2]; double G1[KS + 2];
     // one convex program
     double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aw[kMaxT]; double aR[kMaxT]; double af[kMaxT];
+    double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
+    double etab[kMaxT * 17];        // q^a / a!, a = 0..16
+    int adeg[kMaxT];                // degree at which the token's exponential series may be cut
+    // Newton fallback (programs of at most kNewtonMax variables)
+    double J[kNewtonMax * (kNewtonMax + 1)]; double nR[kNewtonMax]; double nstep[kNewtonMax]; double nsave[kNewtonMax];
     double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT];
-    double gram[kWaves][kGram]; double gamma[kCols];
-    double red[kWaves]; double R0acc; int ok; int pick[2]; int count; int hist[256];
+    double gram[kGram]; double gamma[kCols];
+    // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
+    double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
+    double red[kSW]; double R0acc; int ok; int pick[2]; int count; int hist[256];
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
         unsigned long long keys[kSelCap];
-        double part[kWaves * 17 * 64];
+        double part[kSW * 17 * 64];
     } u;
 };
 
@@ -51,28 +66,223 @@ __device__ __forceinline__ double ipow(double x, int n) {
     return r;
 }
 
-// a^n - (a-d)^n without cancellation
+// a^n - (a-d)^n without cancellation: d * sum_{i<n} a^(n-1-i) b^i with b = a - d, by the
+// recurrence s_i = a s_{i-1} + b^i (all terms nonnegative).
 __device__ __forceinline__ double pow_diff(double a, double d, int n) {
     const double b = a - d;
-    double ap[GR_MAX_N], bp[GR_MAX_N];
-    ap[0] = 1.0; bp[0] = 1.0;
-    for (int i = 1; i < n; ++i) { ap[i] = ap[i - 1] * a; bp[i] = bp[i - 1] * b; }
-    double s = 0.0;
-    for (int i = 0; i < n; ++i) s = s + ap[n - 1 - i] * bp[i];
+    double s = 1.0, bp = 1.0;
+    for (int i = 1; i < n; ++i) { bp = bp * b; s = s * a + bp; }
     return d * s;
+}
+
+// Inclusive prefix sums of x[0..count) in index order, added one after the other exactly as a
+// sequential loop would (so the rounding does not depend on the machine), but held in the
+// registers of one wave: lane j of round r owns element 64 r + j, the running sum travels through
+// v_readlane.  Called by one whole wave; out[0] = start, out[i + 1] = start + x[0] + ... + x[i].
+__device__ __forceinline__ void wave_sequential_scan(const double* x, double* out, int count, double start) {
+    const int lane = threadIdx.x & 63;
+    double acc = start;
+    if (lane == 0) out[0] = start;
+    for (int base = 0; base < count; base += 64) {
+        const double mine = (base + lane < count) ? x[base + lane] : 0.0;
+        double res = 0.0;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            acc = acc + __shfl(mine, j);
+            if (lane == j) res = acc;
+        }
+        if (base + lane < count) out[base + lane + 1] = res;
+    }
 }
 #pragma clang fp contract(fast)
 
+// e^{-y} for y >= 0: Cody-Waite reduction by ln 2 and a degree-12 Taylor polynomial on
+// |r| <= ln(2)/2 (relative error below 1e-15; underflows to 0 beyond y = 708).
+__device__ __forceinline__ double exp_neg(double y) {
+    if (y > 708.0) return 0.0;
+    const double k = rint(y * 1.4426950408889634);
+    double r = fma(k, -6.93147180369123816490e-01, y);
+    r = fma(k, -1.90821492927058770002e-10, r);
+    r = -r;
+    double p = 2.08767569878680989792e-09;              // 1/12!
+    p = fma(p, r, 2.50521083854417187751e-08);           // 1/11!
+    p = fma(p, r, 2.75573192239858906526e-07);           // 1/10!
+    p = fma(p, r, 2.75573192239858906526e-06);           // 1/9!
+    p = fma(p, r, 2.48015873015873015873e-05);           // 1/8!
+    p = fma(p, r, 1.98412698412698412698e-04);           // 1/7!
+    p = fma(p, r, 1.38888888888888888889e-03);           // 1/6!
+    p = fma(p, r, 8.33333333333333333333e-03);           // 1/5!
+    p = fma(p, r, 4.16666666666666666667e-02);           // 1/4!
+    p = fma(p, r, 1.66666666666666666667e-01);           // 1/3!
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, -static_cast<int>(k));
+}
+
+// A(z) <- A(z) * (1 + x (e^{zq} - 1)), the exponential series cut at degree C <= D.
+// e[a] = q^a / a!.
+template <int D, int C>
+__device__ __forceinline__ void mul_factor(double (&A)[D + 1], double x, const double* e) {
+    double ee[C + 1];
+#pragma unroll
+    for (int a = 1; a <= C; ++a) ee[a] = e[a];
+#pragma unroll
+    for (int d = D; d >= 1; --d) {
+        double acc = 0.0;
+#pragma unroll
+        for (int a = 1; a <= (d < C ? d : C); ++a) acc = fma(ee[a], A[d - a], acc);
+        A[d] = fma(x, acc, A[d]);
+    }
+}
+
+// A(z) <- A(z) * B(z), truncated at degree D.
+template <int D>
+__device__ __forceinline__ void mul_series(double (&A)[D + 1], const double (&B)[D + 1]) {
+#pragma unroll
+    for (int d = D; d >= 0; --d) {
+        double acc = 0.0;
+#pragma unroll
+        for (int a = 0; a <= d; ++a) acc = fma(A[a], B[d - a], acc);
+        A[d] = acc;
+    }
+}
+
+// [z^n] of  (e^{zq} - 1) * T(z) / (1 + x (e^{zq} - 1)): the leave-one-out coefficient of a token,
+// by series division (the quotient is only needed below degree n).
+template <int D, int C>
+__device__ __forceinline__ double loo_coeff(const double (&T)[D + 1], double x, const double* e, int n) {
+    double ee[C + 1];
+#pragma unroll
+    for (int a = 1; a <= C; ++a) ee[a] = e[a];
+    double Bq[D + 1];
+    Bq[0] = T[0];
+    double cn = 0.0;
+#pragma unroll
+    for (int d = 1; d <= D; ++d) {
+        double conv = 0.0;
+#pragma unroll
+        for (int a = 1; a <= (d < C ? d : C); ++a) conv = fma(ee[a], Bq[d - a], conv);
+        Bq[d] = fma(-x, conv, T[d]);
+        if (d == n) cn = conv;
+    }
+    return cn;
+}
+
+// Four independent copies of the three primitives above, interleaved instruction by instruction
+// so that the dependent fp64 chains of one copy fill the latency of the others.
+__device__ __forceinline__ void exp_neg4(const double (&y)[4], double (&out)[4]) {
+    double k[4], r[4], p[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) k[j] = rint(fmin(y[j], 1000.0) * 1.4426950408889634);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = fma(k[j], -6.93147180369123816490e-01, fmin(y[j], 1000.0));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = -fma(k[j], -1.90821492927058770002e-10, r[j]);
+    const double c[12] = {2.50521083854417187751e-08, 2.75573192239858906526e-07, 2.75573192239858906526e-06,
+                          2.48015873015873015873e-05, 1.98412698412698412698e-04, 1.38888888888888888889e-03,
+                          8.33333333333333333333e-03, 4.16666666666666666667e-02, 1.66666666666666666667e-01,
+                          0.5, 1.0, 1.0};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p[j] = 2.08767569878680989792e-09;
+#pragma unroll
+    for (int i = 0; i < 12; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p[j] = fma(p[j], r[j], c[i]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[j] = ldexp(p[j], -static_cast<int>(k[j]));   // 2^-1443 flushes to 0
+}
+
+template <int D, int C>
+__device__ __forceinline__ void mul_factor4(double (&A)[4][D + 1], const double (&x)[4], const double (&e)[4][C + 1]) {
+#pragma unroll
+    for (int d = D; d >= 1; --d) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int a = 1; a <= (d < C ? d : C); ++a)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = fma(e[j][a], A[j][d - a], acc[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) A[j][d] = fma(x[j], acc[j], A[j][d]);
+    }
+}
+
+// four quotients T_j / (1 + x_j (e^{zq} - 1)) of the same token (series e) at four nodes
+template <int D, int C>
+__device__ __forceinline__ void loo_coeff4(const double (&T)[4][D + 1], const double (&x)[4], const double (&e)[D + 1],
+                                           int n, double (&cn)[4]) {
+    double Bq[4][D + 1];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { Bq[j][0] = T[j][0]; cn[j] = 0.0; }
+#pragma unroll
+    for (int d = 1; d <= D; ++d) {
+        double conv[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int a = 1; a <= (d < C ? d : C); ++a)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) conv[j] = fma(e[a], Bq[j][d - a], conv[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { Bq[j][d] = fma(-x[j], conv[j], T[j][d]); if (d == n) cn[j] = conv[j]; }
+    }
+}
+
+template <int D, int C>
+__device__ __forceinline__ void phase1_group(double (&A)[4][D + 1], const Lds& L, int i0, int m, double t) {
+    double y[4], x[4], e[4][C + 1];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kSW;
+        const int ii = i < m ? i : i0;
+        y[j] = i < m ? t * L.aw[ii] : 1000.0;                 // a missing token gets x = 0: its factor is 1
+#pragma unroll
+        for (int a = 1; a <= C; ++a) e[j][a] = L.etab[ii * 17 + a];
+    }
+    exp_neg4(y, x);
+    mul_factor4<D, C>(A, x, e);
+}
+
+template <int D, int C>
+__device__ __forceinline__ double phase3_token(const Lds& L, const double (&e)[D + 1], double wt, int n, int wv, int nn) {
+    double acc = 0.0;
+    for (int nu0 = wv; nu0 < nn; nu0 += 4 * kSW) {
+        double T[4][D + 1], y[4], x[4], qq[4], cn[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int nu = nu0 + j * kSW;
+            const int nv = nu < nn ? nu : nu0;
+            y[j] = L.tnode[nv] * wt;
+            qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
+#pragma unroll
+            for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * 17 + d];
+        }
+        exp_neg4(y, x);
+        loo_coeff4<D, C>(T, x, e, n, cn);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = fma(qq[j] * x[j], cn[j], acc);
+    }
+    return acc;
+}
+
 // Routed mass of every active token, and the mass left to the slack term.
-// In: L.aq (q of the active tokens), L.aal (log weights), m, n, ctx, slack, qsum = sum aq.
+//
+// Tokens are held in decreasing q (so the degree at which a token's series may be cut never
+// increases along the list).  Per chunk of 64 quadrature nodes:
+//   phase 1  lanes = nodes; wave w multiplies the factors of tokens w, w+4, w+8, ... into four
+//            independent running products (instruction-level parallelism), then merges them;
+//   phase 2  the four waves' products and the context series are multiplied into T(node), kept in LDS;
+//   phase 3  lanes = tokens; wave w walks nodes w, w+4, ...: for its token each lane divides T(node)
+//            by the token's own factor (series division) and accumulates the z^n coefficient, so no
+//            cross-lane reduction is needed; the four waves' partial sums are added at the end.
+// In: L.aq, L.aal, L.etab / L.adeg / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
 // Out: L.aR[0..m), L.R0acc (slack mass; meaningful when slack = 1).  All threads call it.
 template <int D>
-__device__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum, int* nodes_used) {
+__device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum, int* nodes_used) {
+    constexpr int C1 = D < 2 ? D : 2, C2 = D < 4 ? D : 4;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     double w = 0.0;
     if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; }
-    const double wsum = block_sum(tid < m ? w : 0.0, L.red);
-    const double wmin = block_min(tid < m ? w : 1e300, L.red);
+    const double wsum = block_sum<kSW>(tid < m ? w : 0.0, L.red);
+    const double wmin = block_min<kSW>(tid < m ? w : 1e300, L.red);
     const double t_lo = kQuadLo / (slack + wsum);
     const double t_hi = kQuadHi / (slack + ((slack == 0 || ctx == 0.0) ? wmin : 0.0));
     const double range = log(t_hi / t_lo);
@@ -82,92 +292,220 @@ __device__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double 
     if (N < 1) N = 1;
     if (N > 4096) N = 4096;
     *nodes_used = N;
+#ifdef GR_DEBUG
+    long long c_a = clock64(), c_b = 0, c_c = 0, c_d = 0;
+#endif
     const double atot = ctx + qsum;
     const double tail = step * t_lo / (exp(step) - 1.0);   // trapezoid sum of the nodes below t_lo, x = 1 there
     double fact = 1.0;
     for (int i = 2; i <= n; ++i) fact *= i;
-    if (tid < m) L.aR[tid] = pow_diff(atot, L.aq[tid], n) * tail / fact;
-    if (tid == 0) L.R0acc = ipow(atot, n) * tail / fact;
-    __syncthreads();
+    double r0 = 0.0;                                       // slack mass, accumulated by lane 0 of wave 0
+    double racc[2] = {0.0, 0.0};                           // phase 3 accumulators of tokens lane, lane + 64
 
     for (int c0 = 0; c0 < N; c0 += 64) {
         const int node = c0 + lane;
         const double t = t_lo * exp(step * node);
-        const double qw = node < N ? step * t * exp(-slack * t) : 0.0;
-        // phase 1: this wave's partial product over its tokens
-        double A[D + 1];
-        A[0] = 1.0;
+        const double qw = node < N ? step * t * exp_neg(slack * t) : 0.0;
+        if (wv == 0) { L.tnode[lane] = t; L.qwnode[lane] = qw; }
+#ifdef GR_DEBUG
+        c_b = clock64();
+#endif
+        // ---- phase 1
+        double A[4][D + 1];
 #pragma unroll
-        for (int d = 1; d <= D; ++d) A[d] = 0.0;
-        for (int i = wv; i < m; i += kWaves) {
-            const double x = exp(-t * L.aw[i]);
-            const double q = L.aq[i];
-            double e[D + 1];
-            e[0] = 1.0;
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int a = 1; a <= D; ++a) e[a] = e[a - 1] * q / a;
-#pragma unroll
-            for (int d = D; d >= 1; --d) {
-                double acc = 0.0;
-#pragma unroll
-                for (int a = 1; a <= d; ++a) acc = fma(e[a], A[d - a], acc);
-                A[d] = fma(x, acc, A[d]);
-            }
+            for (int d = 0; d <= D; ++d) A[j][d] = d == 0;
+        for (int i0 = wv; i0 < m; i0 += 4 * kSW) {
+            const int c = L.adeg[i0];                                      // the largest of the four
+            if (c <= C1) phase1_group<D, C1>(A, L, i0, m, t);
+            else if (c <= C2) phase1_group<D, C2>(A, L, i0, m, t);
+            else phase1_group<D, D>(A, L, i0, m, t);
         }
+        mul_series<D>(A[0], A[1]); mul_series<D>(A[2], A[3]); mul_series<D>(A[0], A[2]);
 #pragma unroll
-        for (int d = 0; d <= D; ++d) L.u.part[(wv * (D + 1) + d) * 64 + lane] = A[d];
+        for (int d = 0; d <= D; ++d) L.u.part[(wv * (D + 1) + d) * 64 + lane] = A[0][d];
         __syncthreads();
-        // phase 2: total product, context included
-        double T[D + 1];
-        T[0] = 1.0;
-#pragma unroll
-        for (int d = 1; d <= D; ++d) T[d] = T[d - 1] * ctx / d;
-        for (int w2 = 0; w2 < kWaves; ++w2) {
-            double Bc[D + 1];
-#pragma unroll
-            for (int d = 0; d <= D; ++d) Bc[d] = L.u.part[(w2 * (D + 1) + d) * 64 + lane];
-#pragma unroll
-            for (int d = D; d >= 0; --d) {
-                double acc = 0.0;
-#pragma unroll
-                for (int a = 0; a <= d; ++a) acc = fma(T[a], Bc[d - a], acc);
-                T[d] = acc;
-            }
-        }
-        // phase 3: leave one token out by series division, take the z^n coefficient
-        for (int i = wv; i < m; i += kWaves) {
-            const double x = exp(-t * L.aw[i]);
-            const double q = L.aq[i];
-            double e[D + 1];
-            e[0] = 1.0;
-#pragma unroll
-            for (int a = 1; a <= D; ++a) e[a] = e[a - 1] * q / a;
-            double Bq[D + 1];
-            Bq[0] = T[0];
-            double cn = 0.0;
-#pragma unroll
-            for (int d = 1; d <= D; ++d) {
-                double conv = 0.0;
-#pragma unroll
-                for (int a = 1; a <= d; ++a) conv = fma(e[a], Bq[d - a], conv);
-                Bq[d] = fma(-x, conv, T[d]);
-                if (d == n) cn = conv;
-            }
-            const double v = wave_sum(qw * x * cn);
-            if (lane == 0) L.aR[i] += v;
-        }
+#ifdef GR_DEBUG
+        c_c = clock64();
+#endif
+        // ---- phase 2: wave 0 forms T(node) = e^{z ctx} * product of the four waves' series
         if (wv == 0) {
+            double T[D + 1];
+            T[0] = 1.0;
+#pragma unroll
+            for (int d = 1; d <= D; ++d) T[d] = T[d - 1] * ctx * (1.0 / d);
+            for (int w2 = 0; w2 < kSW; ++w2) {
+                double Bc[D + 1];
+#pragma unroll
+                for (int d = 0; d <= D; ++d) Bc[d] = L.u.part[(w2 * (D + 1) + d) * 64 + lane];
+                mul_series<D>(T, Bc);
+            }
             double tn = 0.0;
 #pragma unroll
-            for (int d = 0; d <= D; ++d) if (d == n) tn = T[d];
-            const double v = wave_sum(qw * tn);
-            if (lane == 0) L.R0acc += v;
+            for (int d = 0; d <= D; ++d) { L.Tl[lane * 17 + d] = T[d]; if (d == n) tn = T[d]; }
+            r0 += wave_sum(qw * tn);
         }
         __syncthreads();
+#ifdef GR_DEBUG
+        c_d = clock64();
+#endif
+        // ---- phase 3
+        const int nn = min(64, N - c0);
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int tok = pass * 64 + lane;
+            if (pass * 64 < m) {
+                const int tk = tok < m ? tok : m - 1;
+                const double wt = L.aw[tk];
+                double e[D + 1];
+#pragma unroll
+                for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * 17 + a];
+                const int c = L.adeg[pass * 64];                           // the largest of this pass
+                double acc;
+                if (c <= C1) acc = phase3_token<D, C1>(L, e, wt, n, wv, nn);
+                else if (c <= C2) acc = phase3_token<D, C2>(L, e, wt, n, wv, nn);
+                else acc = phase3_token<D, D>(L, e, wt, n, wv, nn);
+                racc[pass] += acc;
+            }
+        }
+        __syncthreads();                                   // part / Tl / tnode are rewritten by the next chunk
     }
-    if (tid < m) L.aR[tid] *= L.aw[tid] * fact;
-    if (tid == 0) L.R0acc *= fact * slack;
+    if (lane < m) L.rpart[wv][lane] = racc[0];
+    if (64 + lane < m) L.rpart[wv][64 + lane] = racc[1];
+    if (tid == 0) L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack;
     __syncthreads();
+    if (tid < m) {
+        double r = L.apd[tid] * tail / fact;
+        for (int w2 = 0; w2 < kSW; ++w2) r += L.rpart[w2][tid];
+        L.aR[tid] = r * L.aw[tid] * fact;
+    }
+    __syncthreads();
+#ifdef GR_DEBUG
+    if (tid == 0 && blockIdx.x == GR_DEBUG) { g_dbg[0] += c_b - c_a; g_dbg[1] += c_c - c_b; g_dbg[2] += c_d - c_c; g_dbg[3] += clock64() - c_d; g_dbg[4] += 1; }
+#endif
+}
+
+// One evaluation and the stopping measure: max_i | log(target_i / routed_i) - common term |, where the
+// common term is log(slack_target / slack mass) with slack, log(sum target / sum routed) without
+// (the latter is zero in exact arithmetic and removes the common quadrature error).  f -> L.af.
+template <int D>
+__device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
+                              double tsum, double* rsum_out) {
+    const int tid = threadIdx.x;
+    int nodes;
+    routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
+    const double rsum = block_sum<kSW>(tid < m ? L.aR[tid] : 0.0, L.red);
+    double f = 0.0;
+    if (tid < m) {
+        f = log(L.at[tid] / L.aR[tid]);
+        f -= slack ? log(slack_target / L.R0acc) : log(tsum / rsum);
+        L.af[tid] = f;
+    }
+    *rsum_out = rsum;
+    return block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
+}
+
+// Damped Newton iteration on routed(alpha) = target with a finite-difference Jacobian (the Hessian of
+// Theta_T / Phi_T in alpha), for programs of at most kNewtonMax variables on which the fixed-point
+// iteration is slow (a target that nearly exhausts the tuples containing its token).  Without slack
+// the last weight is pinned (the system is singular along the common shift).  Starts from L.aal.
+template <int D>
+__device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
+                              double tsum, double rel_tol, int max_evals, int* evals) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nfree = slack ? m : m - 1;
+    constexpr int LD = kNewtonMax + 1;
+    constexpr double kFd = 1e-6;
+    double rsum;
+    double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+    *evals += 1;
+    while (err > rel_tol && *evals < max_evals && err < 1e300) {
+        if (tid < m) L.nR[tid] = L.aR[tid];
+        // common ratio routed/target over all vertices, the slack vertex included: Newton aims at
+        // routed_j = ratio * target_j, which is what the stopping measure asks for
+        const double ratio = slack ? (rsum + L.R0acc) / (tsum + slack_target) : rsum / tsum;
+        __syncthreads();
+        for (int k = 0; k < nfree; ++k) {
+            if (tid == k) L.aal[k] += kFd;
+            __syncthreads();
+            int nodes;
+            routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
+            if (tid < nfree) L.J[tid * LD + k] = (L.aR[tid] - L.nR[tid]) / kFd;
+            if (tid == k) L.aal[k] -= kFd;
+            __syncthreads();
+        }
+        *evals += nfree;
+        if (tid < nfree) L.J[tid * LD + kNewtonMax] = L.at[tid] * ratio - L.nR[tid];
+        __syncthreads();
+        // Gauss-Jordan with partial pivoting in wave 0: lane r owns row r
+        if (tid < 64) {
+            bool used = false;
+            int my_col = -1;
+            for (int c = 0; c < nfree; ++c) {
+                double mag = (lane < nfree && !used) ? fabs(L.J[lane * LD + c]) : -1.0;
+                double best = mag; int who = lane;
+                for (int o = 32; o > 0; o >>= 1) {
+                    const double ob = __shfl_xor(best, o); const int ow = __shfl_xor(who, o);
+                    if (ob > best || (ob == best && ow < who)) { best = ob; who = ow; }
+                }
+                const double piv = L.J[who * LD + c];
+                if (lane == who) { used = true; my_col = c; }
+                if (lane < nfree && lane != who && piv != 0.0) {
+                    const double fct = L.J[lane * LD + c] / piv;
+                    for (int j = c; j <= kNewtonMax; ++j)
+                        if (j < nfree || j == kNewtonMax) L.J[lane * LD + j] -= fct * L.J[who * LD + j];
+                }
+            }
+            if (lane < nfree && my_col >= 0) {
+                const double dg = L.J[lane * LD + my_col];
+                L.nstep[my_col] = dg != 0.0 ? L.J[lane * LD + kNewtonMax] / dg : 0.0;
+            }
+        }
+        __syncthreads();
+        const double smax = block_max<kSW>(tid < nfree ? fabs(L.nstep[tid]) : 0.0, L.red);
+        if (!(smax < 1e300)) break;
+        const double clip = smax > 2.0 ? 2.0 / smax : 1.0;
+        // slope of the objective along the step: grad . d with grad_j = routed_j - ratio * target_j
+        double slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * clip * L.nstep[tid] : 0.0, L.red);
+        if (!(slope0 < 0.0)) {
+            // not a descent direction (noise in the difference quotients): take the plain
+            // fixed-point step instead, which always is one
+            if (tid < nfree) L.nstep[tid] = L.af[tid] / clip;
+            __syncthreads();
+            slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * L.af[tid] : 0.0, L.red);
+        }
+#ifdef GR_DEBUG
+        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("newton m %d slack %d evals %d err %.3e smax %.3e slope0 %.3e\n", m, slack, *evals, err, smax, slope0);
+#endif
+        if (tid < m) L.nsave[tid] = L.aal[tid];
+        __syncthreads();
+        // Backtracking on the slope: the objective is convex, so it decreases along the step as long
+        // as the slope stays negative; accept the first lam whose slope is below half of |slope0|.
+        double lam = 1.0, err2 = err;
+        bool ok = false;
+        for (int ls = 0; ls < 20 && !ok; ++ls) {
+            if (tid < nfree) L.aal[tid] = L.nsave[tid] + lam * clip * L.nstep[tid];
+            __syncthreads();
+            err2 = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+            *evals += 1;
+            const double ratio2 = slack ? (rsum + L.R0acc) / (tsum + slack_target) : rsum / tsum;
+            const double slope = block_sum<kSW>(tid < nfree ? (L.aR[tid] - L.at[tid] * ratio2) * clip * L.nstep[tid] : 0.0, L.red);
+#ifdef GR_DEBUG
+            if (tid == 0 && blockIdx.x == GR_DEBUG) printf("   ls %d lam %.3e err2 %.3e slope %.3e\n", ls, lam, err2, slope);
+#endif
+            ok = (err2 < 1e300) && (slope <= 0.5 * fabs(slope0) || err2 < err);
+            if (!ok) lam *= 0.5;
+        }
+        if (!ok) {                                 // no acceptable point along the direction: stop here
+            if (tid < m) L.aal[tid] = L.nsave[tid];
+            __syncthreads();
+            break;
+        }
+        err = err2;
+    }
+    __syncthreads();
+    return err <= rel_tol ? 0 : 1;
 }
 
 // Solve one program by iterative scaling with Anderson mixing.  Returns 0 when converged.
@@ -177,33 +515,50 @@ template <int D>
 __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double slack_target,
                              double rel_tol, int max_iter, int* evals) {
     const int tid = threadIdx.x;
-    const double qsum = block_sum(tid < m ? L.aq[tid] : 0.0, L.red);
-    const double tsum = block_sum(tid < m ? L.at[tid] : 0.0, L.red);
+    const double qsum = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
+    const double tsum = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+    if (tid < m) {
+        // per-token series of e^{zq}, and the degree beyond which its terms change the z^n
+        // coefficient by less than 1e-11 relative: C(n-1, c) (q/atot)^c / (c+1) < 1e-11
+        const double q = L.aq[tid], atot = ctx + qsum;
+        double e = 1.0;
+        L.etab[tid * 17] = 1.0;
+        for (int a = 1; a <= 16; ++a) { e = e * q / a; L.etab[tid * 17 + a] = e; }
+        const double r = q / atot;
+        int keep = D;
+        double binom = 1.0, rp = 1.0;
+        for (int c = 1; c < D; ++c) {
+            binom = binom * (n - c) / c;          // C(n-1, c)
+            rp *= r;
+            if (c >= 2 && binom * rp / (c + 1) < 1e-11) { keep = c; break; }
+        }
+        L.adeg[tid] = keep;
+        L.apd[tid] = pow_diff(atot, q, n);
+    }
+    __syncthreads();
     int hcount = 0, plain = 0;
     double best_err = 1e300;
     int result = 1;
-    for (int it = 1; it <= max_iter; ++it) {
+    const int mix_iters = (m <= kNewtonMax && max_iter > kMixBudget) ? kMixBudget : max_iter;
+    for (int it = 1; it <= mix_iters; ++it) {
         if (!slack) {
-            const double amax = block_max(tid < m ? L.aal[tid] : -1e300, L.red);
+            const double amax = block_max<kSW>(tid < m ? L.aal[tid] : -1e300, L.red);
             if (tid < m) L.aal[tid] -= amax;
             __syncthreads();
         }
-        int nodes;
-        routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
-        *evals += 1;
-        // Without slack the routed masses sum to the tuple mass identically, so only the ratios
-        // R_i / target_i carry information; dividing by their common value also removes the
-        // (common) relative error of the quadrature from the stopping test.
-        const double rsum = slack ? 0.0 : block_sum(tid < m ? L.aR[tid] : 0.0, L.red);
-        double f = 0.0;
-        if (tid < m) {
-            f = log(L.at[tid] / L.aR[tid]);
-            f -= slack ? log(slack_target / L.R0acc) : log(tsum / rsum);
-            L.af[tid] = f;
-        }
-        const double err = block_max(tid < m ? fabs(f) : 0.0, L.red);
 #ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("it %d m %d slack %d err %.3e nodes %d a0 %.6f a1 %.6f R0 %.6e R1 %.6e t0 %.6e t1 %.6e R0acc %.3e hcount %d\n", it, m, slack, err, nodes, L.aal[0], L.aal[1], L.aR[0], L.aR[1], L.at[0], L.at[1], L.R0acc, hcount);
+        const long long it_c0 = clock64();
+#endif
+        double rsum;
+        const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+        *evals += 1;
+        double f = tid < m ? L.af[tid] : 0.0;
+#ifdef GR_DEBUG
+        const long long it_c1 = clock64();
+        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
+#endif
+#ifdef GR_DEBUG
+        (void)0;
 #endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
@@ -230,86 +585,115 @@ __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double
                 dF[c] = on ? f - L.Hf[slot][tid] : 0.0;
                 dA[c] = on ? L.aal[tid] - L.Ha[slot][tid] : 0.0;
             }
-            double prod[kGram];
-            int e = 0;
-#pragma unroll
-            for (int a = 0; a < kCols; ++a)
-#pragma unroll
-                for (int b = a; b < kCols; ++b) prod[e++] = dF[a] * dF[b];
-#pragma unroll
-            for (int a = 0; a < kCols; ++a) prod[e++] = dF[a] * f;
-#pragma unroll
-            for (int j = 0; j < kGram; ++j) {
-                const double s = wave_sum(prod[j]);
-                if ((tid & 63) == 0) L.gram[tid >> 6][j] = s;
+            // Gram matrix and right-hand side: one entry per thread, a loop over the tokens
+            __syncthreads();                               // Hf[cur] is complete
+            if (tid < kGram) {
+                int ca = 0, cb = 0, idx = 0;
+                for (int a2 = 0; a2 < kCols; ++a2)
+                    for (int b2 = a2; b2 < kCols; ++b2) { if (idx == tid) { ca = a2; cb = b2; } ++idx; }
+                const bool rhs = tid >= idx;               // the last kCols entries: dF_a . f
+                if (rhs) ca = tid - idx;
+                const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
+                double acc = 0.0;
+                if (ca < ncol && (rhs || cb < ncol)) {
+                    for (int i = 0; i < m; ++i) {
+                        const double fi = L.Hf[cur][i];
+                        const double da = fi - L.Hf[sa][i];
+                        acc = fma(da, rhs ? fi : fi - L.Hf[sb][i], acc);
+                    }
+                }
+                L.gram[tid] = acc;
             }
             __syncthreads();
             if (tid == 0) {
+                // normal equations by Gaussian elimination without pivoting (the matrix is symmetric
+                // positive definite after the ridge); fully unrolled so that it stays in registers
                 double Gm[kCols][kCols + 1];
-                int idx = 0;
-                for (int a = 0; a < kCols; ++a)
-                    for (int b = a; b < kCols; ++b) {
-                        const double g = L.gram[0][idx] + L.gram[1][idx] + L.gram[2][idx] + L.gram[3][idx];
-                        Gm[a][b] = g; Gm[b][a] = g; ++idx;
+                {
+                    int idx = 0;
+#pragma unroll
+                    for (int a = 0; a < kCols; ++a)
+#pragma unroll
+                        for (int b = a; b < kCols; ++b) {
+                            const double g = L.gram[idx];
+                            Gm[a][b] = g; Gm[b][a] = g; ++idx;
+                        }
+#pragma unroll
+                    for (int a = 0; a < kCols; ++a) {
+                        Gm[a][kCols] = L.gram[idx]; ++idx;
                     }
+                }
                 double tr = 0.0;
-                for (int a = 0; a < ncol; ++a) tr += Gm[a][a];
-                for (int a = 0; a < kCols; ++a) {
-                    Gm[a][kCols] = L.gram[0][idx] + L.gram[1][idx] + L.gram[2][idx] + L.gram[3][idx]; ++idx;
-                    Gm[a][a] += 1e-13 * tr + 1e-300;
-                }
-                int good = 1;
-                for (int c = 0; c < ncol && good; ++c) {            // Gaussian elimination, partial pivoting
-                    int piv = c;
-                    for (int r = c + 1; r < ncol; ++r) if (fabs(Gm[r][c]) > fabs(Gm[piv][c])) piv = r;
-                    if (!(fabs(Gm[piv][c]) > 0.0)) { good = 0; break; }
-                    if (piv != c) for (int j = 0; j <= kCols; ++j) { double tmp = Gm[c][j]; Gm[c][j] = Gm[piv][j]; Gm[piv][j] = tmp; }
-                    for (int r = c + 1; r < ncol; ++r) {
-                        const double fct = Gm[r][c] / Gm[c][c];
-                        for (int j = c; j <= kCols; ++j) Gm[r][j] -= fct * Gm[c][j];
+#pragma unroll
+                for (int a = 0; a < kCols; ++a) if (a < ncol) tr += Gm[a][a];
+                const double ridge = 1e-10 * tr + 1e-300;
+                bool good = true;
+#pragma unroll
+                for (int c = 0; c < kCols; ++c) {
+                    if (c < ncol) {
+                        Gm[c][c] += ridge;
+                        good = good && (Gm[c][c] > 0.0);
+                        const double inv = 1.0 / Gm[c][c];
+#pragma unroll
+                        for (int r = c + 1; r < kCols; ++r) {
+                            if (r < ncol) {
+                                const double fct = Gm[r][c] * inv;
+#pragma unroll
+                                for (int j = c + 1; j <= kCols; ++j) Gm[r][j] = fma(-fct, Gm[c][j], Gm[r][j]);
+                            }
+                        }
                     }
                 }
-                if (good) {
-                    for (int c = ncol - 1; c >= 0; --c) {
-                        double s = Gm[c][kCols];
-                        for (int j = c + 1; j < ncol; ++j) s -= Gm[c][j] * L.gamma[j];
-                        L.gamma[c] = s / Gm[c][c];
-                    }
+                double gam[kCols];
+#pragma unroll
+                for (int c = kCols - 1; c >= 0; --c) {
+                    double sacc = Gm[c][kCols];
+#pragma unroll
+                    for (int j = c + 1; j < kCols; ++j) if (j < ncol) sacc = fma(-Gm[c][j], gam[j], sacc);
+                    gam[c] = (c < ncol) ? sacc / Gm[c][c] : 0.0;
                 }
-                for (int c = ncol; c < kCols; ++c) L.gamma[c] = 0.0;
-                L.ok = good;
+                double gnorm = 0.0;
+#pragma unroll
+                for (int c = 0; c < kCols; ++c) { L.gamma[c] = gam[c]; gnorm += fabs(gam[c]); }
+                L.ok = (good && gnorm < 1e300) ? 1 : 0;
             }
             __syncthreads();
             double cand = f;
 #pragma unroll
             for (int c = 0; c < kCols; ++c) cand -= (dA[c] + dF[c]) * L.gamma[c];
             const int solved = L.ok;
-            const double cmax = block_max(tid < m ? fabs(cand) : 0.0, L.red);
-            if (solved && cmax <= 10.0 * fmax(1.0, fmin(err, best_err))) stepv = cand;
+            const double cmax = block_max<kSW>(tid < m ? fabs(cand) : 0.0, L.red);
+#ifdef GR_DEBUG
+            (void)0;
+#endif
+            // a mixed step longer than 3 in log weight is cut to that length (the same cap as the
+            // Newton fallback); a failed solve drops the history
+            if (solved && cmax < 1e300) stepv = cmax > 3.0 ? cand * (3.0 / cmax) : cand;
             else hcount = 0;
         }
         if (tid < m) L.aal[tid] += stepv;
         ++hcount;
         __syncthreads();
+#ifdef GR_DEBUG
+        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[6] += clock64() - it_c1;
+#endif
     }
     __syncthreads();
+    if (result != 0 && mix_iters < max_iter && best_err < 1e300) {
+        if (tid < m) L.aal[tid] = L.aBest[tid];
+        __syncthreads();
+        result = newton_program<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, rel_tol, max_iter, evals);
+    }
     return result;
 }
 
-__device__ int dispatch_solve(Lds& L, int m, int n, double ctx, int slack, double slack_target,
-                              double rel_tol, int max_iter, int* evals) {
-    if (n <= 2) return solve_program<2>(L, m, n, ctx, slack, slack_target, rel_tol, max_iter, evals);
-    if (n <= 4) return solve_program<4>(L, m, n, ctx, slack, slack_target, rel_tol, max_iter, evals);
-    if (n <= 8) return solve_program<8>(L, m, n, ctx, slack, slack_target, rel_tol, max_iter, evals);
-    return solve_program<16>(L, m, n, ctx, slack, slack_target, rel_tol, max_iter, evals);
-}
-
-// Build the active list of one program from a predicate over support positions [lo, hi), in
-// ascending position.  Returns m (possibly > kMaxT, in which case nothing was written beyond kMaxT).
-__device__ int compact_active(Lds& L, int lo, int hi) {
+// Build the active list of one program: the support positions in [lo, hi) that belong to T and have
+// a positive target, in decreasing q (L.ordq lists the positions of H* and of the rest in that
+// order).  Returns m (possibly > kMaxT, in which case nothing was written beyond kMaxT).
+__device__ int compact_active(Lds& L, int lo, int hi, int kk) {
     const int tid = threadIdx.x;
-    const int j = lo + tid;                              // hi - lo <= KS = kThreads
-    const int on = (j < hi && L.inT[j] && L.tgt[j] > 0.0) ? 1 : 0;
+    const int j = tid < kk ? L.ordq[tid] : -1;           // kk <= KS <= kST
+    const int on = (j >= lo && j < hi && L.inT[j] && L.tgt[j] > 0.0) ? 1 : 0;
     // inclusive scan of `on` over the workgroup
     int incl = on;
     for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if ((tid & 63) >= o) incl += up; }
@@ -317,7 +701,7 @@ __device__ int compact_active(Lds& L, int lo, int hi) {
     if ((tid & 63) == 63) wtot[tid >> 6] = incl;
     __syncthreads();
     int base = 0, total = 0;
-    for (int w = 0; w < kWaves; ++w) { if (w < (tid >> 6)) base += wtot[w]; total += wtot[w]; }
+    for (int w = 0; w < kSW; ++w) { if (w < (tid >> 6)) base += wtot[w]; total += wtot[w]; }
     const int slot = base + incl - 1;
     if (on && slot < kMaxT) L.apos[slot] = j;
     __syncthreads();
@@ -326,12 +710,16 @@ __device__ int compact_active(Lds& L, int lo, int hi) {
 
 }  // namespace
 
-__global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
+template <int D>
+__global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     Lds& L = *reinterpret_cast<Lds*>(lds_raw);
     const int tid = threadIdx.x;
     const int row = blockIdx.x;
     const int n = sp.n, V = sp.V;
+#ifdef GR_DEBUG
+    const long long kernel_c0 = clock64();
+#endif
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
     info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0;
@@ -361,16 +749,16 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
         for (int s = 0; s < sp.splits; ++s) {
             const int c = sp.cand_count[row * sp.splits + s];
             const unsigned long long* src = sp.cand + (static_cast<size_t>(row) * sp.splits + s) * kMaxSupport;
-            for (int i = tid; i < c; i += kThreads) L.u.keys[off + i] = src[i];
+            for (int i = tid; i < c; i += kST) L.u.keys[off + i] = src[i];
             off += c;
         }
     }
     if (tid == 0) L.count = 0;
     __syncthreads();
     unsigned long long theta = 0ull;
-    if (total > sp.k) theta = block_kth_largest(L.u.keys, total, sp.k, L.hist, L.pick);
+    if (total > sp.k) theta = block_kth_largest<kST>(L.u.keys, total, sp.k, L.hist, L.pick);
     const int kk = min(total, sp.k);
-    for (int i = tid; i < total; i += kThreads) {
+    for (int i = tid; i < total; i += kST) {
         const unsigned long long key = L.u.keys[i];
         if (key >= theta) {
             const int slot = atomicAdd(&L.count, 1);
@@ -398,11 +786,11 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
     // ---- prefix sums in the order, sequentially (bit-reproducible), then F(m) = P_m - Q_m^n
     {
 #pragma clang fp contract(off)
-        if (tid == 0) { double a = 0.0; L.P[0] = 0.0; for (int j = 0; j < kk; ++j) { a = a + L.pn[j]; L.P[j + 1] = a; } }
-        if (tid == 64) { double a = 0.0; L.S[0] = 0.0; for (int j = 0; j < kk; ++j) { a = a + L.qd[j]; L.S[j + 1] = a; } }
+        if ((tid >> 6) == 0) wave_sequential_scan(L.pn, L.P, kk, 0.0);
+        if ((tid >> 6) == 1) wave_sequential_scan(L.qd, L.S, kk, 0.0);
         __syncthreads();
         const double stot = L.S[kk];
-        for (int m = tid; m <= kk; m += kThreads) {
+        for (int m = tid; m <= kk; m += kST) {
             const double Qm = L.S[m] / stot;
             L.Q[m] = Qm;
             L.F[m] = (m == 0) ? 0.0 : L.P[m] - ipow(Qm, n);
@@ -413,27 +801,27 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
 
     // ---- H*: the smallest minimising prefix
     double fmin_local = 1e300;
-    for (int m = tid; m <= kk; m += kThreads) fmin_local = fmin(fmin_local, L.F[m]);
-    const double Fmin = block_min(fmin_local, L.red);
+    for (int m = tid; m <= kk; m += kST) fmin_local = fmin(fmin_local, L.F[m]);
+    const double Fmin = block_min<kSW>(fmin_local, L.red);
     double hcand = 1e9;
-    for (int m = tid; m <= kk; m += kThreads) if (L.F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
-    const int h = static_cast<int>(block_min(hcand, L.red));
+    for (int m = tid; m <= kk; m += kST) if (L.F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
+    const int h = static_cast<int>(block_min<kSW>(hcand, L.red));
 
     // ---- G = suffix minima of F (Hillis-Steele over kk+1 entries)
-    for (int m = tid; m <= kk; m += kThreads) L.G0[m] = L.F[m];
+    for (int m = tid; m <= kk; m += kST) L.G0[m] = L.F[m];
     __syncthreads();
     {
         double* src = L.G0; double* dst = L.G1;
         for (int o = 1; o <= kk; o <<= 1) {
-            for (int m = tid; m <= kk; m += kThreads) dst[m] = (m + o <= kk) ? fmin(src[m], src[m + o]) : src[m];
+            for (int m = tid; m <= kk; m += kST) dst[m] = (m + o <= kk) ? fmin(src[m], src[m + o]) : src[m];
             __syncthreads();
             double* t = src; src = dst; dst = t;
         }
-        if (src != L.G0) { for (int m = tid; m <= kk; m += kThreads) L.G0[m] = src[m]; }
+        if (src != L.G0) { for (int m = tid; m <= kk; m += kST) L.G0[m] = src[m]; }
         __syncthreads();
     }
     // residuals, targets, records (F(m) <= G(m+1) for m >= h; m = kk always)
-    for (int m = tid; m <= kk; m += kThreads) {
+    for (int m = tid; m <= kk; m += kST) {
         L.flag[m] = (m >= h && (m == kk || L.F[m] <= L.G0[m + 1])) ? 1 : 0;
         if (m < kk) {
             const double r = (m >= h) ? L.G0[m + 1] - L.G0[m] : 0.0;
@@ -442,21 +830,21 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
     // inclusive count of records -> block id of each token outside H*, and block bounds
-    for (int m = tid; m <= kk; m += kThreads) L.cnt0[m] = L.flag[m];
+    for (int m = tid; m <= kk; m += kST) L.cnt0[m] = L.flag[m];
     __syncthreads();
     {
         int* src = L.cnt0; int* dst = L.cnt1;
         for (int o = 1; o <= kk; o <<= 1) {
-            for (int m = tid; m <= kk; m += kThreads) dst[m] = (m >= o) ? src[m] + src[m - o] : src[m];
+            for (int m = tid; m <= kk; m += kST) dst[m] = (m >= o) ? src[m] + src[m - o] : src[m];
             __syncthreads();
             int* t = src; src = dst; dst = t;
         }
-        if (src != L.cnt0) { for (int m = tid; m <= kk; m += kThreads) L.cnt0[m] = src[m]; }
+        if (src != L.cnt0) { for (int m = tid; m <= kk; m += kST) L.cnt0[m] = src[m]; }
         __syncthreads();
     }
     const int nrec = L.cnt0[kk];
     const int nblk = nrec - 1;
-    for (int m = tid; m <= kk; m += kThreads) {
+    for (int m = tid; m <= kk; m += kST) {
         if (L.flag[m]) L.blo[L.cnt0[m]] = m;             // record number c (1-based) sits at rank m
         if (m < kk) L.blk[m] = (m >= h) ? L.cnt0[m] : 0; // token m (rank m+1) lies after record cnt0[m]
     }
@@ -479,8 +867,13 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
     const double Qh = L.Q[h];
     {
 #pragma clang fp contract(off)
-        if (tid == 0) { double a = 0.0; for (int r = 0; r < h; ++r) { const int j = L.ordq[r]; L.accb[j] = a; a = a + L.qn[j]; } }
-        if (tid == 64) { double a = Qh; for (int r = h; r < kk; ++r) { const int j = L.ordq[r]; L.accb[j] = a; a = a + L.qn[j]; } }
+        // running q mass in decreasing-q order: G0 <- q in that order, G1 <- its sequential prefix sums
+        if (tid < kk) L.G0[tid] = L.qn[L.ordq[tid]];
+        __syncthreads();
+        if ((tid >> 6) == 0) wave_sequential_scan(L.G0, L.G1, h, 0.0);
+        if ((tid >> 6) == 1) wave_sequential_scan(L.G0 + h, L.G1 + h + 1, kk - h, Qh);
+        __syncthreads();
+        if (tid < kk) L.accb[L.ordq[tid]] = L.G1[tid < h ? tid : tid + 1];
         __syncthreads();
         if (tid < kk) {
             const double a = L.accb[tid];
@@ -498,13 +891,16 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
 
+#ifdef GR_DEBUG
+    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("prologue done at %lld cycles (kk %d h %d)\n", clock64() - kernel_c0, kk, h);
+#endif
     // ---- the convex programs: program 0 = inner system, then every outer block of two or more tokens
     int status = GR_ROW_OK, evals = 0;
     for (int b = (h > 0 ? 0 : 1); b <= nblk && status != GR_ROW_TRUNC_CAP; ++b) {
         const int lo = (b == 0) ? 0 : L.blo[b];
         const int hi = (b == 0) ? h : L.blo[b + 1];
         if (b > 0 && hi - lo < 2) continue;
-        const int m = compact_active(L, lo, hi);
+        const int m = compact_active(L, lo, hi, kk);
         if (m > sp.max_T) { status = GR_ROW_TRUNC_CAP; break; }
         if (m == 0 || (b > 0 && m < 2)) continue;
         if (tid < m) {
@@ -512,13 +908,13 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
             L.aq[tid] = L.qn[j]; L.at[tid] = L.tgt[j]; L.aal[tid] = log(L.wgt[j]);
         }
         __syncthreads();
-        const double qa = block_sum(tid < m ? L.aq[tid] : 0.0, L.red);
-        const double ta = block_sum(tid < m ? L.at[tid] : 0.0, L.red);
+        const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
+        const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
         double ctx, scale, slack_target = 0.0;
         if (b == 0) {
             // context = tokens of T with target 0 (weight 0): they fill tuples but take no mass
             const int j = tid;
-            ctx = block_sum((j < h && L.inT[j] && !(L.tgt[j] > 0.0)) ? L.qn[j] : 0.0, L.red);
+            ctx = block_sum<kSW>((j < h && L.inT[j] && !(L.tgt[j] > 0.0)) ? L.qn[j] : 0.0, L.red);
             const double mass = ipow(ctx + qa, n);
             scale = mass / (ta - L.F[h]);
             slack_target = -L.F[h] * scale;
@@ -526,17 +922,20 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
             ctx = L.Q[lo];
             scale = pow_diff(ctx + qa, qa, n) / ta;
         }
-        const double w0sum = block_sum(tid < m ? L.wgt[L.apos[tid]] : 0.0, L.red);
+        const double w0sum = block_sum<kSW>(tid < m ? L.wgt[L.apos[tid]] : 0.0, L.red);
         if (tid < m) L.at[tid] *= scale;
         __syncthreads();
-        const int rc = dispatch_solve(L, m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
+        const int rc = solve_program<D>(L, m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
         if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
         const double wv = (tid < m) ? exp(L.aal[tid]) : 0.0;
-        const double wsum = block_sum(wv, L.red);
+        const double wsum = block_sum<kSW>(wv, L.red);
         if (tid < m) L.wgt[L.apos[tid]] = (b == 0) ? wv : wv * (w0sum / wsum);
         __syncthreads();
     }
 
+#ifdef GR_DEBUG
+    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]);
+#endif
     // ---- policy object
     int* o_order = sp.order + static_cast<size_t>(row) * KS;
     int* o_block = sp.block + static_cast<size_t>(row) * KS;
@@ -558,12 +957,22 @@ __global__ __launch_bounds__(kThreads) void solve_kernel(SolveParams sp) {
 }
 
 hipError_t solve_kernel_setup() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(solve_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
+    const void* kernels[4] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
+                              reinterpret_cast<const void*>(solve_kernel<8>), reinterpret_cast<const void*>(solve_kernel<16>)};
+    for (const void* k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
+// One kernel per series degree D >= n (2, 4, 8, 16), so that each keeps its series in registers.
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream) {
-    hipLaunchKernelGGL(solve_kernel, dim3(sp.B), dim3(kThreads), sizeof(Lds), stream, sp);
+    const dim3 grid(sp.B), block(kST);
+    if (sp.n <= 2) hipLaunchKernelGGL(solve_kernel<2>, grid, block, sizeof(Lds), stream, sp);
+    else if (sp.n <= 4) hipLaunchKernelGGL(solve_kernel<4>, grid, block, sizeof(Lds), stream, sp);
+    else if (sp.n <= 8) hipLaunchKernelGGL(solve_kernel<8>, grid, block, sizeof(Lds), stream, sp);
+    else hipLaunchKernelGGL(solve_kernel<16>, grid, block, sizeof(Lds), stream, sp);
     return hipGetLastError();
 }
 
