@@ -32,6 +32,11 @@ constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the 
 
 #ifdef GR_DEBUG
 __device__ long long g_dbg[8];
+__device__ long long g_mark[16];
+__device__ int g_nmark;
+#define GR_MARK(name) if (threadIdx.x == 0 && blockIdx.x == GR_DEBUG) { g_mark[g_nmark++] = clock64() - kernel_c0; }
+#else
+#define GR_MARK(name)
 #endif
 
 struct Lds {
@@ -587,22 +592,35 @@ __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double
             }
             // Gram matrix and right-hand side: one entry per thread, a loop over the tokens
             __syncthreads();                               // Hf[cur] is complete
-            if (tid < kGram) {
-                int ca = 0, cb = 0, idx = 0;
-                for (int a2 = 0; a2 < kCols; ++a2)
-                    for (int b2 = a2; b2 < kCols; ++b2) { if (idx == tid) { ca = a2; cb = b2; } ++idx; }
-                const bool rhs = tid >= idx;               // the last kCols entries: dF_a . f
-                if (rhs) ca = tid - idx;
-                const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
-                double acc = 0.0;
-                if (ca < ncol && (rhs || cb < ncol)) {
-                    for (int i = 0; i < m; ++i) {
-                        const double fi = L.Hf[cur][i];
-                        const double da = fi - L.Hf[sa][i];
-                        acc = fma(da, rhs ? fi : fi - L.Hf[sb][i], acc);
+            {
+                // entry e of (upper triangle of the Gram matrix, then dF_a . f) goes to wave e mod 4;
+                // lanes cover the tokens, the sums of one wave are independent and overlap
+                const int wv = tid >> 6, lane = tid & 63;
+                constexpr int kPer = (kGram + kSW - 1) / kSW;
+                double pr[kPer];
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) {
+                    const int e = wv + kSW * j;
+                    int ca = 0, cb = 0, idx = 0;
+                    for (int a2 = 0; a2 < kCols; ++a2)
+                        for (int b2 = a2; b2 < kCols; ++b2) { if (idx == e) { ca = a2; cb = b2; } ++idx; }
+                    const bool rhs = e >= idx;
+                    if (rhs) ca = e - idx;
+                    const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
+                    double acc = 0.0;
+                    if (e < kGram && ca < ncol && (rhs || cb < ncol)) {
+                        for (int i = lane; i < m; i += 64) {
+                            const double fi = L.Hf[cur][i];
+                            const double da = fi - L.Hf[sa][i];
+                            acc = fma(da, rhs ? fi : fi - L.Hf[sb][i], acc);
+                        }
                     }
+                    pr[j] = acc;
                 }
-                L.gram[tid] = acc;
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) pr[j] = wave_sum(pr[j]);
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) if (lane == 0 && wv + kSW * j < kGram) L.gram[wv + kSW * j] = pr[j];
             }
             __syncthreads();
             if (tid == 0) {
@@ -770,6 +788,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ordq[tid]]);
     __syncthreads();
 
+    GR_MARK("merged");
     // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id
     if (tid < kk) {
         const double qa = L.accb[tid], pa = L.G0[tid];
@@ -783,6 +802,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
 
+    GR_MARK("ranked");
     // ---- prefix sums in the order, sequentially (bit-reproducible), then F(m) = P_m - Q_m^n
     {
 #pragma clang fp contract(off)
@@ -799,6 +819,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         __syncthreads();
     }
 
+    GR_MARK("prefix");
     // ---- H*: the smallest minimising prefix
     double fmin_local = 1e300;
     for (int m = tid; m <= kk; m += kST) fmin_local = fmin(fmin_local, L.F[m]);
@@ -807,6 +828,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     for (int m = tid; m <= kk; m += kST) if (L.F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
     const int h = static_cast<int>(block_min<kSW>(hcand, L.red));
 
+    GR_MARK("hstar");
     // ---- G = suffix minima of F (Hillis-Steele over kk+1 entries)
     for (int m = tid; m <= kk; m += kST) L.G0[m] = L.F[m];
     __syncthreads();
@@ -850,6 +872,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
 
+    GR_MARK("records");
     // ---- truncation sets: fewest tokens by decreasing q with gamma_T <= tau / epsilon_T <= tau
     if (tid < kk) {
         const int mine_in = tid < h;
@@ -881,6 +904,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             L.inT[tid] = (tid < h) ? ((ipow(Qh, n) - an) > sp.tau) : ((1.0 - an) > sp.tau);
         }
     }
+    GR_MARK("trunc");
     // ---- start weights: target / Pr[token drawn within its system], inner ones in the slack's gauge
     if (tid < kk) {
         const int hi = (tid < h) ? h : L.blo[L.blk[tid] + 1];
@@ -892,7 +916,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     __syncthreads();
 
 #ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("prologue done at %lld cycles (kk %d h %d)\n", clock64() - kernel_c0, kk, h);
+    if (tid == 0 && blockIdx.x == GR_DEBUG) { printf("prologue done at %lld cycles (kk %d h %d) marks:", clock64() - kernel_c0, kk, h); for (int i = 0; i < g_nmark; ++i) printf(" %lld", g_mark[i]); printf("\n"); }
 #endif
     // ---- the convex programs: program 0 = inner system, then every outer block of two or more tokens
     int status = GR_ROW_OK, evals = 0;

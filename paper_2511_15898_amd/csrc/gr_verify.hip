@@ -121,9 +121,10 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     const int* __restrict__ drafts, const float* __restrict__ uniforms, int* __restrict__ token,
     unsigned char* __restrict__ accepted) {
     __shared__ Slice S;
-    __shared__ double w[kTile];
+    __shared__ double w[256];
     __shared__ double red[kWaves];
     __shared__ double wtot[kWaves];
+    __shared__ double seg[64];
     __shared__ int chosen;
     const int tid = threadIdx.x, row = blockIdx.x;
     const RowInfo info = infos[row];
@@ -162,45 +163,102 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
         if (tid == 0) { token[row] = first; accepted[row] = 1; }
         return;
     }
-    // ---- not among the drafts: walk the remaining tokens by ascending id
-    int last_pos = -1;                       // largest token id seen with positive weight
-    int found = -1;
-    for (int base = 0; base < V && found < 0; base += kTile) {
-        tile_weights(w, S, info, o, rh, prow, base, V);
-        double mine[4]; double s4 = 0.0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { mine[j] = w[tid * 4 + j]; s4 += mine[j]; }
-        // exclusive prefix of the per-thread sums
-        double incl = s4;
-        for (int off = 1; off < 64; off <<= 1) { const double up = __shfl_up(incl, off); if ((tid & 63) >= off) incl += up; }
-        if ((tid & 63) == 63) wtot[tid >> 6] = incl;
-        __syncthreads();
-        double before = 0.0, tile_total = 0.0;
-        for (int wv = 0; wv < kWaves; ++wv) { if (wv < (tid >> 6)) before += wtot[wv]; tile_total += wtot[wv]; }
-        double run = c + before + (incl - s4);
-        int hit = 0x7fffffff, lastp = -1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (mine[j] > 0.0) {
-                run += mine[j]; lastp = base + tid * 4 + j;
-                if (hit == 0x7fffffff && u < run) hit = base + tid * 4 + j;
+    // ---- not among the drafts: the remaining tokens by ascending id.  The range that holds the draw
+    // is narrowed level by level: it is cut into at most 64 pieces, every wave sums whole pieces with
+    // coalesced loads (no barrier inside), a scan over the piece sums picks the piece, and the last
+    // 256 tokens are scanned one per thread.  The p row is read once plus two short re-reads.
+    const int lane = tid & 63, wvv = tid >> 6;
+    const double f = S.scale / info.p_total;
+    const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0;
+    // weight of a token that is not f * p: the support (residual rho outside H*, none inside) when
+    // the drafts all lie in H*; the drafts themselves (listed first) in the fallback
+    const int n_special = S.mode == kInner ? info.support : S.nd;
+    int sp_tok = -1; double sp_w = 0.0;
+    if (tid < n_special) {
+        if (S.mode == kInner) { sp_tok = o[tid]; sp_w = tid >= info.h ? S.scale * rh[tid] : 0.0; }
+        else { sp_tok = S.tok[tid]; sp_w = 0.0; }
+    }
+    const double sp_delta = sp_tok >= 0 ? sp_w - f * static_cast<double>(prow[sp_tok]) : 0.0;
+    int lo = 0, len = V;
+    double cum = c;
+    bool beyond = false;                      // the draw lies beyond the total by rounding: take the last token with mass
+    while (len > 256) {
+        const int g = (len + 256 * 64 - 1) / (256 * 64);
+        const int cs = 256 * g;
+        const int np = (len + cs - 1) / cs;
+        const int end = lo + len;
+        for (int pc = wvv; pc < np; pc += kWaves) {
+            double s4 = 0.0;
+            for (int sub = 0; sub < g; ++sub) {
+                const int t0 = lo + pc * cs + sub * 256 + lane * 4;
+                if (vec && t0 + 3 < end) {
+                    const float4 v = *reinterpret_cast<const float4*>(prow + t0);
+                    s4 += (static_cast<double>(v.x) + static_cast<double>(v.y)) + (static_cast<double>(v.z) + static_cast<double>(v.w));
+                } else {
+                    for (int j = 0; j < 4; ++j) if (t0 + j < end) s4 += static_cast<double>(prow[t0 + j]);
+                }
             }
+            s4 = wave_sum(s4);
+            if (lane == 0) seg[pc] = f * s4;
         }
-        const double hmin = block_min(static_cast<double>(hit), red);
-        const double lmax = block_max(static_cast<double>(lastp), red);
-        if (lmax >= 0.0) last_pos = static_cast<int>(lmax);
-        if (hmin < 2147483647.0) found = static_cast<int>(hmin);
-        c += tile_total;
+        __syncthreads();
+        if (sp_tok >= lo && sp_tok < end) atomicAdd(&seg[(sp_tok - lo) / cs], sp_delta);
+        __syncthreads();
+        if (wvv == 0) {
+            const double v = lane < np ? fmax(seg[lane], 0.0) : 0.0;
+            double incl = v;
+            for (int off = 1; off < 64; off <<= 1) { const double up = __shfl_up(incl, off); if (lane >= off) incl += up; }
+            const bool pos = v > 0.0;
+            const unsigned long long hits = __ballot(pos && !beyond && u < cum + incl);
+            const unsigned long long poss = __ballot(pos);
+            int pick = -1, past = 0;
+            if (hits) pick = __ffsll(static_cast<long long>(hits)) - 1;
+            else if (poss) { pick = 63 - __clzll(static_cast<long long>(poss)); past = 1; }
+            if (lane == (pick < 0 ? 0 : pick)) { chosen = pick; red[0] = cum + (incl - v); wtot[0] = past; }
+        }
+        __syncthreads();
+        const int pick = chosen;
+        if (pick < 0) break;
+        cum = red[0];
+        beyond = beyond || wtot[0] != 0.0;
+        lo += pick * cs;
+        len = min(cs, end - lo);
         __syncthreads();
     }
-    if (tid == 0) {
-        int t = found >= 0 ? found : last_pos;
-        bool acc = false;
-        if (t < 0) {                          // no residual mass at all: keep the last draft with mass
+    if (len > 256) {                          // no residual mass at all: keep the last draft with mass
+        if (tid == 0) {
+            int t = -1;
             for (int i = 0; i < S.nd; ++i) if (S.pi[i] > 0.0) t = S.tok[i];
-            acc = t >= 0;
+            token[row] = t; accepted[row] = t >= 0 ? 1 : 0;
         }
-        token[row] = t; accepted[row] = acc ? 1 : 0;
+        return;
+    }
+    {
+        const int t = lo + tid;
+        w[tid] = tid < len ? f * static_cast<double>(prow[t]) : 0.0;
+        __syncthreads();
+        if (sp_tok >= lo && sp_tok < lo + len) w[sp_tok - lo] = sp_w;
+        __syncthreads();
+        const double mw = fmax(w[tid], 0.0);
+        double incl = mw;
+        for (int off = 1; off < 64; off <<= 1) { const double up = __shfl_up(incl, off); if (lane >= off) incl += up; }
+        if (lane == 63) wtot[wvv] = incl;
+        __syncthreads();
+        double bef = 0.0;
+        for (int w2 = 0; w2 < wvv; ++w2) bef += wtot[w2];
+        const bool pos = mw > 0.0;
+        const bool hitme = pos && !beyond && u < cum + bef + incl;
+        const int hm = static_cast<int>(block_min(hitme ? static_cast<double>(t) : 2147483647.0, red));
+        const int lm = static_cast<int>(block_max(pos ? static_cast<double>(t) : -1.0, red));
+        if (tid == 0) {
+            int t_out = hm != 0x7fffffff ? hm : lm;
+            bool acc = false;
+            if (t_out < 0) {                  // V <= 256 and no residual mass
+                for (int i = 0; i < S.nd; ++i) if (S.pi[i] > 0.0) t_out = S.tok[i];
+                acc = t_out >= 0;
+            }
+            token[row] = t_out; accepted[row] = acc ? 1 : 0;
+        }
     }
 }
 
