@@ -56,6 +56,9 @@ struct Lds {
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
     double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
+    double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
+    double e2tab[32];               // 2^(-j/32)
+    int nbig;                       // number of heavy tokens of the current program
     double red[kSW]; double R0acc; int ok; int pick[2]; int count; int hist[256];
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
@@ -174,37 +177,42 @@ __device__ __forceinline__ double loo_coeff(const double (&T)[D + 1], double x, 
     return cn;
 }
 
-// Four independent copies of the three primitives above, interleaved instruction by instruction
-// so that the dependent fp64 chains of one copy fill the latency of the others.
-__device__ __forceinline__ void exp_neg4(const double (&y)[4], double (&out)[4]) {
-    double k[4], r[4], p[4];
+// Four independent copies of the primitives, interleaved instruction by instruction so that the
+// dependent fp64 chains of one copy fill the latency of the others.
+//
+// e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
+// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
+__device__ __forceinline__ void exp_neg4(const double (&y)[4], double (&out)[4], const double* tab) {
+    double kf[4], r[4], p[4], tv[4];
+    int ki[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) k[j] = rint(fmin(y[j], 1000.0) * 1.4426950408889634);
+    for (int j = 0; j < 4; ++j) kf[j] = rint(fmin(y[j], 1000.0) * 46.166241308446828);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = fma(k[j], -6.93147180369123816490e-01, fmin(y[j], 1000.0));
+    for (int j = 0; j < 4; ++j) { ki[j] = static_cast<int>(kf[j]); tv[j] = tab[ki[j] & 31]; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = -fma(k[j], -1.90821492927058770002e-10, r[j]);
-    const double c[12] = {2.50521083854417187751e-08, 2.75573192239858906526e-07, 2.75573192239858906526e-06,
-                          2.48015873015873015873e-05, 1.98412698412698412698e-04, 1.38888888888888888889e-03,
-                          8.33333333333333333333e-03, 4.16666666666666666667e-02, 1.66666666666666666667e-01,
-                          0.5, 1.0, 1.0};
+    for (int j = 0; j < 4; ++j) r[j] = fma(kf[j], -(6.93147180369123816490e-01 / 32.0), fmin(y[j], 1000.0));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) p[j] = 2.08767569878680989792e-09;
+    for (int j = 0; j < 4; ++j) r[j] = -fma(kf[j], -(1.90821492927058770002e-10 / 32.0), r[j]);
+    const double c[5] = {4.16666666666666666667e-02, 1.66666666666666666667e-01, 0.5, 1.0, 1.0};
 #pragma unroll
-    for (int i = 0; i < 12; ++i)
+    for (int j = 0; j < 4; ++j) p[j] = 8.33333333333333333333e-03;
+#pragma unroll
+    for (int i = 0; i < 5; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) p[j] = fma(p[j], r[j], c[i]);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) out[j] = ldexp(p[j], -static_cast<int>(k[j]));   // 2^-1443 flushes to 0
+    for (int j = 0; j < 4; ++j) out[j] = ldexp(p[j] * tv[j], -(ki[j] >> 5));      // 2^-1442 flushes to 0
 }
 
 template <int D, int C>
 __device__ __forceinline__ void mul_factor4(double (&A)[4][D + 1], const double (&x)[4], const double (&e)[4][C + 1]) {
 #pragma unroll
     for (int d = D; d >= 1; --d) {
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        double acc[4];
 #pragma unroll
-        for (int a = 1; a <= (d < C ? d : C); ++a)
+        for (int j = 0; j < 4; ++j) acc[j] = e[j][1] * A[j][d - 1];
+#pragma unroll
+        for (int a = 2; a <= (d < C ? d : C); ++a)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[j] = fma(e[j][a], A[j][d - a], acc[j]);
 #pragma unroll
@@ -221,9 +229,11 @@ __device__ __forceinline__ void loo_coeff4(const double (&T)[4][D + 1], const do
     for (int j = 0; j < 4; ++j) { Bq[j][0] = T[j][0]; cn[j] = 0.0; }
 #pragma unroll
     for (int d = 1; d <= D; ++d) {
-        double conv[4] = {0.0, 0.0, 0.0, 0.0};
+        double conv[4];
 #pragma unroll
-        for (int a = 1; a <= (d < C ? d : C); ++a)
+        for (int j = 0; j < 4; ++j) conv[j] = e[1] * Bq[j][d - 1];
+#pragma unroll
+        for (int a = 2; a <= (d < C ? d : C); ++a)
 #pragma unroll
             for (int j = 0; j < 4; ++j) conv[j] = fma(e[a], Bq[j][d - a], conv[j]);
 #pragma unroll
@@ -231,59 +241,122 @@ __device__ __forceinline__ void loo_coeff4(const double (&T)[4][D + 1], const do
     }
 }
 
-template <int D, int C>
-__device__ __forceinline__ void phase1_group(double (&A)[4][D + 1], const Lds& L, int i0, int m, double t) {
-    double y[4], x[4], e[4][C + 1];
+// Phase 1, tokens that keep their full factor: tokens i0, i0+4, i0+8, i0+12 (below `bound`) into the
+// four running products.
+template <int D>
+__device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, int i0, int bound, double t) {
+    double y[4], x[4], e[4][D + 1];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int i = i0 + j * kSW;
-        const int ii = i < m ? i : i0;
-        y[j] = i < m ? t * L.aw[ii] : 1000.0;                 // a missing token gets x = 0: its factor is 1
+        const int ii = i < bound ? i : i0;
+        y[j] = i < bound ? t * L.aw[ii] : 1000.0;             // a missing token gets x = 0: its factor is 1
 #pragma unroll
-        for (int a = 1; a <= C; ++a) e[j][a] = L.etab[ii * 17 + a];
+        for (int a = 1; a <= D; ++a) e[j][a] = L.etab[ii * 17 + a];
     }
-    exp_neg4(y, x);
-    mul_factor4<D, C>(A, x, e);
+    exp_neg4(y, x, L.e2tab);
+    mul_factor4<D, D>(A, x, e);
 }
 
-template <int D, int C>
-__device__ __forceinline__ double phase3_token(const Lds& L, const double (&e)[D + 1], double wt, int n, int wv, int nn) {
+// Phase 1, light tokens: log(1 + x (e^u - 1)) = sum_k kappa_k(x) u^k / k!  with the cumulants of a
+// Bernoulli(x) variable, so the product of their factors is the exponential of four sums.
+__device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, int i0, int m, double t) {
+    double y[4], x[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kSW;
+        y[j] = i < m ? t * L.aw[i < m ? i : i0] : 1000.0;
+    }
+    exp_neg4(y, x, L.e2tab);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * kSW;
+        const double* e = L.etab + (i < m ? i : i0) * 17;
+        const double v = x[j] * (1.0 - x[j]);                  // kappa_2
+        const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
+        const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
+        K[j][0] = fma(x[j], e[1], K[j][0]);
+        K[j][1] = fma(v, e[2], K[j][1]);
+        K[j][2] = fma(k3, e[3], K[j][2]);
+        K[j][3] = fma(k4, e[4], K[j][3]);
+    }
+}
+
+// Phase 3, a token with its full factor at the four nodes nu0 + j*stride (j = 0..3).
+template <int D>
+__device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D + 1], double wt, int n, int nu0,
+                                             int stride, int nn) {
+    double T[4][D + 1], y[4], x[4], qq[4], cn[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int nu = nu0 + j * stride;
+        const int nv = nu < nn ? nu : 0;
+        y[j] = L.tnode[nv] * wt;
+        qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
+#pragma unroll
+        for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * 17 + d];
+    }
+    exp_neg4(y, x, L.e2tab);
+    loo_coeff4<D, D>(T, x, e, n, cn);
     double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = fma(qq[j] * x[j], cn[j], acc);
+    return acc;
+}
+
+// Phase 3, a light token: (e^u - 1) / (1 + x (e^u - 1)) = u + (1/2 - x) u^2 + (1/6 - x + x^2) u^3 +
+// (1/24 - 7x/12 + 3x^2/2 - x^3) u^4 + ..., so the leave-one-out coefficient is a four-term sum over
+// T[n-1..n-4].  e[k] = q^k / k! (zero for k > n), so the brackets are multiplied by k!.
+__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int n, int wv, int nn) {
+    double acc = 0.0;
+    const int o1 = n - 1, o2 = n >= 2 ? n - 2 : 0, o3 = n >= 3 ? n - 3 : 0, o4 = n >= 4 ? n - 4 : 0;
     for (int nu0 = wv; nu0 < nn; nu0 += 4 * kSW) {
-        double T[4][D + 1], y[4], x[4], qq[4], cn[4];
+        double y[4], x[4], qq[4];
+        int nv[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int nu = nu0 + j * kSW;
-            const int nv = nu < nn ? nu : nu0;
-            y[j] = L.tnode[nv] * wt;
-            qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
-#pragma unroll
-            for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * 17 + d];
+            nv[j] = nu < nn ? nu : nu0;
+            y[j] = L.tnode[nv[j]] * wt;
+            qq[j] = nu < nn ? L.qwnode[nv[j]] : 0.0;
         }
-        exp_neg4(y, x);
-        loo_coeff4<D, C>(T, x, e, n, cn);
+        exp_neg4(y, x, L.e2tab);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc = fma(qq[j] * x[j], cn[j], acc);
+        for (int j = 0; j < 4; ++j) {
+            const double* T = L.Tl + nv[j] * 17;
+            const double xx = x[j];
+            const double g2 = fma(-2.0, xx, 1.0);
+            const double g3 = fma(6.0 * xx, xx - 1.0, 1.0);
+            const double g4 = fma(xx, fma(xx, fma(-24.0, xx, 36.0), -14.0), 1.0);
+            double cn = e[1] * T[o1];
+            cn = fma(e[2] * g2, T[o2], cn);
+            cn = fma(e[3] * g3, T[o3], cn);
+            cn = fma(e[4] * g4, T[o4], cn);
+            acc = fma(qq[j] * xx, cn, acc);
+        }
     }
     return acc;
 }
 
 // Routed mass of every active token, and the mass left to the slack term.
 //
-// Tokens are held in decreasing q (so the degree at which a token's series may be cut never
-// increases along the list).  Per chunk of 64 quadrature nodes:
-//   phase 1  lanes = nodes; wave w multiplies the factors of tokens w, w+4, w+8, ... into four
-//            independent running products (instruction-level parallelism), then merges them;
-//   phase 2  the four waves' products and the context series are multiplied into T(node), kept in LDS;
-//   phase 3  lanes = tokens; wave w walks nodes w, w+4, ...: for its token each lane divides T(node)
-//            by the token's own factor (series division) and accumulates the z^n coefficient, so no
-//            cross-lane reduction is needed; the four waves' partial sums are added at the end.
-// In: L.aq, L.aal, L.etab / L.adeg / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
+// Tokens are held in decreasing q.  The first L.nbig of them ("heavy") keep their full factor
+// 1 + x (e^{zq} - 1); the others ("light": q so small that terms beyond u^4 cannot change the z^n
+// coefficient, or n <= 4 where four terms are exact) enter through four cumulant sums.
+// Per chunk of 64 quadrature nodes:
+//   phase 1  lanes = nodes; wave w takes tokens w, w+4, ...: heavy ones into four interleaved running
+//            products, light ones into the cumulant sums;
+//   phase 2  wave 0 forms T(node) = exp(z ctx + cumulant series) * product of the heavy products -> LDS;
+//   phase 3  lanes = tokens, wave w walks nodes w, w+4, ...: each lane takes the leave-one-out
+//            coefficient of its token (series division for heavy tokens, the four-term expansion for
+//            light ones) and accumulates; no cross-lane reduction for the light tokens, two shuffles
+//            for the heavy ones (16 tokens x 4 node groups per wave).
+// In: L.aq, L.aal, L.etab / L.nbig / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
 // Out: L.aR[0..m), L.R0acc (slack mass; meaningful when slack = 1).  All threads call it.
 template <int D>
 __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum, int* nodes_used) {
-    constexpr int C1 = D < 2 ? D : 2, C2 = D < 4 ? D : 4;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int nbig = L.nbig;
     double w = 0.0;
     if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; }
     const double wsum = block_sum<kSW>(tid < m ? w : 0.0, L.red);
@@ -305,7 +378,21 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     double fact = 1.0;
     for (int i = 2; i <= n; ++i) fact *= i;
     double r0 = 0.0;                                       // slack mass, accumulated by lane 0 of wave 0
-    double racc[2] = {0.0, 0.0};                           // phase 3 accumulators of tokens lane, lane + 64
+    double racc[2] = {0.0, 0.0};                           // phase 3 accumulators of light tokens lane, lane + 64
+    if (tid < m) { for (int w2 = 0; w2 < kSW; ++w2) L.rpart[w2][tid] = 0.0; }
+    const int first_small = nbig + ((wv - nbig) % kSW + kSW) % kSW;   // first light token of this wave
+    // this lane's light tokens in phase 3: series terms q^k / k!, k <= min(n, 4)
+    double es[2][5]; double ws[2];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tok = pass * 64 + lane;
+        const int tk = tok < m ? tok : 0;
+        ws[pass] = m > 0 ? L.aw[tk] : 0.0;
+#pragma unroll
+        for (int a = 1; a <= 4; ++a) es[pass][a] = (a <= n && m > 0) ? L.etab[tk * 17 + a] : 0.0;
+        es[pass][0] = 0.0;
+    }
+    __syncthreads();
 
     for (int c0 = 0; c0 < N; c0 += 64) {
         const int node = c0 + lane;
@@ -316,35 +403,57 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
         c_b = clock64();
 #endif
         // ---- phase 1
-        double A[4][D + 1];
+        if (nbig > 0) {
+            double A[4][D + 1];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int d = 0; d <= D; ++d) A[j][d] = d == 0;
-        for (int i0 = wv; i0 < m; i0 += 4 * kSW) {
-            const int c = L.adeg[i0];                                      // the largest of the four
-            if (c <= C1) phase1_group<D, C1>(A, L, i0, m, t);
-            else if (c <= C2) phase1_group<D, C2>(A, L, i0, m, t);
-            else phase1_group<D, D>(A, L, i0, m, t);
+                for (int d = 0; d <= D; ++d) A[j][d] = d == 0;
+            for (int i0 = wv; i0 < nbig; i0 += 4 * kSW) phase1_big<D>(A, L, i0, nbig, t);
+            mul_series<D>(A[0], A[1]); mul_series<D>(A[2], A[3]); mul_series<D>(A[0], A[2]);
+#pragma unroll
+            for (int d = 0; d <= D; ++d) L.u.part[(wv * (D + 1) + d) * 64 + lane] = A[0][d];
         }
-        mul_series<D>(A[0], A[1]); mul_series<D>(A[2], A[3]); mul_series<D>(A[0], A[2]);
+        {
+            double K[4][4];
 #pragma unroll
-        for (int d = 0; d <= D; ++d) L.u.part[(wv * (D + 1) + d) * 64 + lane] = A[0][d];
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) K[j][k] = 0.0;
+            for (int i0 = first_small; i0 < m; i0 += 4 * kSW) phase1_small(K, L, i0, m, t);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) L.cum[(wv * 4 + k) * 64 + lane] = (K[0][k] + K[1][k]) + (K[2][k] + K[3][k]);
+        }
         __syncthreads();
 #ifdef GR_DEBUG
         c_c = clock64();
 #endif
-        // ---- phase 2: wave 0 forms T(node) = e^{z ctx} * product of the four waves' series
+        // ---- phase 2 (wave 0)
         if (wv == 0) {
+            double Kt[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                Kt[k] = 0.0;
+                for (int w2 = 0; w2 < kSW; ++w2) Kt[k] += L.cum[(w2 * 4 + k) * 64 + lane];
+            }
+            Kt[0] += ctx;                                  // e^{z ctx}
+            // T = exp(Kt_1 z + ... + Kt_4 z^4):  d T_d = sum_k k Kt_k T_{d-k}
             double T[D + 1];
             T[0] = 1.0;
 #pragma unroll
-            for (int d = 1; d <= D; ++d) T[d] = T[d - 1] * ctx * (1.0 / d);
-            for (int w2 = 0; w2 < kSW; ++w2) {
-                double Bc[D + 1];
+            for (int d = 1; d <= D; ++d) {
+                double acc = Kt[0] * T[d - 1];
 #pragma unroll
-                for (int d = 0; d <= D; ++d) Bc[d] = L.u.part[(w2 * (D + 1) + d) * 64 + lane];
-                mul_series<D>(T, Bc);
+                for (int k = 2; k <= (d < 4 ? d : 4); ++k) acc = fma(static_cast<double>(k) * Kt[k - 1], T[d - k], acc);
+                T[d] = acc * (1.0 / d);
+            }
+            if (nbig > 0) {
+                for (int w2 = 0; w2 < kSW; ++w2) {
+                    double Bc[D + 1];
+#pragma unroll
+                    for (int d = 0; d <= D; ++d) Bc[d] = L.u.part[(w2 * (D + 1) + d) * 64 + lane];
+                    mul_series<D>(T, Bc);
+                }
             }
             double tn = 0.0;
 #pragma unroll
@@ -357,27 +466,28 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
 #endif
         // ---- phase 3
         const int nn = min(64, N - c0);
+        // heavy tokens: 16 per round, lane = (token, node group); this wave's nodes are wv, wv+4, ...,
+        // node group g takes every fourth of them
+        for (int b0 = 0; b0 < nbig; b0 += 16) {
+            const int tok = b0 + (lane & 15);
+            const int tk = tok < nbig ? tok : 0;
+            double e[D + 1];
+#pragma unroll
+            for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * 17 + a];
+            double acc = phase3_big<D>(L, e, L.aw[tk], n, wv + kSW * (lane >> 4), 4 * kSW, nn);
+            acc += __shfl_xor(acc, 16);
+            acc += __shfl_xor(acc, 32);
+            if (lane < 16 && tok < nbig) L.rpart[wv][tok] += acc;
+        }
+        // light tokens
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
-            const int tok = pass * 64 + lane;
-            if (pass * 64 < m) {
-                const int tk = tok < m ? tok : m - 1;
-                const double wt = L.aw[tk];
-                double e[D + 1];
-#pragma unroll
-                for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * 17 + a];
-                const int c = L.adeg[pass * 64];                           // the largest of this pass
-                double acc;
-                if (c <= C1) acc = phase3_token<D, C1>(L, e, wt, n, wv, nn);
-                else if (c <= C2) acc = phase3_token<D, C2>(L, e, wt, n, wv, nn);
-                else acc = phase3_token<D, D>(L, e, wt, n, wv, nn);
-                racc[pass] += acc;
-            }
+            if (pass * 64 < m && (pass + 1) * 64 > nbig) racc[pass] += phase3_small(L, es[pass], ws[pass], n, wv, nn);
         }
-        __syncthreads();                                   // part / Tl / tnode are rewritten by the next chunk
+        __syncthreads();                                   // part / cum / Tl / tnode are rewritten by the next chunk
     }
-    if (lane < m) L.rpart[wv][lane] = racc[0];
-    if (64 + lane < m) L.rpart[wv][64 + lane] = racc[1];
+    if (lane < m && lane >= nbig) L.rpart[wv][lane] = racc[0];
+    if (64 + lane < m && 64 + lane >= nbig) L.rpart[wv][64 + lane] = racc[1];
     if (tid == 0) L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack;
     __syncthreads();
     if (tid < m) {
@@ -529,17 +639,17 @@ __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double
         double e = 1.0;
         L.etab[tid * 17] = 1.0;
         for (int a = 1; a <= 16; ++a) { e = e * q / a; L.etab[tid * 17 + a] = e; }
+        // light if the u^5 and later terms of its factor cannot change the z^n coefficient by more
+        // than 1e-11 relative: C(n-1, 4) (q/atot)^4 / 5 < 1e-11; exact for n <= 4
         const double r = q / atot;
-        int keep = D;
-        double binom = 1.0, rp = 1.0;
-        for (int c = 1; c < D; ++c) {
-            binom = binom * (n - c) / c;          // C(n-1, c)
-            rp *= r;
-            if (c >= 2 && binom * rp / (c + 1) < 1e-11) { keep = c; break; }
-        }
-        L.adeg[tid] = keep;
+        double binom = 1.0;
+        for (int c = 1; c <= 4; ++c) binom = binom * (n - c) / c;         // C(n-1, 4)
+        L.adeg[tid] = (n <= 4 || binom * r * r * r * r / 5.0 < 1e-11) ? 0 : D;
         L.apd[tid] = pow_diff(atot, q, n);
     }
+    if (tid < 32) L.e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
+    const int nheavy = block_sum_i<kSW>((tid < m && L.adeg[tid] != 0) ? 1 : 0, L.red);
+    if (tid == 0) L.nbig = nheavy;
     __syncthreads();
     int hcount = 0, plain = 0;
     double best_err = 1e300;
@@ -563,7 +673,7 @@ __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double
         if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
 #endif
 #ifdef GR_DEBUG
-        (void)0;
+        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("it %d m %d nbig %d slack %d err %.3e best %.3e hcount %d plain %d nodes?\n", it, m, L.nbig, slack, err, best_err, hcount, plain);
 #endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
