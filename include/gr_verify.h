@@ -55,7 +55,8 @@ typedef struct {
     int    max_iter;   /* iteration cap per convex program; <= 0 selects 1000 */
     int    max_T;      /* cap on the variables of one program; <= 0 or > GR_MAX_T selects GR_MAX_T */
     double rel_tol;    /* stop when every routed mass is within this relative distance of its
-                          target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-9 */
+                          target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-8, an order
+                          above the error of the quadrature behind the routed masses */
     int    flags;      /* 0, or GR_FLAG_PROFILE */
 } gr_config;
 

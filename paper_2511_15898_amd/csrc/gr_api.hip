@@ -10,7 +10,7 @@ namespace { constexpr int kProfSlots = 512; }
 struct gr_handle_s {
     int max_B = 0, max_V = 0;
     int max_iter = 1000, max_T = GR_MAX_T;
-    double rel_tol = 1e-9;
+    double rel_tol = 1e-8;
     int device = 0;
     // scratch of the select kernel
     unsigned long long* cand = nullptr; int* cand_count = nullptr;

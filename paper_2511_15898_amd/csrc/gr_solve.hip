@@ -260,25 +260,42 @@ __device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, 
 
 // Phase 1, light tokens: log(1 + x (e^u - 1)) = sum_k kappa_k(x) u^k / k!  with the cumulants of a
 // Bernoulli(x) variable, so the product of their factors is the exponential of four sums.
-__device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, int i0, int m, double t) {
-    double y[4], x[4];
+// Tokens first, first + kSW, ... below m, four at a time; the LDS operands of the next four are
+// requested before the arithmetic of the current four so that their latency is covered.
+__device__ __forceinline__ void phase1_small_load(const Lds& L, int i0, int m, double (&aw)[4], double (&e)[4][4]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int i = i0 + j * kSW;
-        y[j] = i < m ? t * L.aw[i < m ? i : i0] : 1000.0;
+        const int ii = i < m ? i : m - 1;
+        aw[j] = i < m ? L.aw[ii] : 1e300;                      // a missing token gets x = 0: no contribution
+#pragma unroll
+        for (int a = 0; a < 4; ++a) e[j][a] = L.etab[ii * 17 + 1 + a];
     }
-    exp_neg4(y, x, L.e2tab);
+}
+__device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, int first, int m, double t) {
+    if (first >= m) return;
+    double awn[4], en[4][4];
+    phase1_small_load(L, first, m, awn, en);
+    for (int i0 = first; i0 < m; i0 += 4 * kSW) {
+        double y[4], x[4], e[4][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int i = i0 + j * kSW;
-        const double* e = L.etab + (i < m ? i : i0) * 17;
-        const double v = x[j] * (1.0 - x[j]);                  // kappa_2
-        const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
-        const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
-        K[j][0] = fma(x[j], e[1], K[j][0]);
-        K[j][1] = fma(v, e[2], K[j][1]);
-        K[j][2] = fma(k3, e[3], K[j][2]);
-        K[j][3] = fma(k4, e[4], K[j][3]);
+        for (int j = 0; j < 4; ++j) {
+            y[j] = t * awn[j];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) e[j][a] = en[j][a];
+        }
+        if (i0 + 4 * kSW < m) phase1_small_load(L, i0 + 4 * kSW, m, awn, en);
+        exp_neg4(y, x, L.e2tab);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double v = x[j] * (1.0 - x[j]);                  // kappa_2
+            const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
+            const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
+            K[j][0] = fma(x[j], e[j][0], K[j][0]);
+            K[j][1] = fma(v, e[j][1], K[j][1]);
+            K[j][2] = fma(k3, e[j][2], K[j][2]);
+            K[j][3] = fma(k4, e[j][3], K[j][3]);
+        }
     }
 }
 
@@ -307,32 +324,44 @@ __device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D +
 // Phase 3, a light token: (e^u - 1) / (1 + x (e^u - 1)) = u + (1/2 - x) u^2 + (1/6 - x + x^2) u^3 +
 // (1/24 - 7x/12 + 3x^2/2 - x^3) u^4 + ..., so the leave-one-out coefficient is a four-term sum over
 // T[n-1..n-4].  e[k] = q^k / k! (zero for k > n), so the brackets are multiplied by k!.
+// The node operands (uniform over the wave) of the next four nodes are requested before the
+// arithmetic of the current four.
+struct NodeOps { double t[4], qw[4], T[4][4]; };
+__device__ __forceinline__ void phase3_small_load(const Lds& L, int nu0, int nn, const int (&o)[4], NodeOps& r) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int nu = nu0 + j * kSW;
+        const int nv = nu < nn ? nu : nu0;
+        r.t[j] = L.tnode[nv];
+        r.qw[j] = nu < nn ? L.qwnode[nv] : 0.0;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) r.T[j][a] = L.Tl[nv * 17 + o[a]];
+    }
+}
 __device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int n, int wv, int nn) {
     double acc = 0.0;
-    const int o1 = n - 1, o2 = n >= 2 ? n - 2 : 0, o3 = n >= 3 ? n - 3 : 0, o4 = n >= 4 ? n - 4 : 0;
+    const int o[4] = {n - 1, n >= 2 ? n - 2 : 0, n >= 3 ? n - 3 : 0, n >= 4 ? n - 4 : 0};
+    if (wv >= nn) return acc;
+    NodeOps nx;
+    phase3_small_load(L, wv, nn, o, nx);
     for (int nu0 = wv; nu0 < nn; nu0 += 4 * kSW) {
-        double y[4], x[4], qq[4];
-        int nv[4];
+        const NodeOps c = nx;
+        if (nu0 + 4 * kSW < nn) phase3_small_load(L, nu0 + 4 * kSW, nn, o, nx);
+        double y[4], x[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int nu = nu0 + j * kSW;
-            nv[j] = nu < nn ? nu : nu0;
-            y[j] = L.tnode[nv[j]] * wt;
-            qq[j] = nu < nn ? L.qwnode[nv[j]] : 0.0;
-        }
+        for (int j = 0; j < 4; ++j) y[j] = c.t[j] * wt;
         exp_neg4(y, x, L.e2tab);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const double* T = L.Tl + nv[j] * 17;
             const double xx = x[j];
             const double g2 = fma(-2.0, xx, 1.0);
             const double g3 = fma(6.0 * xx, xx - 1.0, 1.0);
             const double g4 = fma(xx, fma(xx, fma(-24.0, xx, 36.0), -14.0), 1.0);
-            double cn = e[1] * T[o1];
-            cn = fma(e[2] * g2, T[o2], cn);
-            cn = fma(e[3] * g3, T[o3], cn);
-            cn = fma(e[4] * g4, T[o4], cn);
-            acc = fma(qq[j] * xx, cn, acc);
+            double cn = e[1] * c.T[j][0];
+            cn = fma(e[2] * g2, c.T[j][1], cn);
+            cn = fma(e[3] * g3, c.T[j][2], cn);
+            cn = fma(e[4] * g4, c.T[j][3], cn);
+            acc = fma(c.qw[j] * xx, cn, acc);
         }
     }
     return acc;
@@ -420,7 +449,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int k = 0; k < 4; ++k) K[j][k] = 0.0;
-            for (int i0 = first_small; i0 < m; i0 += 4 * kSW) phase1_small(K, L, i0, m, t);
+            phase1_small(K, L, first_small, m, t);
 #pragma unroll
             for (int k = 0; k < 4; ++k) L.cum[(wv * 4 + k) * 64 + lane] = (K[0][k] + K[1][k]) + (K[2][k] + K[3][k]);
         }
@@ -671,9 +700,6 @@ __device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double
 #ifdef GR_DEBUG
         const long long it_c1 = clock64();
         if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
-#endif
-#ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("it %d m %d nbig %d slack %d err %.3e best %.3e hcount %d plain %d nodes?\n", it, m, L.nbig, slack, err, best_err, hcount, plain);
 #endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {

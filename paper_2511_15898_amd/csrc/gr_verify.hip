@@ -113,6 +113,17 @@ __device__ void tile_weights(double* w, const Slice& S, const RowInfo& info, con
     __syncthreads();
 }
 
+// Four consecutive probabilities from token t0 on; entries at or beyond `end` read as zero.
+__device__ __forceinline__ float4 load4(const float* prow, int t0, int end, bool vec) {
+    if (vec && t0 + 3 < end) return *reinterpret_cast<const float4*>(prow + t0);
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (t0 < end) r.x = prow[t0];
+    if (t0 + 1 < end) r.y = prow[t0 + 1];
+    if (t0 + 2 < end) r.z = prow[t0 + 2];
+    if (t0 + 3 < end) r.w = prow[t0 + 3];
+    return r;
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(kThreads) void verify_kernel(
@@ -187,19 +198,31 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
         const int cs = 256 * g;
         const int np = (len + cs - 1) / cs;
         const int end = lo + len;
-        for (int pc = wvv; pc < np; pc += kWaves) {
-            double s4 = 0.0;
-            for (int sub = 0; sub < g; ++sub) {
-                const int t0 = lo + pc * cs + sub * 256 + lane * 4;
-                if (vec && t0 + 3 < end) {
-                    const float4 v = *reinterpret_cast<const float4*>(prow + t0);
-                    s4 += (static_cast<double>(v.x) + static_cast<double>(v.y)) + (static_cast<double>(v.z) + static_cast<double>(v.w));
-                } else {
-                    for (int j = 0; j < 4; ++j) if (t0 + j < end) s4 += static_cast<double>(prow[t0 + j]);
+        // two pieces per round and up to eight loads of each in flight: one workgroup streams the row,
+        // so the walk is bound by load latency, not by bandwidth
+        for (int pc = wvv; pc < np; pc += 2 * kWaves) {
+            double sa = 0.0, sb = 0.0;
+            const int pb = pc + kWaves;
+            for (int sub0 = 0; sub0 < g; sub0 += 8) {
+                float4 va[8], vb[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int ta = lo + pc * cs + (sub0 + j) * 256 + lane * 4;
+                    va[j] = sub0 + j < g ? load4(prow, ta, end, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int tb = lo + pb * cs + (sub0 + j) * 256 + lane * 4;
+                    vb[j] = (pb < np && sub0 + j < g) ? load4(prow, tb, end, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    sa += (static_cast<double>(va[j].x) + static_cast<double>(va[j].y)) + (static_cast<double>(va[j].z) + static_cast<double>(va[j].w));
+                    sb += (static_cast<double>(vb[j].x) + static_cast<double>(vb[j].y)) + (static_cast<double>(vb[j].z) + static_cast<double>(vb[j].w));
                 }
             }
-            s4 = wave_sum(s4);
-            if (lane == 0) seg[pc] = f * s4;
+            sa = wave_sum(sa); sb = wave_sum(sb);
+            if (lane == 0) { seg[pc] = f * sa; if (pb < np) seg[pb] = f * sb; }
         }
         __syncthreads();
         if (sp_tok >= lo && sp_tok < end) atomicAdd(&seg[(sp_tok - lo) / cs], sp_delta);
