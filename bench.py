@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64 lanes x 2 flop x 2.4 GHz)
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) on the default
+# workload, scaled by what the same counters read for a 256 MiB device copy in the same run
+# (profiles/hbm_traffic_large_vocab.md).  Only valid for that workload at the default tau.
+MEASURED_TRAFFIC_BYTES = {"select_kernel": 265173000, "solve_kernel": 8866000, "verify_kernel": 1503000}
+
 
 def cpu_baseline(wl, tol, budget_s=15.0):
     """The CPU checker as it stands, single thread, on the first rows of the same batch."""
@@ -47,6 +52,8 @@ def main():
     ap.add_argument("--workload", default="large", choices=["large", "llm", "small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="run one 256 MiB device-to-device copy first (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; rows shard across GPUs without exchange "
@@ -68,6 +75,12 @@ def main():
         gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
         gr.gr_verify(h, d, u, tok, ok)
 
+    if args.pmc_copy:
+        src = torch.ones(1 << 26, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -79,9 +92,10 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = None if args.no_events else gr.gr_profile_read(h)
-    exp = gr.gr_policy_export(h, wl.B, dev)
+    stats = gr.gr_solve_stats(h, wl.B, dev)
     torch.cuda.synchronize()
-    status = st.cpu().numpy(); iters = exp["iterations"].cpu().numpy()
+    status = st.cpu().numpy(); iters = stats["evaluations"].cpu().numpy()
+    node_tokens = float(stats["node_tokens"].sum().item())
     gr.gr_destroy(h)
 
     ms_per_step = dt / args.steps * 1e3
@@ -94,9 +108,19 @@ def main():
             achieved = algo_bytes / (kernels[dom] * 1e-3) / 1e9
             roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+        elif dom == "solve_kernel":
+            # algorithmic arithmetic of the solve: 4 n^2 flops per (evaluator call, quadrature node, active token)
+            flops = 4.0 * wl.n * wl.n * node_tokens
+            achieved = flops / (kernels[dom] * 1e-3) / 1e12
+            roofline = {"bound": "alu", "kernel": dom, "achieved": achieved, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / FP64_PEAK_TFLOPS, "traffic": None,
+                        "algorithmic_flops_per_launch": flops, "node_tokens_per_launch": node_tokens}
         else:
-            roofline = {"bound": "alu", "kernel": dom, "achieved": None, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": None, "traffic": None}
+        if args.workload == "large" and abs(args.tol - 1e-4) < 1e-12:
+            roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dom)
+            roofline["traffic_all_kernels"] = MEASURED_TRAFFIC_BYTES or None
         roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
         roofline["events_steps"] = prof["steps"]
         roofline["select_hbm_frac"] = algo_bytes / (kernels["select_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS

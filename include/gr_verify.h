@@ -107,6 +107,14 @@ int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_giv
 int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
                      int* support, int* h_size, int* iterations, void* hip_stream);
 
+/* Work done by the last gr_solve, per row ([B] device arrays, either may be NULL):
+ * evaluations = calls of the routed-mass evaluator (one per fixed-point or Newton step, plus
+ * the finite-difference columns of a Newton Jacobian); node_tokens = sum over those calls of
+ * (quadrature nodes x active tokens of the program), the unit in which the arithmetic of the
+ * generating-function evaluator of Sec. 6.3's objectives is counted: one call costs about
+ * 4 n^2 floating-point operations per (node, token) pair. */
+int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens, void* hip_stream);
+
 /* Measurement hook (handles created with GR_FLAG_PROFILE): average duration in milliseconds of
  * the streaming selection kernel, the per-row solve kernel (both launched by gr_solve) and the
  * verification kernel, over the gr_solve + gr_verify pairs issued since the last read (at most

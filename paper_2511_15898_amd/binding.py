@@ -19,7 +19,7 @@ GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_verify", "gr_policy_slice", "gr_policy_export",
-           "gr_profile_read", "gr_strerror")
+           "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
 
@@ -53,6 +53,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
+    lib.gr_solve_stats.argtypes = [vp] * 4
     lib.gr_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.gr_strerror.argtypes = [ci]
@@ -146,6 +147,16 @@ def gr_profile_read(handle: int) -> dict:
     if rc != GR_OK:
         raise GrError(rc, "gr_profile_read")
     return {"select_ms": a.value, "solve_ms": b.value, "verify_ms": c.value, "steps": n.value}
+
+
+def gr_solve_stats(handle: int, B: int, device, stream=None) -> dict:
+    """Per-row work of the last solve: evaluator calls and (nodes x active tokens) summed over them."""
+    ev = torch.empty(B, dtype=torch.int32, device=device)
+    nt = torch.empty(B, dtype=torch.float64, device=device)
+    rc = load_library().gr_solve_stats(handle, ev.data_ptr(), nt.data_ptr(), _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_solve_stats")
+    return {"evaluations": ev, "node_tokens": nt}
 
 
 def gr_policy_export(handle: int, B: int, device, stream=None) -> dict:

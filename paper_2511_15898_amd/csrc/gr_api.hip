@@ -184,6 +184,13 @@ __global__ void export_kernel(const RowInfo* info, int B, int* support, int* h_s
     if (iterations) iterations[b] = info[b].iterations;
 }
 
+__global__ void stats_kernel(const RowInfo* info, int B, int* evaluations, double* node_tokens) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    if (evaluations) evaluations[b] = info[b].iterations;
+    if (node_tokens) node_tokens[b] = info[b].node_tokens;
+}
+
 }  // namespace
 
 extern "C" int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
@@ -204,6 +211,14 @@ extern "C" int gr_policy_export(gr_handle h, int* order, int* block, double* wei
         if (hipGetLastError() != hipSuccess) return GR_EHIP;
     }
     return GR_OK;
+}
+
+extern "C" int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens, void* hip_stream) {
+    if (!h) return GR_EINVAL;
+    if (!h->solved) return GR_ESTATE;
+    hipLaunchKernelGGL(stats_kernel, dim3((h->B + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       h->info, h->B, evaluations, node_tokens);
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_EHIP;
 }
 
 extern "C" const char* gr_strerror(int code) {

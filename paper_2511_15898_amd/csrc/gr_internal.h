@@ -26,6 +26,7 @@ struct RowInfo {
     double res_total;   // sum of residuals p(i) - p_i over tokens outside H* (= 1 - alpha*)
     double p_total;     // float64 row sum of p
     double q_total;     // float64 row sum of q (before top-k)
+    double node_tokens; // sum over evaluator calls of (quadrature nodes x active tokens)
 };
 
 struct SolveParams {

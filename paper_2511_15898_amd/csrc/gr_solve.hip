@@ -59,6 +59,7 @@ struct Lds {
     double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
     double e2tab[32];               // 2^(-j/32)
     int nbig;                       // number of heavy tokens of the current program
+    double work;                    // sum over evaluator calls of nodes x active tokens (thread 0 only)
     double red[kSW]; double R0acc; int ok; int pick[2]; int count; int hist[256];
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
@@ -517,7 +518,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     }
     if (lane < m && lane >= nbig) L.rpart[wv][lane] = racc[0];
     if (64 + lane < m && 64 + lane >= nbig) L.rpart[wv][64 + lane] = racc[1];
-    if (tid == 0) L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack;
+    if (tid == 0) { L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack; L.work += static_cast<double>(N) * m; }
     __syncthreads();
     if (tid < m) {
         double r = L.apd[tid] * tail / fact;
@@ -876,7 +877,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 #endif
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
-    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0;
+    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0;
 
     // ---- merge the slices
     int total = 0, bad = 0;
@@ -907,7 +908,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             off += c;
         }
     }
-    if (tid == 0) L.count = 0;
+    if (tid == 0) { L.count = 0; L.work = 0.0; }
     __syncthreads();
     unsigned long long theta = 0ull;
     if (total > sp.k) theta = block_kth_largest<kST>(L.u.keys, total, sp.k, L.hist, L.pick);
@@ -1110,6 +1111,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         info.support = kk; info.h = h; info.status = status; info.iterations = evals;
         info.alpha_star = 1.0 + L.F[h];
         info.res_total = -L.F[h];
+        info.node_tokens = L.work;
         sp.info[row] = info;
         sp.accept_prob[row] = static_cast<float>(1.0 + L.F[h]);
         sp.status[row] = status;
