@@ -39,13 +39,15 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_ENOMEM       (-2)   /* device allocation failed */
 #define GR_ESTATE       (-3)   /* gr_verify / gr_policy_* before a successful gr_solve */
 #define GR_EHIP         (-4)   /* a HIP runtime call failed */
-#define GR_EUNSUPPORTED (-5)   /* support larger than GR_MAX_SUPPORT (e.g. no top-k on a large V) */
+#define GR_EUNSUPPORTED (-5)   /* a top-k above GR_MAX_SUPPORT and below V; dense export of a full-V policy */
 
 /* per-row status written by gr_solve */
 #define GR_ROW_OK         0
 #define GR_ROW_TRUNC_CAP  1    /* a program needed more than max_T variables (App. "Truncated Solver Details") */
 #define GR_ROW_ITER_CAP   2    /* iteration cap reached before the gradient criterion (same appendix) */
 #define GR_ROW_BAD        3    /* NaN / negative entry, or a row sum further than 1e-3 from 1 */
+#define GR_ROW_UNSOLVED   4    /* support above GR_MAX_SUPPORT: accept_prob is exact, the convex programs
+                                  were not run */
 
 #define GR_MAX_SUPPORT  256    /* largest top-k support (|V_0|) the LDS-resident path holds */
 #define GR_MAX_T        128    /* largest number of variables of one convex program */
@@ -70,8 +72,9 @@ int gr_destroy(gr_handle h);
  * p, q        [B, V] float32 row-major, each row a distribution (q before top-k).
  * n           number of i.i.d. drafts per row, 1..GR_MAX_N.
  * k           top-k applied to q (ties: lower token id); k <= 0 or k >= V means none.
- *             The support (tokens with q > 0 after top-k) must not exceed GR_MAX_SUPPORT,
- *             otherwise GR_EUNSUPPORTED.
+ *             A top-k above GR_MAX_SUPPORT and below V is refused with GR_EUNSUPPORTED.
+ *             Without top-k on V > GR_MAX_SUPPORT the support lives in a device workspace that
+ *             this call allocates or grows (136 bytes per token and row); V must stay below 2^24.
  * tol         the paper's error threshold tau (Alg. 1), >= 0: truncation sets are the fewest
  *             tokens by decreasing q with gamma_T <= tol (inner) / epsilon_T <= tol (outer).
  * accept_prob [B] float32 out: alpha* (Thm 3.1).       status [B] int32 out: GR_ROW_*.
@@ -106,6 +109,12 @@ int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_giv
  * support, h_size, iterations: [B] int32.  Any pointer may be NULL. */
 int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
                      int* support, int* h_size, int* iterations, void* hip_stream);
+
+/* One row of the policy object, the first `count` ranks (count <= the row's support): the same
+ * arrays as gr_policy_export.  This is the only export of a policy over a support above
+ * GR_MAX_SUPPORT (no top-k), whose rows hold up to V entries.  Device pointers, any may be NULL. */
+int gr_policy_export_row(gr_handle h, int row, int count, int* order, int* block, double* weight,
+                         double* rho, void* hip_stream);
 
 /* Work done by the last gr_solve, per row ([B] device arrays, either may be NULL):
  * evaluations = calls of the routed-mass evaluator (one per fixed-point or Newton step, plus

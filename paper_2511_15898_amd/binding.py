@@ -15,11 +15,11 @@ from .build import LIB_PATH
 GR_MAX_SUPPORT = 256
 GR_MAX_T = 128
 GR_MAX_N = 16
-GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
+GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD, GR_ROW_UNSOLVED = 0, 1, 2, 3, 4
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_verify", "gr_policy_slice", "gr_policy_export",
-           "gr_solve_stats", "gr_profile_read", "gr_strerror")
+           "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
 
@@ -54,6 +54,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
     lib.gr_solve_stats.argtypes = [vp] * 4
+    lib.gr_policy_export_row.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
     lib.gr_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.gr_strerror.argtypes = [ci]
@@ -147,6 +148,21 @@ def gr_profile_read(handle: int) -> dict:
     if rc != GR_OK:
         raise GrError(rc, "gr_profile_read")
     return {"select_ms": a.value, "solve_ms": b.value, "verify_ms": c.value, "steps": n.value}
+
+
+def gr_policy_export_row(handle: int, row: int, count: int, device, stream=None) -> dict:
+    """The first `count` ranks of one row's policy object (works for any support size)."""
+    out = {
+        "order": torch.empty(count, dtype=torch.int32, device=device),
+        "block": torch.empty(count, dtype=torch.int32, device=device),
+        "weight": torch.empty(count, dtype=torch.float64, device=device),
+        "rho": torch.empty(count, dtype=torch.float64, device=device),
+    }
+    rc = load_library().gr_policy_export_row(handle, row, count, *(out[k].data_ptr() for k in ("order", "block", "weight", "rho")),
+                                             _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_policy_export_row")
+    return out
 
 
 def gr_solve_stats(handle: int, B: int, device, stream=None) -> dict:

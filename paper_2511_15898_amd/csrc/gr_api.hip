@@ -23,6 +23,10 @@ struct gr_handle_s {
     bool profile = false;
     hipEvent_t ev[kProfSlots][5] = {};
     int prof_count = 0;
+    // full-vocabulary path: workspace (grown on demand by gr_solve) and the arguments of the last such solve
+    void* full_ws = nullptr; size_t full_ws_bytes = 0;
+    FullParams full = {};
+    bool full_mode = false;
     // last solve
     bool solved = false;
     const float* p = nullptr;
@@ -44,6 +48,7 @@ void free_all(gr_handle h) {
     void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
+    (void)hipFree(h->full_ws);
     if (h->profile)
         for (auto& slot : h->ev)
             for (auto& e : slot)
@@ -58,6 +63,32 @@ int choose_splits(int B, int V) {
     if (s > kMaxSplits) s = kMaxSplits;
     while (s > 1 && V / s < 4 * kSelTile) --s;
     return s;
+}
+
+// Carve the workspace of the full-vocabulary path out of one allocation (grown, never shrunk).
+int prepare_full(gr_handle h, int B, int V) {
+    const size_t vs = static_cast<size_t>(V) + 2, rows = static_cast<size_t>(B);
+    const size_t per_array_pad = 256;
+    const size_t need = rows * vs * kFullBytesPerToken + 40 * per_array_pad + rows * 3 * sizeof(int);
+    if (need > h->full_ws_bytes) {
+        (void)hipFree(h->full_ws);
+        h->full_ws = nullptr; h->full_ws_bytes = 0;
+        if (hipMalloc(&h->full_ws, need) != hipSuccess) { (void)hipGetLastError(); return GR_ENOMEM; }
+        h->full_ws_bytes = need;
+    }
+    unsigned char* cur = static_cast<unsigned char*>(h->full_ws);
+    auto take = [&](size_t bytes) { void* r = cur; cur += (bytes + per_array_pad - 1) / per_array_pad * per_array_pad; return r; };
+    FullParams& f = h->full;
+    const size_t cnt = rows * vs;
+    f.key0 = static_cast<unsigned long long*>(take(cnt * 8)); f.key1 = static_cast<unsigned long long*>(take(cnt * 8));
+    f.val0 = static_cast<int*>(take(cnt * 4)); f.val1 = static_cast<int*>(take(cnt * 4));
+    f.order = static_cast<int*>(take(cnt * 4)); f.byq = static_cast<int*>(take(cnt * 4));
+    double** dbl[] = {&f.pn, &f.qn, &f.P, &f.Q, &f.F, &f.G, &f.rho, &f.tgt, &f.weight, &f.rho_id};
+    for (double** d : dbl) *d = static_cast<double*>(take(cnt * 8));
+    int** ints[] = {&f.flag, &f.blk, &f.blo, &f.inT, &f.bcount, &f.rank_of};
+    for (int** d : ints) *d = static_cast<int*>(take(cnt * 4));
+    f.nblk = static_cast<int*>(take(rows * 4)); f.tcount = static_cast<int*>(take(rows * 8));
+    return GR_OK;
 }
 
 }  // namespace
@@ -107,8 +138,27 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     if (n < 1 || n > GR_MAX_N) return GR_EINVAL;
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
-    if (k_eff > kMaxSupport) return GR_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (k_eff > kMaxSupport) {
+        // no top-k on a vocabulary above GR_MAX_SUPPORT: the HBM-resident path
+        if (k_eff != V || V >= (1 << 24)) return GR_EUNSUPPORTED;
+        h->solved = false;
+        const int rc = prepare_full(h, B, V);
+        if (rc != GR_OK) return rc;
+        FullParams& f = h->full;
+        f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.max_T = h->max_T; f.max_iter = h->max_iter;
+        f.run_programs = 0;
+        f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
+        f.info = h->info; f.accept_prob = accept_prob; f.status = status;
+        mark(h, 0, stream);
+        mark(h, 1, stream);
+        launch_full_prologue(f, stream);
+        if (hipGetLastError() != hipSuccess) return GR_EHIP;
+        mark(h, 2, stream);
+        h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
+        return GR_OK;
+    }
+    h->full_mode = false;
     const int splits = choose_splits(B, V);
     int slice_len = (V + splits - 1) / splits;
     slice_len = (slice_len + 3) & ~3;
@@ -197,6 +247,7 @@ extern "C" int gr_policy_export(gr_handle h, int* order, int* block, double* wei
                                 int* support, int* h_size, int* iterations, void* hip_stream) {
     if (!h) return GR_EINVAL;
     if (!h->solved) return GR_ESTATE;
+    if (h->full_mode && (order || block || weight || rho)) return GR_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t cnt = static_cast<size_t>(h->B) * kMaxSupport;
     hipError_t e = hipSuccess;
@@ -211,6 +262,28 @@ extern "C" int gr_policy_export(gr_handle h, int* order, int* block, double* wei
         if (hipGetLastError() != hipSuccess) return GR_EHIP;
     }
     return GR_OK;
+}
+
+extern "C" int gr_policy_export_row(gr_handle h, int row, int count, int* order, int* block, double* weight,
+                                    double* rho, void* hip_stream) {
+    if (!h || row < 0 || count < 0) return GR_EINVAL;
+    if (!h->solved) return GR_ESTATE;
+    if (row >= h->B) return GR_EINVAL;
+    const size_t stride = h->full_mode ? static_cast<size_t>(h->V) + 2 : kMaxSupport;
+    if (static_cast<size_t>(count) > stride) return GR_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int* s_order = h->full_mode ? h->full.order : h->order;
+    const int* s_block = h->full_mode ? h->full.blk : h->block;
+    const double* s_weight = h->full_mode ? h->full.weight : h->weight;
+    const double* s_rho = h->full_mode ? h->full.rho : h->rho;
+    const size_t off = static_cast<size_t>(row) * stride, n = static_cast<size_t>(count);
+    hipError_t e = hipSuccess;
+    if (n == 0) return GR_OK;
+    if (order && e == hipSuccess) e = hipMemcpyAsync(order, s_order + off, n * sizeof(int), hipMemcpyDeviceToDevice, stream);
+    if (block && e == hipSuccess) e = hipMemcpyAsync(block, s_block + off, n * sizeof(int), hipMemcpyDeviceToDevice, stream);
+    if (weight && e == hipSuccess) e = hipMemcpyAsync(weight, s_weight + off, n * sizeof(double), hipMemcpyDeviceToDevice, stream);
+    if (rho && e == hipSuccess) e = hipMemcpyAsync(rho, s_rho + off, n * sizeof(double), hipMemcpyDeviceToDevice, stream);
+    return e == hipSuccess ? GR_OK : GR_EHIP;
 }
 
 extern "C" int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens, void* hip_stream) {
@@ -228,7 +301,7 @@ extern "C" const char* gr_strerror(int code) {
         case GR_ENOMEM: return "device allocation failed";
         case GR_ESTATE: return "no solved policy in this handle";
         case GR_EHIP: return "HIP runtime error";
-        case GR_EUNSUPPORTED: return "support larger than GR_MAX_SUPPORT";
+        case GR_EUNSUPPORTED: return "support larger than GR_MAX_SUPPORT with a top-k below V, or a dense export of a full-vocabulary policy";
         default: return "unknown error";
     }
 }

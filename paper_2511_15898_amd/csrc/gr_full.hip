@@ -1,0 +1,417 @@
+// Full-vocabulary support: steps 1 and 2 of the verifier (Sec. 5.1 ratio order and prefix psi, Sec. 6
+// H*, alpha*, outer residuals of Thm 6.2, records, truncation sets of Alg. 1) for a draft distribution
+// without top-k, where the support (up to V tokens) does not fit LDS.
+//
+// Every per-token array lives in a per-handle HBM workspace, row-major with stride V + 2; one
+// 256-thread workgroup works through a row.  The arithmetic that decides integers (prefix sums, F,
+// the running masses of the truncation sets) is the same sequential fp64 arithmetic as on the
+// LDS-resident path.
+#include "gr_internal.h"
+
+namespace gr {
+
+namespace {
+
+struct SortLds {
+    int hist[256]; int base[256]; int wcnt[kWaves][256]; int flag;
+};
+
+// Stable least-significant-digit radix sort of `count` (key, value) pairs of one row, ascending in the
+// 64-bit key, 8 bits per pass, between the buffer pairs (k0, v0) and (k1, v1).  Returns 0 or 1: the pair
+// that holds the result.  Passes whose digit is the same for every key are skipped.  All threads call.
+__device__ int block_radix_sort(unsigned long long* k0, int* v0, unsigned long long* k1, int* v1, int count,
+                                SortLds& S) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    int cur = 0;
+    for (int shift = 0; shift < 64; shift += 8) {
+        const unsigned long long* ks = cur ? k1 : k0; const int* vs = cur ? v1 : v0;
+        unsigned long long* kd = cur ? k0 : k1; int* vd = cur ? v0 : v1;
+        S.hist[tid] = 0;
+        for (int w = 0; w < kWaves; ++w) S.wcnt[w][tid] = 0;
+        if (tid == 0) S.flag = 0;
+        __syncthreads();
+        for (int i = tid; i < count; i += kThreads) atomicAdd(&S.hist[static_cast<int>((ks[i] >> shift) & 255ull)], 1);
+        __syncthreads();
+        if (S.hist[tid] == count) S.flag = 1;
+        if (wv == 0) {
+            // exclusive scan of the histogram: lane l owns digits 4l .. 4l+3
+            int c[4]; int tot = 0;
+            for (int j = 0; j < 4; ++j) { c[j] = S.hist[4 * lane + j]; tot += c[j]; }
+            int incl = tot;
+            for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+            int run = incl - tot;
+            for (int j = 0; j < 4; ++j) { S.base[4 * lane + j] = run; run += c[j]; }
+        }
+        __syncthreads();
+        if (S.flag) { __syncthreads(); continue; }
+        const int ntiles = (count + kThreads - 1) / kThreads;
+        unsigned long long knext = 0ull; int vnext = 0;
+        if (tid < count) { knext = ks[tid]; vnext = vs[tid]; }
+        for (int t = 0; t < ntiles; ++t) {
+            const int i = t * kThreads + tid;
+            const bool valid = i < count;
+            const unsigned long long key = knext; const int val = vnext;
+            if (i + kThreads < count) { knext = ks[i + kThreads]; vnext = vs[i + kThreads]; }
+            const int d = static_cast<int>((key >> shift) & 255ull);
+            // lanes of this wave that hold the same digit
+            unsigned long long peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (d >> b) & 1;
+                const unsigned long long m = __ballot(valid && bit);
+                peers &= bit ? m : ~m;
+            }
+            const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+            if (valid && rank == 0) S.wcnt[wv][d] = __popcll(peers);
+            __syncthreads();
+            if (valid) {
+                int off = S.base[d] + rank;
+                for (int w = 0; w < wv; ++w) off += S.wcnt[w][d];
+                kd[off] = key; vd[off] = val;
+            }
+            __syncthreads();
+            {
+                int add = 0;
+                for (int w = 0; w < kWaves; ++w) { add += S.wcnt[w][tid]; S.wcnt[w][tid] = 0; }
+                S.base[tid] += add;
+            }
+            __syncthreads();
+        }
+        cur ^= 1;
+        __syncthreads();
+    }
+    return cur;
+}
+
+// Exclusive suffix minimum over the 256 threads: min of v over the threads after this one (1e300 for
+// the last); *total = min over all.  buf0, buf1: LDS double[256].
+__device__ double block_suffix_min_excl(double v, double* buf0, double* buf1, double* total) {
+    const int tid = threadIdx.x;
+    double* src = buf0; double* dst = buf1;
+    src[tid] = v;
+    __syncthreads();
+    for (int o = 1; o < kThreads; o <<= 1) {
+        dst[tid] = (tid + o < kThreads) ? fmin(src[tid], src[tid + o]) : src[tid];
+        __syncthreads();
+        double* t = src; src = dst; dst = t;
+    }
+    const double excl = (tid + 1 < kThreads) ? src[tid + 1] : 1e300;
+    *total = src[0];
+    __syncthreads();
+    return excl;
+}
+
+// Exclusive prefix sum over the 256 threads; *total = sum over all.  buf0, buf1: LDS int[256].
+__device__ int block_prefix_sum_excl(int v, int* buf0, int* buf1, int* total) {
+    const int tid = threadIdx.x;
+    int* src = buf0; int* dst = buf1;
+    src[tid] = v;
+    __syncthreads();
+    for (int o = 1; o < kThreads; o <<= 1) {
+        dst[tid] = (tid >= o) ? src[tid] + src[tid - o] : src[tid];
+        __syncthreads();
+        int* t = src; src = dst; dst = t;
+    }
+    const int excl = src[tid] - v;
+    *total = src[kThreads - 1];
+    __syncthreads();
+    return excl;
+}
+
+__device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot) {
+    RowInfo info;
+    info.support = 0; info.h = 0; info.status = GR_ROW_BAD; info.iterations = 0;
+    info.alpha_star = __longlong_as_double(0x7ff8000000000000ll);
+    info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0;
+    fp.info[row] = info;
+    fp.accept_prob[row] = __uint_as_float(0x7fc00000u);
+    fp.status[row] = GR_ROW_BAD;
+}
+
+}  // namespace
+
+// ---- kernel 1: row sums and validity, the support in token order, sort by decreasing q/p (ties by id).
+// The sort key is the correctly rounded float64 quotient q/p: for float32 inputs two different
+// ratios differ by at least 2^-48 relative, so their quotients differ and keep their order, and equal
+// ratios give equal quotients -- the same order as the exact cross-product comparison (Sec. 5.1).
+__global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
+    __shared__ SortLds S;
+    __shared__ double red[kWaves];
+    __shared__ int wtot[kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
+    const int V = fp.V;
+    const size_t vs = static_cast<size_t>(V) + 2;
+    const float* pr = fp.p + static_cast<size_t>(row) * V;
+    const float* qr = fp.q + static_cast<size_t>(row) * V;
+    unsigned long long* k0 = fp.key0 + row * vs; unsigned long long* k1 = fp.key1 + row * vs;
+    int* v0 = fp.val0 + row * vs; int* v1 = fp.val1 + row * vs;
+
+    double ps = 0.0, qs = 0.0; int bad = 0;
+    for (int i = tid; i < V; i += kThreads) {
+        const float pv = pr[i], qv = qr[i];
+        bad |= !(qv >= 0.f) | !(pv >= 0.f);
+        ps += static_cast<double>(pv); qs += static_cast<double>(qv);
+    }
+    const double ptot = block_sum(ps, red);
+    const double qtot = block_sum(qs, red);
+    const int anybad = block_sum_i(bad, red);
+    if (anybad || !(fabs(ptot - 1.0) <= 1e-3) || !(fabs(qtot - 1.0) <= 1e-3)) {
+        if (tid == 0) mark_bad(fp, row, ptot, qtot);
+        return;
+    }
+    // the support (q > 0) in token order, with its keys
+    int kk = 0;
+    for (int t0 = 0; t0 < V; t0 += kThreads) {
+        const int i = t0 + tid;
+        const float qv = i < V ? qr[i] : 0.f;
+        const bool in = qv > 0.f;
+        const unsigned long long mask = __ballot(in);
+        if (lane == 0) wtot[wv] = __popcll(mask);
+        __syncthreads();
+        int off = kk + __popcll(mask & ((1ull << lane) - 1ull));
+        int tile_total = 0;
+        for (int w = 0; w < kWaves; ++w) { if (w < wv) off += wtot[w]; tile_total += wtot[w]; }
+        if (in) {
+            const double ratio = static_cast<double>(qv) / static_cast<double>(pr[i]);   // p = 0 gives +inf: first
+            k0[off] = ~static_cast<unsigned long long>(__double_as_longlong(ratio));
+            v0[off] = i;
+        }
+        kk += tile_total;
+        __syncthreads();
+    }
+    if (kk == 0) {
+        if (tid == 0) mark_bad(fp, row, ptot, qtot);
+        return;
+    }
+    __syncthreads();
+    const int res = block_radix_sort(k0, v0, k1, v1, kk, S);
+    const int* sorted = res ? v1 : v0;
+    int* order = fp.order + row * vs;
+    for (int r = tid; r < kk; r += kThreads) order[r] = sorted[r];
+    if (tid == 0) {
+        RowInfo info;
+        info.support = kk; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
+        info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0;
+        fp.info[row] = info;
+    }
+}
+
+// ---- kernel 2: prefix sums in the order, F, H*, alpha*, suffix minima, residuals, records, blocks.
+__global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
+    constexpr int kTile = 1024;
+    __shared__ double xin[2][kTile];
+    __shared__ double xout[2][kTile + 1];
+    __shared__ double red[kWaves];
+    __shared__ double dbuf[2][kThreads];
+    __shared__ int ibuf[2][kThreads];
+    const int tid = threadIdx.x, wv = tid >> 6, row = blockIdx.x;
+    const int V = fp.V, n = fp.n;
+    const size_t vs = static_cast<size_t>(V) + 2;
+    RowInfo info = fp.info[row];
+    if (info.status == GR_ROW_BAD) return;
+    const int kk = info.support;
+    const float* pr = fp.p + static_cast<size_t>(row) * V;
+    const float* qr = fp.q + static_cast<size_t>(row) * V;
+    const int* order = fp.order + row * vs;
+    double* pn = fp.pn + row * vs; double* qn = fp.qn + row * vs;
+    double* P = fp.P + row * vs; double* Q = fp.Q + row * vs; double* F = fp.F + row * vs; double* G = fp.G + row * vs;
+    double* rho = fp.rho + row * vs; double* tgt = fp.tgt + row * vs;
+    int* flag = fp.flag + row * vs; int* blk = fp.blk + row * vs; int* blo = fp.blo + row * vs;
+    int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
+
+    for (int r = tid; r < kk; r += kThreads) {
+        const int id = order[r];
+        pn[r] = static_cast<double>(pr[id]) / info.p_total;
+        qn[r] = static_cast<double>(qr[id]);                     // raw q for now
+        inT[r] = 0;
+    }
+    if (tid == 0) { P[0] = 0.0; Q[0] = 0.0; }
+    __syncthreads();
+    // sequential prefix sums, a tile at a time through LDS (wave 0: p, wave 1: q)
+    double carry_p = 0.0, carry_q = 0.0;
+    for (int t0 = 0; t0 < kk; t0 += kTile) {
+        const int cnt = min(kTile, kk - t0);
+        for (int i = tid; i < cnt; i += kThreads) { xin[0][i] = pn[t0 + i]; xin[1][i] = qn[t0 + i]; }
+        __syncthreads();
+        if (wv == 0) wave_sequential_scan(xin[0], xout[0], cnt, carry_p);
+        if (wv == 1) wave_sequential_scan(xin[1], xout[1], cnt, carry_q);
+        __syncthreads();
+        for (int i = tid; i < cnt; i += kThreads) { P[t0 + i + 1] = xout[0][i + 1]; Q[t0 + i + 1] = xout[1][i + 1]; }
+        carry_p = xout[0][cnt]; carry_q = xout[1][cnt];
+        __syncthreads();
+    }
+    const double stot = carry_q;
+    {
+#pragma clang fp contract(off)
+        for (int m = tid; m <= kk; m += kThreads) {
+            const double Qm = Q[m] / stot;
+            Q[m] = Qm;
+            F[m] = (m == 0) ? 0.0 : P[m] - ipow(Qm, n);
+            if (m < kk) qn[m] = qn[m] / stot;
+        }
+    }
+    __syncthreads();
+    // H*: the smallest minimising prefix
+    double fmin_local = 1e300;
+    for (int m = tid; m <= kk; m += kThreads) fmin_local = fmin(fmin_local, F[m]);
+    const double Fmin = block_min(fmin_local, red);
+    double hcand = 1e18;
+    for (int m = tid; m <= kk; m += kThreads) if (F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
+    const int h = static_cast<int>(block_min(hcand, red));
+    // G = suffix minima of F over m = 0..kk, tiles of 1024 from the top down (4 consecutive entries per thread)
+    {
+        double later = 1e300;                                   // min of F over the tiles above
+        const int ntile = (kk + 1 + kTile - 1) / kTile;
+        for (int t = ntile - 1; t >= 0; --t) {
+            const int m0 = t * kTile + tid * 4;
+            double a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] = (m0 + j <= kk) ? F[m0 + j] : 1e300;
+            double s[4];
+            s[3] = a[3]; s[2] = fmin(a[2], s[3]); s[1] = fmin(a[1], s[2]); s[0] = fmin(a[0], s[1]);
+            double total;
+            const double after = fmin(block_suffix_min_excl(s[0], dbuf[0], dbuf[1], &total), later);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (m0 + j <= kk) G[m0 + j] = fmin(s[j], after);
+            later = fmin(later, total);
+        }
+    }
+    __syncthreads();
+    // residuals, targets, records (F(m) <= G(m+1) for m >= h; m = kk always)
+    for (int m = tid; m <= kk; m += kThreads) {
+        flag[m] = (m >= h && (m == kk || F[m] <= G[m + 1])) ? 1 : 0;
+        if (m < kk) {
+            const double r = (m >= h) ? G[m + 1] - G[m] : 0.0;
+            rho[m] = r; tgt[m] = pn[m] - r;
+        }
+    }
+    __syncthreads();
+    // inclusive count of records -> block of each token outside H*, record positions
+    int nrec = 0;
+    {
+        const int ntile = (kk + 1 + kTile - 1) / kTile;
+        for (int t = 0; t < ntile; ++t) {
+            const int m0 = t * kTile + tid * 4;
+            int f[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f[j] = (m0 + j <= kk) ? flag[m0 + j] : 0;
+            int total;
+            int run = nrec + block_prefix_sum_excl(f[0] + f[1] + f[2] + f[3], ibuf[0], ibuf[1], &total);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + j;
+                if (m <= kk) {
+                    run += f[j];
+                    if (f[j]) blo[run] = m;                     // record number `run` (1-based) sits at rank m
+                    if (m < kk) blk[m] = (m >= h) ? run : 0;    // token m lies after record `run`
+                }
+            }
+            nrec += total;
+        }
+    }
+    __syncthreads();
+    for (int b = tid; b <= nrec; b += kThreads) bcount[b] = 0;
+    if (tid == 0) {
+        info.h = h;
+        info.alpha_star = 1.0 + F[h];
+        info.res_total = -F[h];
+        fp.info[row] = info;
+        fp.nblk[row] = nrec - 1;
+        fp.accept_prob[row] = static_cast<float>(1.0 + F[h]);
+    }
+}
+
+// ---- kernel 3: truncation sets (Alg. 1: fewest tokens by decreasing q with gamma_T <= tau inside H*,
+// epsilon_T <= tau outside), size of every program, row status.
+__global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
+    __shared__ SortLds S;
+    __shared__ int cnt_in, cnt_out, act_in, capped;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
+    const int V = fp.V, n = fp.n;
+    const size_t vs = static_cast<size_t>(V) + 2;
+    const RowInfo info = fp.info[row];
+    if (info.status == GR_ROW_BAD) return;
+    const int kk = info.support, h = info.h;
+    const float* qr = fp.q + static_cast<size_t>(row) * V;
+    const int* order = fp.order + row * vs;
+    unsigned long long* k0 = fp.key0 + row * vs; unsigned long long* k1 = fp.key1 + row * vs;
+    int* v0 = fp.val0 + row * vs; int* v1 = fp.val1 + row * vs;
+    int* byq = fp.byq + row * vs;
+    const double* qn = fp.qn + row * vs; const double* Q = fp.Q + row * vs; const double* tgt = fp.tgt + row * vs;
+    const int* blk = fp.blk + row * vs; const int* blo = fp.blo + row * vs;
+    int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
+
+    // ranks by (inside H* first, decreasing q, token id)
+    for (int r = tid; r < kk; r += kThreads) {
+        const int id = order[r];
+        const unsigned long long qb = static_cast<unsigned long long>(~__float_as_uint(qr[id]));
+        k0[r] = (static_cast<unsigned long long>(r < h ? 0 : 1) << 56) | (qb << 24) | static_cast<unsigned long long>(id);
+        v0[r] = r;
+    }
+    if (tid == 0) { cnt_in = 0; cnt_out = 0; act_in = 0; capped = 0; }
+    __syncthreads();
+    const int res = block_radix_sort(k0, v0, k1, v1, kk, S);
+    const int* sorted = res ? v1 : v0;
+    for (int i = tid; i < kk; i += kThreads) byq[i] = sorted[i];
+    __syncthreads();
+    const double Qh = Q[h];
+    // wave 0 walks H* by decreasing q, wave 1 the other tokens: a token joins T while the mass before
+    // it leaves more than tau (running sums added one after the other, as a sequential loop would)
+    if (wv < 2) {
+#pragma clang fp contract(off)
+        const int first = wv == 0 ? 0 : h;
+        const int len = wv == 0 ? h : kk - h;
+        const double bound = wv == 0 ? ipow(Qh, n) : 1.0;
+        double acc = wv == 0 ? 0.0 : Qh;
+        int taken = 0, active = 0;
+        bool done = false;
+        for (int base = 0; base < len && !done; base += 64) {
+            const bool valid = base + lane < len;
+            const int r = valid ? byq[first + base + lane] : 0;
+            const double mine = valid ? qn[r] : 0.0;
+            double before = 0.0;
+#pragma unroll
+            for (int j = 0; j < 64; ++j) {
+                if (lane == j) before = acc;
+                acc = acc + __shfl(mine, j);
+            }
+            const double bn = (before > 0.0) ? ipow(before, n) : 0.0;
+            const bool in = valid && (bound - bn > fp.tau);
+            const unsigned long long out_mask = __ballot(valid && !in);
+            int upto = 64;                                       // lanes below `upto` join T
+            if (out_mask) { upto = __ffsll(static_cast<long long>(out_mask)) - 1; done = true; }
+            const bool join = valid && lane < upto;
+            if (join) inT[r] = 1;
+            const bool act = join && tgt[r] > 0.0;
+            taken += __popcll(__ballot(join));
+            active += __popcll(__ballot(act));
+            if (wv == 1 && act) {
+                const int b = blk[r];
+                if (blo[b + 1] - blo[b] >= 2) {
+                    const int old = atomicAdd(&bcount[b], 1);
+                    if (old + 1 > fp.max_T) capped = 1;
+                }
+            }
+        }
+        if (lane == 0) {
+            if (wv == 0) { cnt_in = taken; act_in = active; } else { cnt_out = taken; }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int status = (act_in > fp.max_T || capped) ? GR_ROW_TRUNC_CAP : (fp.run_programs ? GR_ROW_OK : GR_ROW_UNSOLVED);
+        fp.tcount[2 * row] = cnt_in; fp.tcount[2 * row + 1] = cnt_out;
+        RowInfo out = info;
+        out.status = status;
+        fp.info[row] = out;
+        fp.status[row] = status;
+    }
+}
+
+void launch_full_prologue(const FullParams& fp, hipStream_t stream) {
+    hipLaunchKernelGGL(full_order_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);
+    hipLaunchKernelGGL(full_scan_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);
+    hipLaunchKernelGGL(full_trunc_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);
+}
+
+}  // namespace gr

@@ -47,6 +47,27 @@ struct SolveParams {
     float* accept_prob; int* status;  // caller's outputs [B]
 };
 
+// Workspace and arguments of the full-vocabulary path (no top-k).  Per-token arrays are row-major with
+// stride V + 2; P, Q, F, G hold kk + 1 entries per row (prefix index 0..kk), blo the record positions.
+struct FullParams {
+    const float* p; const float* q;
+    int B, V, n, max_T, max_iter;
+    int run_programs;  // 0: rows whose programs fit are marked GR_ROW_UNSOLVED instead of being solved
+    double tau, rel_tol;
+    unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
+    int* order;        // token ids by decreasing q/p
+    int* byq;          // ranks by (inside H* first, decreasing q, token id)
+    double* pn; double* qn; double* P; double* Q; double* F; double* G; double* rho; double* tgt; double* weight;
+    int* flag; int* blk; int* blo; int* inT; int* bcount;
+    int* rank_of;      // [B, V + 2] rank of each token id, -1 outside the support
+    double* rho_id;    // [B, V + 2] residual p(i) - p_i by token id (0 inside H*)
+    int* nblk;         // [B] number of outer blocks
+    int* tcount;       // [B, 2] sizes of the two truncation sets
+    RowInfo* info; float* accept_prob; int* status;
+};
+constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 9 * 8 + 5 * 4 + 4 + 8;
+
+void launch_full_prologue(const FullParams& fp, hipStream_t stream);
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
                    hipStream_t stream);
@@ -154,6 +175,44 @@ __device__ __forceinline__ int block_sum_i(int v, double* red) {
     __syncthreads();
     return t;
 }
+
+// Arithmetic whose rounding must not depend on the compiler: no contraction into fused multiply-adds.
+#pragma clang fp contract(off)
+__device__ __forceinline__ double ipow(double x, int n) {
+    double r = x;
+    for (int i = 1; i < n; ++i) r = r * x;
+    return r;
+}
+
+// a^n - (a-d)^n without cancellation: d * sum_{i<n} a^(n-1-i) b^i with b = a - d, by the
+// recurrence s_i = a s_{i-1} + b^i (all terms nonnegative).
+__device__ __forceinline__ double pow_diff(double a, double d, int n) {
+    const double b = a - d;
+    double s = 1.0, bp = 1.0;
+    for (int i = 1; i < n; ++i) { bp = bp * b; s = s * a + bp; }
+    return d * s;
+}
+
+// Inclusive prefix sums of x[0..count) in index order, added one after the other exactly as a
+// sequential loop would (so the rounding does not depend on the machine), but held in the
+// registers of one wave: lane j of round r owns element 64 r + j, the running sum travels through
+// v_readlane.  Called by one whole wave; out[0] = start, out[i + 1] = start + x[0] + ... + x[i].
+__device__ __forceinline__ void wave_sequential_scan(const double* x, double* out, int count, double start) {
+    const int lane = threadIdx.x & 63;
+    double acc = start;
+    if (lane == 0) out[0] = start;
+    for (int base = 0; base < count; base += 64) {
+        const double mine = (base + lane < count) ? x[base + lane] : 0.0;
+        double res = 0.0;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            acc = acc + __shfl(mine, j);
+            if (lane == j) res = acc;
+        }
+        if (base + lane < count) out[base + lane + 1] = res;
+    }
+}
+#pragma clang fp contract(fast)
 
 // Candidate key: larger q first, ties to the lower token id.  q >= 0, so its bit pattern is
 // monotone; the low word holds ~id so that a plain 64-bit compare gives the order.

@@ -68,42 +68,6 @@ struct Lds {
     } u;
 };
 
-#pragma clang fp contract(off)
-__device__ __forceinline__ double ipow(double x, int n) {
-    double r = x;
-    for (int i = 1; i < n; ++i) r = r * x;
-    return r;
-}
-
-// a^n - (a-d)^n without cancellation: d * sum_{i<n} a^(n-1-i) b^i with b = a - d, by the
-// recurrence s_i = a s_{i-1} + b^i (all terms nonnegative).
-__device__ __forceinline__ double pow_diff(double a, double d, int n) {
-    const double b = a - d;
-    double s = 1.0, bp = 1.0;
-    for (int i = 1; i < n; ++i) { bp = bp * b; s = s * a + bp; }
-    return d * s;
-}
-
-// Inclusive prefix sums of x[0..count) in index order, added one after the other exactly as a
-// sequential loop would (so the rounding does not depend on the machine), but held in the
-// registers of one wave: lane j of round r owns element 64 r + j, the running sum travels through
-// v_readlane.  Called by one whole wave; out[0] = start, out[i + 1] = start + x[0] + ... + x[i].
-__device__ __forceinline__ void wave_sequential_scan(const double* x, double* out, int count, double start) {
-    const int lane = threadIdx.x & 63;
-    double acc = start;
-    if (lane == 0) out[0] = start;
-    for (int base = 0; base < count; base += 64) {
-        const double mine = (base + lane < count) ? x[base + lane] : 0.0;
-        double res = 0.0;
-#pragma unroll
-        for (int j = 0; j < 64; ++j) {
-            acc = acc + __shfl(mine, j);
-            if (lane == j) res = acc;
-        }
-        if (base + lane < count) out[base + lane + 1] = res;
-    }
-}
-#pragma clang fp contract(fast)
 
 // e^{-y} for y >= 0: Cody-Waite reduction by ln 2 and a degree-12 Taylor polynomial on
 // |r| <= ln(2)/2 (relative error below 1e-15; underflows to 0 beyond y = 708).
