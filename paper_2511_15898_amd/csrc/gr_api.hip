@@ -65,6 +65,19 @@ int choose_splits(int B, int V) {
     return s;
 }
 
+PolicyView policy_view(gr_handle h) {
+    PolicyView pv;
+    if (h->full_mode) {
+        const FullParams& f = h->full;
+        pv.order = f.order; pv.block = f.blk; pv.weight = f.weight; pv.rho = f.rho;
+        pv.rank_of = f.rank_of; pv.rho_id = f.rho_id; pv.stride = static_cast<size_t>(h->V) + 2;
+    } else {
+        pv.order = h->order; pv.block = h->block; pv.weight = h->weight; pv.rho = h->rho;
+        pv.rank_of = nullptr; pv.rho_id = nullptr; pv.stride = kMaxSupport;
+    }
+    return pv;
+}
+
 // Carve the workspace of the full-vocabulary path out of one allocation (grown, never shrunk).
 int prepare_full(gr_handle h, int B, int V) {
     const size_t vs = static_cast<size_t>(V) + 2, rows = static_cast<size_t>(B);
@@ -147,13 +160,14 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         if (rc != GR_OK) return rc;
         FullParams& f = h->full;
         f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.max_T = h->max_T; f.max_iter = h->max_iter;
-        f.run_programs = 0;
+        f.run_programs = 1;
         f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
         f.info = h->info; f.accept_prob = accept_prob; f.status = status;
         mark(h, 0, stream);
         mark(h, 1, stream);
         launch_full_prologue(f, stream);
         if (hipGetLastError() != hipSuccess) return GR_EHIP;
+        if (launch_full_programs(f, stream) != hipSuccess) return GR_EHIP;
         mark(h, 2, stream);
         h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
         return GR_OK;
@@ -187,8 +201,7 @@ extern "C" int gr_verify(gr_handle h, const int* drafts, const float* uniforms, 
     if (!h->solved) return GR_ESTATE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     mark(h, 3, stream);
-    launch_verify(h->p, h->B, h->V, h->n, h->order, h->block, h->weight, h->rho, h->info, drafts, uniforms,
-                  token, accepted, stream);
+    launch_verify(h->p, h->B, h->V, h->n, policy_view(h), h->info, drafts, uniforms, token, accepted, stream);
     if (hipGetLastError() != hipSuccess) return GR_EHIP;
     mark(h, 4, stream);
     if (h->profile && h->prof_count < kProfSlots) ++h->prof_count;
@@ -219,8 +232,8 @@ extern "C" int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float*
                                void* hip_stream) {
     if (!h || !drafts || !pi || !accept_given_drafts) return GR_EINVAL;
     if (!h->solved) return GR_ESTATE;
-    launch_slice(h->p, h->B, h->V, h->n, h->order, h->block, h->weight, h->rho, h->info, drafts, pi,
-                 accept_given_drafts, static_cast<hipStream_t>(hip_stream));
+    launch_slice(h->p, h->B, h->V, h->n, policy_view(h), h->info, drafts, pi, accept_given_drafts,
+                 static_cast<hipStream_t>(hip_stream));
     return hipGetLastError() == hipSuccess ? GR_OK : GR_EHIP;
 }
 

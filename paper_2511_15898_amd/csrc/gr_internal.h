@@ -72,12 +72,19 @@ void launch_select(const float* p, const float* q, int B, int V, int k, int spli
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
                    hipStream_t stream);
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream);
-void launch_verify(const float* p, int B, int V, int n, const int* order, const int* block,
-                   const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+// The policy object as the verify and slice kernels read it.  Top-k policies: arrays [B, stride] with
+// stride = kMaxSupport, rank_of = rho_id = nullptr.  Full-vocabulary policies: stride = V + 2, plus the
+// rank of every token id and the residuals by token id.
+struct PolicyView {
+    const int* order; const int* block; const double* weight; const double* rho;
+    const int* rank_of; const double* rho_id;
+    size_t stride;
+};
+void launch_verify(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                    const float* uniforms, int* token, unsigned char* accepted, hipStream_t stream);
-void launch_slice(const float* p, int B, int V, int n, const int* order, const int* block,
-                  const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+void launch_slice(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                   float* pi, float* accept_given, hipStream_t stream);
+hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream);
 hipError_t solve_kernel_setup();
 
 // ---------------------------------------------------------------- device helpers

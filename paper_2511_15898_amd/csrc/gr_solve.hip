@@ -1082,10 +1082,166 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
 }
 
+// ---- full-vocabulary policies: the convex programs of a row whose steps 1-2 were done in HBM.
+// Start weights of every support token, the dense per-token arrays the verify kernel reads, then the
+// inner program over T inside H* and one outer program per block that holds two or more active
+// tokens of T -- the same programs, in the same arithmetic, as the LDS-resident path.
+template <int D>
+__global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    Lds& L = *reinterpret_cast<Lds*>(lds_raw);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
+    const int n = fp.n, V = fp.V;
+    const size_t vs = static_cast<size_t>(V) + 2;
+    RowInfo info = fp.info[row];
+    if (info.status == GR_ROW_BAD) return;
+    const int kk = info.support, h = info.h;
+    const float* pr = fp.p + static_cast<size_t>(row) * V;
+    const float* qr = fp.q + static_cast<size_t>(row) * V;
+    const int* order = fp.order + row * vs; const int* byq = fp.byq + row * vs;
+    const double* qn = fp.qn + row * vs; const double* Q = fp.Q + row * vs; const double* F = fp.F + row * vs;
+    const double* rho = fp.rho + row * vs; const double* tgt = fp.tgt + row * vs;
+    const int* blk = fp.blk + row * vs; const int* blo = fp.blo + row * vs; const int* inT = fp.inT + row * vs;
+    const int* bcount = fp.bcount + row * vs;
+    double* weight = fp.weight + row * vs; double* rho_id = fp.rho_id + row * vs; int* rank_of = fp.rank_of + row * vs;
+    const double Fh = F[h];
+
+    // tokens outside the support keep all of p as residual; then the support by rank
+    for (int i = tid; i < V; i += kST) {
+        if (!(qr[i] > 0.f)) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
+    }
+    for (int r = tid; r < kk; r += kST) {
+        const int hi = (r < h) ? h : blo[blk[r] + 1];
+        const double top = Q[hi];
+        const double gauge = (r < h) ? ipow(top, n) / (-Fh) : 1.0;
+        const double t = tgt[r];
+        weight[r] = (t > 0.0) ? gauge * t / pow_diff(top, qn[r], n) : 0.0;
+        const int id = order[r];
+        rank_of[id] = r; rho_id[id] = rho[r];
+    }
+    if (info.status != GR_ROW_OK) return;
+    if (tid == 0) L.work = 0.0;
+    __syncthreads();
+
+    int status = GR_ROW_OK, evals = 0;
+    // ---- inner program: T inside H* is the first tcount[0] entries of byq, already by decreasing q
+    if (h > 0) {
+        const int c_in = fp.tcount[2 * row];
+        int m = 0;
+        double ctx_part = 0.0;
+        for (int base = 0; base < c_in; base += kST) {
+            const int i = base + tid;
+            const int r = i < c_in ? byq[i] : -1;
+            const double t = r >= 0 ? tgt[r] : 0.0;
+            const bool on = r >= 0 && t > 0.0;
+            if (r >= 0 && !on) ctx_part += qn[r];
+            const unsigned long long mask = __ballot(on);
+            if (lane == 0) L.hist[wv] = __popcll(mask);
+            __syncthreads();
+            int slot = m + __popcll(mask & ((1ull << lane) - 1ull));
+            int tile_total = 0;
+            for (int w = 0; w < kSW; ++w) { if (w < wv) slot += L.hist[w]; tile_total += L.hist[w]; }
+            if (on && slot < kMaxT) { L.apos[slot] = r; L.aq[slot] = qn[r]; L.at[slot] = t; L.aal[slot] = log(weight[r]); }
+            m += tile_total;
+            __syncthreads();
+        }
+        const double ctx = block_sum<kSW>(ctx_part, L.red);
+        if (m > 0 && m <= kMaxT) {
+            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
+            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+            const double mass = ipow(ctx + qa, n);
+            const double scale = mass / (ta - Fh);
+            const double slack_target = -Fh * scale;
+            if (tid < m) L.at[tid] *= scale;
+            __syncthreads();
+            const int rc = solve_program<D>(L, m, n, ctx, 1, slack_target, fp.rel_tol, fp.max_iter, &evals);
+            if (rc != 0) status = GR_ROW_ITER_CAP;
+            if (tid < m) weight[L.apos[tid]] = exp(L.aal[tid]);
+            __syncthreads();
+        }
+    }
+    // ---- outer programs: windows of kST blocks, those with two or more active tokens of T
+    const int nblk = fp.nblk[row];
+    for (int b0 = 1; b0 <= nblk; b0 += kST) {
+        const int bme = b0 + tid;
+        const bool need = bme <= nblk && bcount[bme] >= 2;
+        const unsigned long long nmask = __ballot(need);
+        if (lane == 0) L.hist[wv] = __popcll(nmask);
+        __syncthreads();
+        int pslot = __popcll(nmask & ((1ull << lane) - 1ull));
+        int nprog = 0;
+        for (int w = 0; w < kSW; ++w) { if (w < wv) pslot += L.hist[w]; nprog += L.hist[w]; }
+        if (need) L.flag[pslot] = bme;                      // nprog <= kST <= KS + 2
+        __syncthreads();
+        for (int pi = 0; pi < nprog; ++pi) {
+            const int b = L.flag[pi];
+            const int lo = blo[b], hi = blo[b + 1];
+            // active tokens of the block, by rank
+            int m = 0;
+            for (int base = lo; base < hi; base += kST) {
+                const int r = base + tid;
+                const bool on = r < hi && inT[r] && tgt[r] > 0.0;
+                const unsigned long long mask = __ballot(on);
+                if (lane == 0) L.hist[wv] = __popcll(mask);
+                __syncthreads();
+                int slot = m + __popcll(mask & ((1ull << lane) - 1ull));
+                int tile_total = 0;
+                for (int w = 0; w < kSW; ++w) { if (w < wv) slot += L.hist[w]; tile_total += L.hist[w]; }
+                if (on && slot < kMaxT) { L.adeg[slot] = r; L.af[slot] = qn[r]; L.aR[slot] = tgt[r]; L.aw[slot] = log(weight[r]); }
+                m += tile_total;
+                __syncthreads();
+            }
+            if (m < 2 || m > kMaxT) continue;               // cannot happen for a row with status OK
+            // by decreasing q (the evaluator takes its heavy tokens first), ties by rank
+            if (tid < m) {
+                const double qa = L.af[tid];
+                int pos = 0;
+                for (int j = 0; j < m; ++j) pos += (L.af[j] > qa) || (L.af[j] == qa && j < tid);
+                L.apos[pos] = L.adeg[tid]; L.aq[pos] = qa; L.at[pos] = L.aR[tid]; L.aal[pos] = L.aw[tid];
+            }
+            __syncthreads();
+            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
+            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+            const double ctx = Q[lo];
+            const double scale = pow_diff(ctx + qa, qa, n) / ta;
+            const double w0sum = block_sum<kSW>(tid < m ? exp(L.aal[tid]) : 0.0, L.red);
+            if (tid < m) L.at[tid] *= scale;
+            __syncthreads();
+            const int rc = solve_program<D>(L, m, n, ctx, 0, 0.0, fp.rel_tol, fp.max_iter, &evals);
+            if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
+            const double wvv = (tid < m) ? exp(L.aal[tid]) : 0.0;
+            const double wsum = block_sum<kSW>(wvv, L.red);
+            if (tid < m) weight[L.apos[tid]] = wvv * (w0sum / wsum);
+            __syncthreads();
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        info.status = status; info.iterations = evals; info.node_tokens = L.work;
+        fp.info[row] = info;
+        fp.status[row] = status;
+    }
+}
+
+hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream) {
+    const dim3 grid(fp.B), block(kST);
+    if (fp.n <= 2) hipLaunchKernelGGL(full_programs_kernel<2>, grid, block, sizeof(Lds), stream, fp);
+    else if (fp.n <= 4) hipLaunchKernelGGL(full_programs_kernel<4>, grid, block, sizeof(Lds), stream, fp);
+    else if (fp.n <= 8) hipLaunchKernelGGL(full_programs_kernel<8>, grid, block, sizeof(Lds), stream, fp);
+    else hipLaunchKernelGGL(full_programs_kernel<16>, grid, block, sizeof(Lds), stream, fp);
+    return hipGetLastError();
+}
+
 hipError_t solve_kernel_setup() {
     const void* kernels[4] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
                               reinterpret_cast<const void*>(solve_kernel<8>), reinterpret_cast<const void*>(solve_kernel<16>)};
     for (const void* k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
+        if (e != hipSuccess) return e;
+    }
+    const void* full_kernels[4] = {reinterpret_cast<const void*>(full_programs_kernel<2>), reinterpret_cast<const void*>(full_programs_kernel<4>),
+                                   reinterpret_cast<const void*>(full_programs_kernel<8>), reinterpret_cast<const void*>(full_programs_kernel<16>)};
+    for (const void* k : full_kernels) {
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
         if (e != hipSuccess) return e;
     }

@@ -29,8 +29,11 @@ struct Slice {
 };
 
 // All threads call; result in LDS `S`.  order/block/weight: this row's policy arrays.
+// rank_of: token -> rank of a full-vocabulary policy (nullptr for a top-k policy, whose ranks are
+// found by a scan of `order`).
 __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, const int* block,
-                            const double* weight, const int* drafts, int n, const float* prow, int V) {
+                            const double* weight, const int* rank_of, const int* drafts, int n,
+                            const float* prow, int V) {
     const int tid = threadIdx.x;
     if (tid == 0) {
         int nd = 0;
@@ -46,9 +49,13 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
     }
     __syncthreads();
     const int kk = info.support;
-    if (info.status == GR_ROW_OK && tid < kk) {
-        const int t = order[tid];
-        for (int i = 0; i < S.nd; ++i) if (S.tok[i] == t) S.pos[i] = tid;
+    if (info.status == GR_ROW_OK) {
+        if (rank_of) {
+            if (tid < S.nd) S.pos[tid] = rank_of[S.tok[tid]];
+        } else if (tid < kk) {
+            const int t = order[tid];
+            for (int i = 0; i < S.nd; ++i) if (S.tok[i] == t) S.pos[i] = tid;
+        }
     }
     __syncthreads();
     if (tid == 0) {
@@ -92,8 +99,17 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
 
 // Residual weights of one tile of tokens [base, base + kTile) into LDS `w` (zero beyond V).
 __device__ void tile_weights(double* w, const Slice& S, const RowInfo& info, const int* order,
-                             const double* rho, const float* prow, int base, int V) {
+                             const double* rho, const double* rho_id, const float* prow, int base, int V) {
     const int tid = threadIdx.x;
+    if (rho_id && S.mode == kInner) {                   // full-vocabulary policy: residuals by token id
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = base + tid * 4 + j;
+            w[tid * 4 + j] = t < V ? S.scale * rho_id[t] : 0.0;
+        }
+        __syncthreads();
+        return;
+    }
     const double f = S.scale / info.p_total;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -127,8 +143,7 @@ __device__ __forceinline__ float4 load4(const float* prow, int t0, int end, bool
 }  // namespace
 
 __global__ __launch_bounds__(kThreads) void verify_kernel(
-    const float* __restrict__ p, int V, int n, const int* __restrict__ order, const int* __restrict__ block,
-    const double* __restrict__ weight, const double* __restrict__ rho, const RowInfo* __restrict__ infos,
+    const float* __restrict__ p, int V, int n, PolicyView pv, const RowInfo* __restrict__ infos,
     const int* __restrict__ drafts, const float* __restrict__ uniforms, int* __restrict__ token,
     unsigned char* __restrict__ accepted) {
     __shared__ Slice S;
@@ -140,15 +155,17 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     const int tid = threadIdx.x, row = blockIdx.x;
     const RowInfo info = infos[row];
     const float* prow = p + static_cast<size_t>(row) * V;
-    const int* o = order + static_cast<size_t>(row) * KS;
-    const int* bl = block + static_cast<size_t>(row) * KS;
-    const double* wt = weight + static_cast<size_t>(row) * KS;
-    const double* rh = rho + static_cast<size_t>(row) * KS;
+    const int* o = pv.order + static_cast<size_t>(row) * pv.stride;
+    const int* bl = pv.block + static_cast<size_t>(row) * pv.stride;
+    const double* wt = pv.weight + static_cast<size_t>(row) * pv.stride;
+    const double* rh = pv.rho + static_cast<size_t>(row) * pv.stride;
+    const int* rk = pv.rank_of ? pv.rank_of + static_cast<size_t>(row) * pv.stride : nullptr;
+    const double* rid = pv.rho_id ? pv.rho_id + static_cast<size_t>(row) * pv.stride : nullptr;
     if (info.status == GR_ROW_BAD) {
         if (tid == 0) { token[row] = -1; accepted[row] = 0; }
         return;
     }
-    build_slice(S, info, o, bl, wt, drafts + static_cast<size_t>(row) * n, n, prow, V);
+    build_slice(S, info, o, bl, wt, rk, drafts + static_cast<size_t>(row) * n, n, prow, V);
     const double u = static_cast<double>(uniforms[row]);
     double c = 0.0;
     if (tid == 0) {
@@ -183,7 +200,9 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0;
     // weight of a token that is not f * p: the support (residual rho outside H*, none inside) when
     // the drafts all lie in H*; the drafts themselves (listed first) in the fallback
-    const int n_special = S.mode == kInner ? info.support : S.nd;
+    // a full-vocabulary policy whose drafts all lie in H* spreads the slack over scale * rho_id[t]
+    const bool dense = rid != nullptr && S.mode == kInner;
+    const int n_special = dense ? 0 : (S.mode == kInner ? info.support : S.nd);
     int sp_tok = -1; double sp_w = 0.0;
     if (tid < n_special) {
         if (S.mode == kInner) { sp_tok = o[tid]; sp_w = tid >= info.h ? S.scale * rh[tid] : 0.0; }
@@ -198,6 +217,19 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
         const int cs = 256 * g;
         const int np = (len + cs - 1) / cs;
         const int end = lo + len;
+        if (dense) {
+            for (int pc = wvv; pc < np; pc += kWaves) {
+                double sa = 0.0;
+#pragma unroll 4
+                for (int sub = 0; sub < g; ++sub) {
+                    const int t0 = lo + pc * cs + sub * 256 + lane * 4;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) if (t0 + j < end) sa += rid[t0 + j];
+                }
+                sa = wave_sum(sa);
+                if (lane == 0) seg[pc] = S.scale * sa;
+            }
+        } else
         // two pieces per round and up to eight loads of each in flight: one workgroup streams the row,
         // so the walk is bound by load latency, not by bandwidth
         for (int pc = wvv; pc < np; pc += 2 * kWaves) {
@@ -258,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     }
     {
         const int t = lo + tid;
-        w[tid] = tid < len ? f * static_cast<double>(prow[t]) : 0.0;
+        w[tid] = tid < len ? (dense ? S.scale * rid[t] : f * static_cast<double>(prow[t])) : 0.0;
         __syncthreads();
         if (sp_tok >= lo && sp_tok < lo + len) w[sp_tok - lo] = sp_w;
         __syncthreads();
@@ -286,8 +318,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
 }
 
 __global__ __launch_bounds__(kThreads) void slice_kernel(
-    const float* __restrict__ p, int V, int n, const int* __restrict__ order, const int* __restrict__ block,
-    const double* __restrict__ weight, const double* __restrict__ rho, const RowInfo* __restrict__ infos,
+    const float* __restrict__ p, int V, int n, PolicyView pv, const RowInfo* __restrict__ infos,
     const int* __restrict__ drafts, float* __restrict__ pi, float* __restrict__ accept_given) {
     __shared__ Slice S;
     __shared__ double w[kTile];
@@ -295,18 +326,20 @@ __global__ __launch_bounds__(kThreads) void slice_kernel(
     const RowInfo info = infos[row];
     const float* prow = p + static_cast<size_t>(row) * V;
     float* out = pi + static_cast<size_t>(row) * V;
-    const int* o = order + static_cast<size_t>(row) * KS;
+    const int* o = pv.order + static_cast<size_t>(row) * pv.stride;
+    const int* rk = pv.rank_of ? pv.rank_of + static_cast<size_t>(row) * pv.stride : nullptr;
+    const double* rid = pv.rho_id ? pv.rho_id + static_cast<size_t>(row) * pv.stride : nullptr;
     if (info.status == GR_ROW_BAD) {
         for (int t = tid; t < V; t += kThreads) out[t] = 0.f;
         if (tid == 0) accept_given[row] = 0.f;
         return;
     }
-    build_slice(S, info, o, block + static_cast<size_t>(row) * KS, weight + static_cast<size_t>(row) * KS,
-                drafts + static_cast<size_t>(row) * n, n, prow, V);
+    build_slice(S, info, o, pv.block + static_cast<size_t>(row) * pv.stride, pv.weight + static_cast<size_t>(row) * pv.stride,
+                rk, drafts + static_cast<size_t>(row) * n, n, prow, V);
     const bool spread = (S.mode == kInner || S.mode == kFallback) && S.scale > 0.0;
     for (int base = 0; base < V; base += kTile) {
         if (spread) {
-            tile_weights(w, S, info, o, rho + static_cast<size_t>(row) * KS, prow, base, V);
+            tile_weights(w, S, info, o, pv.rho + static_cast<size_t>(row) * pv.stride, rid, prow, base, V);
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) w[tid * 4 + j] = 0.0;
@@ -327,18 +360,15 @@ __global__ __launch_bounds__(kThreads) void slice_kernel(
     if (tid == 0) accept_given[row] = static_cast<float>(S.acc);
 }
 
-void launch_verify(const float* p, int B, int V, int n, const int* order, const int* block,
-                   const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+void launch_verify(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                    const float* uniforms, int* token, unsigned char* accepted, hipStream_t stream) {
-    hipLaunchKernelGGL(verify_kernel, dim3(B), dim3(kThreads), 0, stream, p, V, n, order, block, weight,
-                       rho, info, drafts, uniforms, token, accepted);
+    hipLaunchKernelGGL(verify_kernel, dim3(B), dim3(kThreads), 0, stream, p, V, n, pv, info, drafts, uniforms,
+                       token, accepted);
 }
 
-void launch_slice(const float* p, int B, int V, int n, const int* order, const int* block,
-                  const double* weight, const double* rho, const RowInfo* info, const int* drafts,
+void launch_slice(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                   float* pi, float* accept_given, hipStream_t stream) {
-    hipLaunchKernelGGL(slice_kernel, dim3(B), dim3(kThreads), 0, stream, p, V, n, order, block, weight,
-                       rho, info, drafts, pi, accept_given);
+    hipLaunchKernelGGL(slice_kernel, dim3(B), dim3(kThreads), 0, stream, p, V, n, pv, info, drafts, pi, accept_given);
 }
 
 }  // namespace gr

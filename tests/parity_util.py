@@ -8,10 +8,13 @@ ABS_TOL = 1e-5          # spec tolerance on alpha* and on every policy ent
 EDGE_TOL = 1e-5         # a uniform this close to a CDF edge may fall either way
 
 
-def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=None):
+def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=None, export_rows=None):
+    """Run the HIP path.  A policy over more than GR_MAX_SUPPORT tokens (no top-k on a large V) has no
+    dense export: its rows listed in `export_rows` are fetched one by one into out["rows"]."""
     import torch
     from paper_2511_15898_amd import binding as gr
     dev = torch.device("cuda:0")
+    full = (wl.k <= 0 or wl.k >= wl.V) and wl.V > gr.GR_MAX_SUPPORT
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     d = torch.from_numpy(wl.drafts if drafts is None else drafts).to(dev)
     u = torch.from_numpy(wl.uniforms).to(dev)
@@ -22,9 +25,23 @@ def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=N
         out = {"accept_prob": acc, "status": st, "token": tok, "accepted": ok}
         if want_slice:
             out["pi"], out["accept_given"] = gr.gr_policy_slice(h, d, wl.V)
-        out.update(gr.gr_policy_export(h, wl.B, dev))
+        rows = {}
+        if full:
+            for name in ("support", "h_size", "iterations"):
+                out[name] = torch.empty(wl.B, dtype=torch.int32, device=dev)
+            rc = gr.load_library().gr_policy_export(h, None, None, None, None, out["support"].data_ptr(), out["h_size"].data_ptr(),
+                                                    out["iterations"].data_ptr(), torch.cuda.current_stream().cuda_stream)
+            assert rc == 0, rc
+            torch.cuda.synchronize()
+            sup = out["support"].cpu().numpy()
+            for b in (export_rows or []):
+                rows[b] = {k: v.cpu().numpy() for k, v in gr.gr_policy_export_row(h, b, int(sup[b]), dev).items()}
+        else:
+            out.update(gr.gr_policy_export(h, wl.B, dev))
         torch.cuda.synchronize()
         out = {k: v.cpu().numpy() for k, v in out.items()}
+        if full:
+            out["rows"] = rows
     finally:
         gr.gr_destroy(h)
     return out
@@ -49,9 +66,11 @@ def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None):
         assert out["status"][b] == sol.status, (b, out["status"][b], sol.status)
         kk = len(sol.order)
         assert out["support"][b] == kk and out["h_size"][b] == sol.h, (b, out["support"][b], kk, out["h_size"][b], sol.h)
-        assert np.array_equal(out["order"][b, :kk], sol.order), (b, "ratio order differs")
-        assert np.array_equal(out["block"][b, :kk], sol.block_of), (b, "block split differs")
-        assert np.abs(out["rho"][b, :kk] - sol.rho).max() < 1e-12, (b, "residuals differ")
+        g_order, g_block, g_rho = (out["rows"][b]["order"], out["rows"][b]["block"], out["rows"][b]["rho"]) if "rows" in out \
+            else (out["order"][b, :kk], out["block"][b, :kk], out["rho"][b, :kk])
+        assert np.array_equal(g_order, sol.order), (b, "ratio order differs")
+        assert np.array_equal(g_block, sol.block_of), (b, "block split differs")
+        assert np.abs(g_rho - sol.rho).max() < 1e-12, (b, "residuals differ")
         if "pi" in out:
             dpi = float(np.abs(out["pi"][b] - pi).max())
             stats["max_dpi"] = max(stats["max_dpi"], dpi)

@@ -113,7 +113,7 @@ def test_call_level_errors():
                 gr.gr_solve(h, p, p, args["n"], args["k"], args["tol"])
             assert e.value.code == gr.GR_EINVAL
         with pytest.raises(gr.GrError) as e:
-            gr.gr_solve(h, p, p, 2, 0, 1e-6)          # no top-k on V = 1024: support beyond the cap
+            gr.gr_solve(h, p, p, 2, 300, 1e-6)        # a top-k between GR_MAX_SUPPORT and V
         assert e.value.code == gr.GR_EUNSUPPORTED
         big = torch.full((8, 1024), 1.0 / 1024, device=dev)
         with pytest.raises(gr.GrError) as e:
@@ -121,21 +121,5 @@ def test_call_level_errors():
         assert e.value.code == gr.GR_EINVAL
         with pytest.raises(TypeError):
             gr.gr_solve(h, p.double(), p, 2, 8, 1e-6)
-    finally:
-        gr.gr_destroy(h)
-
-
-def test_full_vocab_support_is_refused():
-    """Config 5's 'top-k = full V' cells need a support of 128256 tokens; this build keeps the
-    support in LDS (at most 256 tokens) and says so instead of answering approximately."""
-    import torch
-    from paper_2511_15898_amd import binding as gr
-    dev = torch.device("cuda:0")
-    h = gr.gr_create(2, 128256)
-    try:
-        p = torch.full((2, 128256), 1.0 / 128256, device=dev)
-        with pytest.raises(gr.GrError) as e:
-            gr.gr_solve(h, p, p, 4, 128256, 1e-6)
-        assert e.value.code == gr.GR_EUNSUPPORTED
     finally:
         gr.gr_destroy(h)

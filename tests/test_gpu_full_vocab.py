@@ -1,0 +1,120 @@
+"""GPU parity of the full-vocabulary path (no top-k, support above GR_MAX_SUPPORT): ratio order by the
+HBM sort, alpha*, residuals, blocks, truncation sets and row status, the convex programs of rows whose
+truncation sets fit, the dense slice and the sampled token, against the CPU checker.  Same tolerances
+as the top-k parity tests."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2511_15898_amd import workloads as W
+from parity_util import check_alpha_all_rows, compare_rows, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16])
+def test_stress_full_vocab_cells(n):
+    """Config 5's 'top-k = full V' cells at V = 128256 (4 rows per cell: the checker needs seconds per
+    row).  Most rows are degenerate (alpha* = 1 with H* empty or everything) or exceed the cap on |T|;
+    alpha* is checked on every row, everything else on the rows where it is unique."""
+    wl = W.stress(B=4, n=n, k=0, seed_sub=900 + n)
+    out = run_gpu(wl, 1e-4, export_rows=range(wl.B))
+    check_alpha_all_rows(wl, out)
+    stats = compare_rows(wl, out, range(wl.B), 1e-4)
+    assert stats["rows"] == wl.B
+    assert np.all(np.abs(out["pi"].sum(1) - 1.0) < 1e-4)
+
+
+@pytest.mark.parametrize("V,n,tol", [(5000, 4, 1e-4), (5000, 2, 1e-4), (3000, 8, 1e-3), (777, 16, 1e-3)])
+def test_mid_size_vocab_without_top_k(V, n, tol):
+    """LLM-shaped rows on a vocabulary that the checker handles quickly: every row is compared, and
+    rows with alpha* < 1 whose truncation sets fit exercise both kinds of convex program."""
+    wl = W.llm_shaped(B=24, V=V, n=n, k=0, seed_sub=40 + n)
+    out = run_gpu(wl, tol, export_rows=range(wl.B))
+    check_alpha_all_rows(wl, out)
+    stats = compare_rows(wl, out, range(wl.B), tol)
+    assert stats["rows"] == wl.B and stats["fragile"] < wl.B
+    assert np.any(out["status"] == 0) and out["iterations"].max() > 0
+
+
+def test_residual_draws_walk_the_dense_residuals():
+    """Uniforms close to 1 force the draw past the drafts wherever the conditional acceptance is below
+    1, so the sampled token comes from the residual spread over all V tokens."""
+    wl = W.llm_shaped(B=24, V=5000, n=2, k=0, seed_sub=77)
+    wl = dataclasses.replace(wl, uniforms=np.full(wl.B, 0.9990234375, dtype=np.float32))
+    out = run_gpu(wl, 1e-4, export_rows=range(wl.B))
+    compare_rows(wl, out, range(wl.B), 1e-4)
+    assert np.any(out["accepted"] == 0)
+
+
+def test_flat_rows_and_exact_zeros():
+    """Dirichlet rows (flat: every program exceeds the cap, the fallback transport is used) and rows
+    with exact zeros in q (tokens outside the support rank nowhere and keep p as residual)."""
+    wl = W.tiny(B=12, V=300, n=2)
+    out = run_gpu(wl, 1e-2, export_rows=range(wl.B))
+    compare_rows(wl, out, range(wl.B), 1e-2)
+    rng = np.random.default_rng(5)
+    wl = W.llm_shaped(B=8, V=2000, n=3, k=0, seed_sub=3)
+    q = wl.q.copy()
+    q[:, rng.permutation(2000)[:700]] = 0.0
+    q = (q / q.sum(1, keepdims=True, dtype=np.float32)).astype(np.float32)
+    drafts = W.draw_drafts(q, 0, wl.n, rng)
+    wl = dataclasses.replace(wl, q=np.ascontiguousarray(q), drafts=drafts)
+    out = run_gpu(wl, 1e-4, export_rows=range(wl.B))
+    assert np.all(out["support"] == (q > 0).sum(1))
+    check_alpha_all_rows(wl, out)
+    compare_rows(wl, out, range(wl.B), 1e-4)
+
+
+def test_bad_rows_bad_drafts_and_determinism():
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    wl = W.llm_shaped(B=6, V=1500, n=4, k=0, seed_sub=9)
+    p = wl.p.copy(); q = wl.q.copy()
+    p[1, 7] = np.nan
+    q[2] = q[2] * np.float32(0.5)                       # row sum 0.5
+    q[3, 11] = 0.0
+    drafts = wl.drafts.copy()
+    drafts[3, 0] = 11                                   # a draft with q = 0
+    drafts[4, 1] = 1500                                 # out of range
+    wl2 = dataclasses.replace(wl, p=p, q=q, drafts=drafts)
+    a = run_gpu(wl2, 1e-4, export_rows=[0, 5])
+    b = run_gpu(wl2, 1e-4, export_rows=[0, 5])
+    assert a["status"][1] == gr.GR_ROW_BAD and a["status"][2] == gr.GR_ROW_BAD
+    assert np.isnan(a["accept_prob"][1]) and a["token"][1] == -1 and a["token"][2] == -1
+    assert a["token"][4] == -1 and a["accepted"][4] == 0
+    if a["status"][3] == gr.GR_ROW_OK:
+        assert a["token"][3] == -1 and a["accepted"][3] == 0
+    compare_rows(wl2, a, [0, 5], 1e-4)
+    for key in ("accept_prob", "status", "token", "accepted", "pi"):
+        assert np.array_equal(a[key], b[key], equal_nan=True), key
+    for r in (0, 5):
+        assert np.array_equal(a["rows"][r]["order"], b["rows"][r]["order"])
+        assert np.array_equal(a["rows"][r]["weight"], b["rows"][r]["weight"])
+
+
+def test_uniform_rows_at_full_size_and_refused_top_k():
+    """p = q uniform over 128256 tokens: all ratios tie (order = token id), alpha* = 1.  A top-k between
+    GR_MAX_SUPPORT and V is refused."""
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    dev = torch.device("cuda:0")
+    V = 128256
+    h = gr.gr_create(2, V)
+    try:
+        p = torch.full((2, V), 1.0 / V, device=dev)
+        acc, st = gr.gr_solve(h, p, p, 4, V, 1e-6)
+        d = torch.tensor([[5, 9, 5, 100000], [0, 1, 2, 3]], dtype=torch.int32, device=dev)
+        u = torch.tensor([0.3, 0.9], device=dev)
+        tok, ok = gr.gr_verify(h, d, u)
+        row = gr.gr_policy_export_row(h, 0, V, dev)
+        torch.cuda.synchronize()
+        assert np.allclose(acc.cpu().numpy(), 1.0, atol=1e-6)
+        assert np.array_equal(row["order"].cpu().numpy(), np.arange(V))
+        assert np.all(tok.cpu().numpy() >= 0) and np.all(tok.cpu().numpy() < V)
+        with pytest.raises(gr.GrError) as e:
+            gr.gr_solve(h, p, p, 4, 1000, 1e-6)
+        assert e.value.code == gr.GR_EUNSUPPORTED
+    finally:
+        gr.gr_destroy(h)

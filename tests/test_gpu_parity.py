@@ -52,8 +52,8 @@ def test_large_vocab_full_size(tol):
 @pytest.mark.parametrize("n", [2, 4, 8, 16])
 @pytest.mark.parametrize("k", [8, 32, 128])
 def test_stress_cells(n, k):
-    """Config 5 cells with a top-k (batch reduced to 96 rows per cell; the full-V cells are beyond
-    the LDS-resident support, see test_full_vocab_support_is_refused)."""
+    """Config 5 cells with a top-k (batch reduced to 96 rows per cell; the full-V cells are in
+    test_gpu_full_vocab.py)."""
     wl = W.stress(B=96, n=n, k=k, seed_sub=100 * n + k)
     out = run_gpu(wl, 1e-6)
     check_alpha_all_rows(wl, out)
