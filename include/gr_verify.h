@@ -46,8 +46,6 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_ROW_TRUNC_CAP  1    /* a program needed more than max_T variables (App. "Truncated Solver Details") */
 #define GR_ROW_ITER_CAP   2    /* iteration cap reached before the gradient criterion (same appendix) */
 #define GR_ROW_BAD        3    /* NaN / negative entry, or a row sum further than 1e-3 from 1 */
-#define GR_ROW_UNSOLVED   4    /* support above GR_MAX_SUPPORT: accept_prob is exact, the convex programs
-                                  were not run */
 
 #define GR_MAX_SUPPORT  256    /* largest top-k support (|V_0|) the LDS-resident path holds */
 #define GR_MAX_T        128    /* largest number of variables of one convex program */

@@ -15,7 +15,7 @@ from .build import LIB_PATH
 GR_MAX_SUPPORT = 256
 GR_MAX_T = 128
 GR_MAX_N = 16
-GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD, GR_ROW_UNSOLVED = 0, 1, 2, 3, 4
+GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_verify", "gr_policy_slice", "gr_policy_export",

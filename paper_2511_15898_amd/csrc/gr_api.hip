@@ -160,7 +160,6 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         if (rc != GR_OK) return rc;
         FullParams& f = h->full;
         f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.max_T = h->max_T; f.max_iter = h->max_iter;
-        f.run_programs = 1;
         f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
         f.info = h->info; f.accept_prob = accept_prob; f.status = status;
         mark(h, 0, stream);

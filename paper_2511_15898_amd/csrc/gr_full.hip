@@ -399,7 +399,7 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     }
     __syncthreads();
     if (tid == 0) {
-        const int status = (act_in > fp.max_T || capped) ? GR_ROW_TRUNC_CAP : (fp.run_programs ? GR_ROW_OK : GR_ROW_UNSOLVED);
+        const int status = (act_in > fp.max_T || capped) ? GR_ROW_TRUNC_CAP : GR_ROW_OK;
         fp.tcount[2 * row] = cnt_in; fp.tcount[2 * row + 1] = cnt_out;
         RowInfo out = info;
         out.status = status;

@@ -52,7 +52,6 @@ struct SolveParams {
 struct FullParams {
     const float* p; const float* q;
     int B, V, n, max_T, max_iter;
-    int run_programs;  // 0: rows whose programs fit are marked GR_ROW_UNSOLVED instead of being solved
     double tau, rel_tol;
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p

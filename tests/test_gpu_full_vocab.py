@@ -118,3 +118,22 @@ def test_uniform_rows_at_full_size_and_refused_top_k():
         assert e.value.code == gr.GR_EUNSUPPORTED
     finally:
         gr.gr_destroy(h)
+
+
+def test_stress_full_vocab_cell_at_full_batch():
+    """One 'full V' cell at config 5's own size (1024 rows x 128256 tokens, n = 8): alpha* against
+    the checker on sampled rows, statuses and tokens valid on every row."""
+    import torch
+    from oracle import gr_oracle as G
+    from paper_2511_15898_amd import binding as gr
+    wl = W.stress(B=1024, n=8, k=0, seed_sub=908)
+    out = run_gpu(wl, 1e-4, want_slice=False)
+    assert np.all((out["status"] == gr.GR_ROW_OK) | (out["status"] == gr.GR_ROW_TRUNC_CAP))
+    assert np.all((out["token"] >= 0) & (out["token"] < wl.V))
+    assert np.all(out["support"] == (wl.q > 0).sum(1))
+    for b in (0, 511, 1023):
+        order = G.ratio_order(wl.p[b], wl.q[b], G.topk_support(wl.q[b], 0))
+        pt = float(np.sum(wl.p[b], dtype=np.float64))
+        _, _, F = G.prefix_psi(wl.p[b][order].astype(np.float64) / pt, wl.q[b][order], wl.n)
+        assert abs(out["accept_prob"][b] - (1.0 + F.min())) < 1e-5
+        assert out["h_size"][b] == int(np.argmin(F)) or np.sort(F)[1] - np.sort(F)[0] < 1e-13
