@@ -15,6 +15,7 @@ struct gr_handle_s {
     // scratch of the select kernel
     unsigned long long* cand = nullptr; int* cand_count = nullptr;
     double* part_psum = nullptr; double* part_qsum = nullptr; int* part_bad = nullptr;
+    double* piece_psum = nullptr; int piece_stride = 0;   // float64 sums of p per 256 tokens, [max_B, piece_stride]
     // policy object of the last solve
     int* order = nullptr; int* block = nullptr; double* weight = nullptr; double* rho = nullptr; double* pnorm = nullptr;
     RowInfo* info = nullptr;
@@ -45,7 +46,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -71,9 +72,11 @@ PolicyView policy_view(gr_handle h) {
         const FullParams& f = h->full;
         pv.order = f.order; pv.block = f.blk; pv.weight = f.weight; pv.rho = f.rho;
         pv.rank_of = f.rank_of; pv.rho_id = f.rho_id; pv.stride = static_cast<size_t>(h->V) + 2;
+        pv.piece_psum = nullptr; pv.piece_stride = 0;
     } else {
         pv.order = h->order; pv.block = h->block; pv.weight = h->weight; pv.rho = h->rho;
         pv.rank_of = nullptr; pv.rho_id = nullptr; pv.stride = kMaxSupport;
+        pv.piece_psum = h->piece_psum; pv.piece_stride = h->piece_stride;
     }
     return pv;
 }
@@ -126,6 +129,8 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* 
               dev_alloc(&h->block, rows * kMaxSupport) && dev_alloc(&h->weight, rows * kMaxSupport) &&
               dev_alloc(&h->rho, rows * kMaxSupport) && dev_alloc(&h->pnorm, rows * kMaxSupport) &&
               dev_alloc(&h->info, rows);
+    h->piece_stride = (max_V + kSelTile - 1) / kSelTile * (kSelTile / 256) + kMaxSplits * (kSelTile / 256);
+    ok = ok && dev_alloc(&h->piece_psum, rows * h->piece_stride);
     if (!ok) { free_all(h); delete h; (void)hipGetLastError(); return GR_ENOMEM; }
     if (cfg && (cfg->flags & GR_FLAG_PROFILE)) {
         h->profile = true;
@@ -174,11 +179,11 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     h->full_mode = false;
     const int splits = choose_splits(B, V);
     int slice_len = (V + splits - 1) / splits;
-    slice_len = (slice_len + 3) & ~3;
+    slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;
     h->solved = false;
     mark(h, 0, stream);
     launch_select(p, q, B, V, k_eff, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
-                  h->part_bad, stream);
+                  h->part_bad, h->piece_psum, h->piece_stride, stream);
     if (hipGetLastError() != hipSuccess) return GR_EHIP;
     mark(h, 1, stream);
     SolveParams sp;

@@ -69,7 +69,7 @@ constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 9 * 8 + 5 * 4 + 4 
 void launch_full_prologue(const FullParams& fp, hipStream_t stream);
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
-                   hipStream_t stream);
+                   double* piece_psum, int piece_stride, hipStream_t stream);
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream);
 // The policy object as the verify and slice kernels read it.  Top-k policies: arrays [B, stride] with
 // stride = kMaxSupport, rank_of = rho_id = nullptr.  Full-vocabulary policies: stride = V + 2, plus the
@@ -78,6 +78,8 @@ struct PolicyView {
     const int* order; const int* block; const double* weight; const double* rho;
     const int* rank_of; const double* rho_id;
     size_t stride;
+    const double* piece_psum;   // [B, piece_stride] float64 sums of p over pieces of 256 tokens, or nullptr
+    int piece_stride;
 };
 void launch_verify(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                    const float* uniforms, int* token, unsigned char* accepted, hipStream_t stream);

@@ -7,7 +7,8 @@
 
 namespace gr {
 
-// grid = (splits, B); workgroup (s, b) streams tokens [s*slice_len, min(V, (s+1)*slice_len)) of row b.
+// grid = (splits, B); workgroup (s, b) streams tokens [s*slice_len, min(V, (s+1)*slice_len)) of row b;
+// slice_len is a multiple of the tile (1024 tokens).
 // Candidates are 64-bit keys (q bits, ~id) appended to an LDS buffer while they exceed the current
 // threshold; when a further tile might overflow the buffer it is cut back to its k largest keys and
 // the threshold is raised to the k-th.  The buffer never overflows: before each tile it holds at most
@@ -15,7 +16,8 @@ namespace gr {
 __global__ __launch_bounds__(kThreads) void select_kernel(
     const float* __restrict__ p, const float* __restrict__ q, int V, int k, int slice_len,
     unsigned long long* __restrict__ cand, int* __restrict__ cand_count,
-    double* __restrict__ part_psum, double* __restrict__ part_qsum, int* __restrict__ part_bad) {
+    double* __restrict__ part_psum, double* __restrict__ part_qsum, int* __restrict__ part_bad,
+    double* __restrict__ piece_psum, int piece_stride) {
     __shared__ unsigned long long keys[kSelCap];
     __shared__ int hist[256];
     __shared__ int pick[2];
@@ -54,6 +56,14 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 qv[j] = in ? qr[i0 + j] : 0.f;
                 pv[j] = in ? pr[i0 + j] : 0.f;
             }
+        }
+        // float64 sum of p over the 256 tokens this wave holds (slices start on tile boundaries, so the
+        // pieces line up over the whole row): the rejection walk of the verify kernel starts from these
+        {
+            const double p4 = (static_cast<double>(pv[0]) + static_cast<double>(pv[1])) +
+                              (static_cast<double>(pv[2]) + static_cast<double>(pv[3]));
+            const double pw = wave_sum(p4);
+            if ((tid & 63) == 0) piece_psum[static_cast<size_t>(b) * piece_stride + (base >> 8) + (tid >> 6)] = pw;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -120,10 +130,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
 
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
-                   hipStream_t stream) {
+                   double* piece_psum, int piece_stride, hipStream_t stream) {
     dim3 grid(splits, B);
     hipLaunchKernelGGL(select_kernel, grid, dim3(kThreads), 0, stream, p, q, V, k, slice_len, cand,
-                       cand_count, psum, qsum, bad);
+                       cand_count, psum, qsum, bad, piece_psum, piece_stride);
 }
 
 }  // namespace gr

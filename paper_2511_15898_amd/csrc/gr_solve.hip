@@ -621,7 +621,7 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
 // In: L.aq, L.at (targets, already scaled to the tuple mass), L.aal (start log weights).
 // Out: L.aal.  `evals` counts evaluator calls.
 template <int D>
-__device__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double slack_target,
+__device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double slack_target,
                              double rel_tol, int max_iter, int* evals) {
     const int tid = threadIdx.x;
     const double qsum = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);

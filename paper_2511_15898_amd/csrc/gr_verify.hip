@@ -202,6 +202,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     // the drafts all lie in H*; the drafts themselves (listed first) in the fallback
     // a full-vocabulary policy whose drafts all lie in H* spreads the slack over scale * rho_id[t]
     const bool dense = rid != nullptr && S.mode == kInner;
+    const double* pieces = (pv.piece_psum && !dense) ? pv.piece_psum + static_cast<size_t>(row) * pv.piece_stride : nullptr;
     const int n_special = dense ? 0 : (S.mode == kInner ? info.support : S.nd);
     int sp_tok = -1; double sp_w = 0.0;
     if (tid < n_special) {
@@ -217,7 +218,19 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
         const int cs = 256 * g;
         const int np = (len + cs - 1) / cs;
         const int end = lo + len;
-        if (dense) {
+        if (pieces) {
+            // the sums of p over every 256 tokens came with the select pass: no read of the row here
+            const int npv = (V + 255) >> 8;
+            for (int pc = wvv; pc < np; pc += kWaves) {
+                double sa = 0.0;
+                for (int sub = lane; sub < g; sub += 64) {
+                    const int idx = (lo >> 8) + pc * g + sub;
+                    if (idx < npv) sa += pieces[idx];
+                }
+                sa = wave_sum(sa);
+                if (lane == 0) seg[pc] = f * sa;
+            }
+        } else if (dense) {
             for (int pc = wvv; pc < np; pc += kWaves) {
                 double sa = 0.0;
 #pragma unroll 4
