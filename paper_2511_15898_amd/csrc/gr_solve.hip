@@ -26,6 +26,7 @@ constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation 
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
 constexpr int kNewtonMax = 32;       // largest program the Newton fallback takes
+constexpr double kStretch = 4.0;      // cap on the per-coordinate stretch of the fixed-point step
 constexpr int kMixBudget = 60;       // evaluations given to the mixed fixed-point iteration before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
@@ -56,6 +57,7 @@ struct Lds {
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
     double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
+    double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa: aS = w dR/dw - ... (see routed_eval)
     double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
     double e2tab[32];               // 2^(-j/32)
     int nbig;                       // number of heavy tokens of the current program
@@ -267,22 +269,28 @@ __device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, in
 // Phase 3, a token with its full factor at the four nodes nu0 + j*stride (j = 0..3).
 template <int D>
 __device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D + 1], double wt, int n, int nu0,
-                                             int stride, int nn) {
-    double T[4][D + 1], y[4], x[4], qq[4], cn[4];
+                                             int stride, int nn, double& acc_t) {
+    double T[4][D + 1], y[4], x[4], qq[4], cn[4], tt[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int nu = nu0 + j * stride;
         const int nv = nu < nn ? nu : 0;
-        y[j] = L.tnode[nv] * wt;
+        tt[j] = L.tnode[nv];
+        y[j] = tt[j] * wt;
         qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
 #pragma unroll
         for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * 17 + d];
     }
     exp_neg4(y, x, L.e2tab);
     loo_coeff4<D, D>(T, x, e, n, cn);
-    double acc = 0.0;
+    double acc = 0.0, at = 0.0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc = fma(qq[j] * x[j], cn[j], acc);
+    for (int j = 0; j < 4; ++j) {
+        const double term = qq[j] * x[j] * cn[j];
+        acc += term;
+        at = fma(term, tt[j], at);
+    }
+    acc_t = at;
     return acc;
 }
 
@@ -303,9 +311,11 @@ __device__ __forceinline__ void phase3_small_load(const Lds& L, int nu0, int nn,
         for (int a = 0; a < 4; ++a) r.T[j][a] = L.Tl[nv * 17 + o[a]];
     }
 }
-__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int n, int wv, int nn) {
-    double acc = 0.0;
+__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int n, int wv, int nn,
+                                               double& acc_t) {
+    double acc = 0.0, at = 0.0;
     const int o[4] = {n - 1, n >= 2 ? n - 2 : 0, n >= 3 ? n - 3 : 0, n >= 4 ? n - 4 : 0};
+    acc_t = 0.0;
     if (wv >= nn) return acc;
     NodeOps nx;
     phase3_small_load(L, wv, nn, o, nx);
@@ -326,9 +336,12 @@ __device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5
             cn = fma(e[2] * g2, c.T[j][1], cn);
             cn = fma(e[3] * g3, c.T[j][2], cn);
             cn = fma(e[4] * g4, c.T[j][3], cn);
-            acc = fma(c.qw[j] * xx, cn, acc);
+            const double term = c.qw[j] * xx * cn;
+            acc += term;
+            at = fma(term, c.t[j], at);
         }
     }
+    acc_t = at;
     return acc;
 }
 
@@ -373,7 +386,8 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     for (int i = 2; i <= n; ++i) fact *= i;
     double r0 = 0.0;                                       // slack mass, accumulated by lane 0 of wave 0
     double racc[2] = {0.0, 0.0};                           // phase 3 accumulators of light tokens lane, lane + 64
-    if (tid < m) { for (int w2 = 0; w2 < kSW; ++w2) L.rpart[w2][tid] = 0.0; }
+    double sacc[2] = {0.0, 0.0};                           // the same, weighted by the node abscissa t
+    if (tid < m) { for (int w2 = 0; w2 < kSW; ++w2) { L.rpart[w2][tid] = 0.0; L.spart[w2][tid] = 0.0; } }
     const int first_small = nbig + ((wv - nbig) % kSW + kSW) % kSW;   // first light token of this wave
     // this lane's light tokens in phase 3: series terms q^k / k!, k <= min(n, 4)
     double es[2][5]; double ws[2];
@@ -468,26 +482,34 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             double e[D + 1];
 #pragma unroll
             for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * 17 + a];
-            double acc = phase3_big<D>(L, e, L.aw[tk], n, wv + kSW * (lane >> 4), 4 * kSW, nn);
-            acc += __shfl_xor(acc, 16);
-            acc += __shfl_xor(acc, 32);
-            if (lane < 16 && tok < nbig) L.rpart[wv][tok] += acc;
+            double acct;
+            double acc = phase3_big<D>(L, e, L.aw[tk], n, wv + kSW * (lane >> 4), 4 * kSW, nn, acct);
+            acc += __shfl_xor(acc, 16); acct += __shfl_xor(acct, 16);
+            acc += __shfl_xor(acc, 32); acct += __shfl_xor(acct, 32);
+            if (lane < 16 && tok < nbig) { L.rpart[wv][tok] += acc; L.spart[wv][tok] += acct; }
         }
         // light tokens
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
-            if (pass * 64 < m && (pass + 1) * 64 > nbig) racc[pass] += phase3_small(L, es[pass], ws[pass], n, wv, nn);
+            if (pass * 64 < m && (pass + 1) * 64 > nbig) {
+                double at;
+                racc[pass] += phase3_small(L, es[pass], ws[pass], n, wv, nn, at);
+                sacc[pass] += at;
+            }
         }
         __syncthreads();                                   // part / cum / Tl / tnode are rewritten by the next chunk
     }
-    if (lane < m && lane >= nbig) L.rpart[wv][lane] = racc[0];
-    if (64 + lane < m && 64 + lane >= nbig) L.rpart[wv][64 + lane] = racc[1];
+    if (lane < m && lane >= nbig) { L.rpart[wv][lane] = racc[0]; L.spart[wv][lane] = sacc[0]; }
+    if (64 + lane < m && 64 + lane >= nbig) { L.rpart[wv][64 + lane] = racc[1]; L.spart[wv][64 + lane] = sacc[1]; }
     if (tid == 0) { L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack; L.work += static_cast<double>(N) * m; }
     __syncthreads();
     if (tid < m) {
         double r = L.apd[tid] * tail / fact;
-        for (int w2 = 0; w2 < kSW; ++w2) r += L.rpart[w2][tid];
+        // the nodes below t_lo (x = 1 there) add tail to the integral of 1 and tail2 to that of t
+        double sq = L.apd[tid] * (step * t_lo * t_lo / (exp(2.0 * step) - 1.0)) / fact;
+        for (int w2 = 0; w2 < kSW; ++w2) { r += L.rpart[w2][tid]; sq += L.spart[w2][tid]; }
         L.aR[tid] = r * L.aw[tid] * fact;
+        L.aS[tid] = sq * L.aw[tid] * L.aw[tid] * fact;
     }
     __syncthreads();
 #ifdef GR_DEBUG
@@ -509,7 +531,12 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
     if (tid < m) {
         f = log(L.at[tid] / L.aR[tid]);
         f -= slack ? log(slack_target / L.R0acc) : log(tsum / rsum);
-        L.af[tid] = f;
+        // The fixed-point step treats the routed mass as proportional to the weight; its true
+        // logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a token loses to
+        // itself), so the step of each coordinate is stretched by R / (R - S), at most kStretch.
+        const double R = L.aR[tid], d = R - L.aS[tid];
+        const double stretch = (d * kStretch > R) ? R / d : kStretch;
+        L.af[tid] = f * stretch;
     }
     *rsum_out = rsum;
     return block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
@@ -666,6 +693,9 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
         const long long it_c1 = clock64();
         if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
 #endif
+#ifdef GR_DEBUG
+        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("it %d m %d nbig %d slack %d err %.3e best %.3e hcount %d plain %d\n", it, m, L.nbig, slack, err, best_err, hcount, plain);
+#endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
             // a mixed step went astray: back to the best point, plain (monotone) steps for a while
@@ -742,15 +772,12 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                         Gm[a][kCols] = L.gram[idx]; ++idx;
                     }
                 }
-                double tr = 0.0;
-#pragma unroll
-                for (int a = 0; a < kCols; ++a) if (a < ncol) tr += Gm[a][a];
-                const double ridge = 1e-10 * tr + 1e-300;
                 bool good = true;
 #pragma unroll
                 for (int c = 0; c < kCols; ++c) {
                     if (c < ncol) {
-                        Gm[c][c] += ridge;
+                        // a ridge relative to the column itself: recent columns are far shorter than old ones
+                        Gm[c][c] = Gm[c][c] * (1.0 + 1e-10) + 1e-300;
                         good = good && (Gm[c][c] > 0.0);
                         const double inv = 1.0 / Gm[c][c];
 #pragma unroll
@@ -789,6 +816,10 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
             // Newton fallback); a failed solve drops the history
             if (solved && cmax < 1e300) stepv = cmax > 3.0 ? cand * (3.0 / cmax) : cand;
             else hcount = 0;
+        }
+        if (ncol < 1) {                                    // a plain step: the same cap on its length
+            const double fmx = block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
+            if (fmx > 3.0) stepv = f * (3.0 / fmx);
         }
         if (tid < m) L.aal[tid] += stepv;
         ++hcount;
@@ -1231,6 +1262,8 @@ hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream) {
     else hipLaunchKernelGGL(full_programs_kernel<16>, grid, block, sizeof(Lds), stream, fp);
     return hipGetLastError();
 }
+
+static_assert(sizeof(Lds) <= 160 * 1024, "the solve workgroup's state must fit the CU's LDS");
 
 hipError_t solve_kernel_setup() {
     const void* kernels[4] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
