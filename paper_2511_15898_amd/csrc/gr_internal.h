@@ -235,9 +235,11 @@ __device__ __forceinline__ float key_q(unsigned long long key) {
     return __uint_as_float(static_cast<unsigned>(key >> 32));
 }
 
-// k-th largest of `count` distinct keys held in LDS (1 <= k <= count <= kSelCap), by
-// most-significant-digit radix selection, 8 bits per pass.  All NT threads of the workgroup call it.
-// hist: LDS int[256]; pick: LDS int[2].
+// A threshold theta such that exactly k of the `count` distinct keys held in LDS are >= theta
+// (1 <= k <= count <= kSelCap; theta <= the k-th largest key), by most-significant-digit radix
+// selection, 8 bits per pass.  The walk stops as soon as the bucket it enters holds exactly the keys
+// still needed: theta is then that bucket's prefix with the lower digits zero.  All NT threads of the
+// workgroup call it.  hist: LDS int[256]; pick: LDS int[4].
 template <int NT = kThreads>
 __device__ inline unsigned long long block_kth_largest(const unsigned long long* keys, int count, int k,
                                                        int* hist, int* pick) {
@@ -266,7 +268,7 @@ __device__ inline unsigned long long block_kth_largest(const unsigned long long*
             if (excl < need && need <= incl) {
                 int above = excl;
                 for (int j = 0; j < 4; ++j) {
-                    if (need <= above + c[j]) { pick[0] = 255 - 4 * tid - j; pick[1] = need - above; break; }
+                    if (need <= above + c[j]) { pick[0] = 255 - 4 * tid - j; pick[1] = need - above; pick[2] = c[j]; break; }
                     above += c[j];
                 }
             }
@@ -274,7 +276,9 @@ __device__ inline unsigned long long block_kth_largest(const unsigned long long*
         __syncthreads();
         prefix |= static_cast<unsigned long long>(pick[0]) << shift;
         need = pick[1];
+        const bool whole_bucket = pick[2] == need;
         __syncthreads();
+        if (whole_bucket) break;
     }
     return prefix;
 }

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     double* __restrict__ piece_psum, int piece_stride) {
     __shared__ unsigned long long keys[kSelCap];
     __shared__ int hist[256];
-    __shared__ int pick[2];
+    __shared__ int pick[4];
     __shared__ int count;
     __shared__ double red[kWaves];
 

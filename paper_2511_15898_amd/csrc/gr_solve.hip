@@ -62,7 +62,7 @@ struct Lds {
     double e2tab[32];               // 2^(-j/32)
     int nbig;                       // number of heavy tokens of the current program
     double work;                    // sum over evaluator calls of nodes x active tokens (thread 0 only)
-    double red[kSW]; double R0acc; int ok; int pick[2]; int count; int hist[256];
+    double red[kSW]; double R0acc; int ok; int pick[4]; int count; int hist[256];
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
         unsigned long long keys[kSelCap];
@@ -921,18 +921,33 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     __syncthreads();
 
     GR_MARK("merged");
-    // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id
-    if (tid < kk) {
-        const double qa = L.accb[tid], pa = L.G0[tid];
-        const int ta = L.ordq[tid];
-        int rank = 0;
-        for (int j = 0; j < kk; ++j) {
-            const double lhs = L.accb[j] * pa, rhs = qa * L.G0[j];   // j before me?
-            rank += (lhs > rhs) || (lhs == rhs && L.ordq[j] < ta);
+    // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id.
+    // Rank counting; `parts` threads share a token (each counts over a stretch of the others).
+    {
+        const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
+        const int per = kST / parts;                       // tokens a part can hold
+        const int me = tid % per, part = tid / per;
+        if (tid < kk) L.cnt0[tid] = 0;
+        __syncthreads();
+        if (me < kk) {
+            const double qa = L.accb[me], pa = L.G0[me];
+            const int ta = L.ordq[me];
+            const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
+            int rank = 0;
+            for (int j = j0; j < j1; ++j) {
+                const double lhs = L.accb[j] * pa, rhs = qa * L.G0[j];   // j before me?
+                rank += (lhs > rhs) || (lhs == rhs && L.ordq[j] < ta);
+            }
+            if (parts > 1) atomicAdd(&L.cnt0[me], rank); else L.cnt0[me] = rank;
         }
-        L.tok[rank] = ta; L.qd[rank] = qa; L.pn[rank] = pa / ptot;
+        __syncthreads();
+        if (tid < kk) {
+            const int rank = L.cnt0[tid];
+            const double pa = L.G0[tid];
+            L.tok[rank] = L.ordq[tid]; L.qd[rank] = L.accb[tid]; L.pn[rank] = pa / ptot;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     GR_MARK("ranked");
     // ---- prefix sums in the order, sequentially (bit-reproducible), then F(m) = P_m - Q_m^n
@@ -1006,17 +1021,27 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 
     GR_MARK("records");
     // ---- truncation sets: fewest tokens by decreasing q with gamma_T <= tau / epsilon_T <= tau
-    if (tid < kk) {
-        const int mine_in = tid < h;
-        const float qa = static_cast<float>(L.qd[tid]);
-        const int ta = L.tok[tid];
-        int rank = 0;
-        for (int j = 0; j < kk; ++j) {
-            const int same = (j < h) == mine_in;
-            const float qj = static_cast<float>(L.qd[j]);
-            rank += same && ((qj > qa) || (qj == qa && L.tok[j] < ta));
+    {
+        const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
+        const int per = kST / parts;
+        const int me = tid % per, part = tid / per;
+        if (tid < kk) L.cnt1[tid] = 0;
+        __syncthreads();
+        if (me < kk) {
+            const int mine_in = me < h;
+            const float qa = static_cast<float>(L.qd[me]);
+            const int ta = L.tok[me];
+            const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
+            int rank = 0;
+            for (int j = j0; j < j1; ++j) {
+                const int same = (j < h) == mine_in;
+                const float qj = static_cast<float>(L.qd[j]);
+                rank += same && ((qj > qa) || (qj == qa && L.tok[j] < ta));
+            }
+            if (parts > 1) atomicAdd(&L.cnt1[me], rank); else L.cnt1[me] = rank;
         }
-        L.ordq[(mine_in ? 0 : h) + rank] = tid;
+        __syncthreads();
+        if (tid < kk) L.ordq[(tid < h ? 0 : h) + L.cnt1[tid]] = tid;
     }
     __syncthreads();
     const double Qh = L.Q[h];
