@@ -40,6 +40,11 @@ __device__ int g_nmark;
 #define GR_MARK(name)
 #endif
 
+// Operands of the light-token arithmetic, packed so that one token (phase 1) or one quadrature node
+// (phase 3) is three 16-byte LDS reads at constant offsets.
+struct alignas(16) NodeRec { double t, qw, T[4]; };          // abscissa, weight, total series at degrees n-1 .. n-4
+struct alignas(16) TokRec { double aw, e[4], pad; };         // weight, q^k / k! for k = 1..4
+
 struct Lds {
     // support, in ratio order
     int tok[KS]; int blk[KS]; int inT[KS]; int ordq[KS]; int apos[kMaxT];
@@ -59,6 +64,8 @@ struct Lds {
     double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
     double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa: aS = w dR/dw - ... (see routed_eval)
     double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
+    NodeRec nrec[64 + 16];          // nodes of the current chunk; the 16 beyond are zero (weight 0)
+    TokRec trec[kMaxT + 16];        // active tokens; the 16 beyond the last have aw = 1e300 (x = 0)
     double e2tab[32];               // 2^(-j/32)
     int nbig;                       // number of heavy tokens of the current program
     double work;                    // sum over evaluator calls of nodes x active tokens (thread 0 only)
@@ -227,42 +234,40 @@ __device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, 
 
 // Phase 1, light tokens: log(1 + x (e^u - 1)) = sum_k kappa_k(x) u^k / k!  with the cumulants of a
 // Bernoulli(x) variable, so the product of their factors is the exponential of four sums.
-// Tokens first, first + kSW, ... below m, four at a time; the LDS operands of the next four are
-// requested before the arithmetic of the current four so that their latency is covered.
-__device__ __forceinline__ void phase1_small_load(const Lds& L, int i0, int m, double (&aw)[4], double (&e)[4][4]) {
+// Tokens first, first + kSW, ... below m, four at a time (records beyond m contribute nothing); two
+// register sets alternate so that the LDS operands of the next four are requested before the
+// arithmetic of the current four.
+__device__ __forceinline__ void phase1_small_load(const Lds& L, int i0, TokRec (&r)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = L.trec[i0 + j * kSW];
+}
+__device__ __forceinline__ void phase1_small_quad(double (&K)[4][4], const TokRec (&r)[4], double t, const double* tab) {
+    double y[4], x[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) y[j] = t * r[j].aw;
+    exp_neg4(y, x, tab);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int i = i0 + j * kSW;
-        const int ii = i < m ? i : m - 1;
-        aw[j] = i < m ? L.aw[ii] : 1e300;                      // a missing token gets x = 0: no contribution
-#pragma unroll
-        for (int a = 0; a < 4; ++a) e[j][a] = L.etab[ii * 17 + 1 + a];
+        const double v = x[j] * (1.0 - x[j]);                  // kappa_2
+        const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
+        const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
+        K[j][0] = fma(x[j], r[j].e[0], K[j][0]);
+        K[j][1] = fma(v, r[j].e[1], K[j][1]);
+        K[j][2] = fma(k3, r[j].e[2], K[j][2]);
+        K[j][3] = fma(k4, r[j].e[3], K[j][3]);
     }
 }
 __device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, int first, int m, double t) {
     if (first >= m) return;
-    double awn[4], en[4][4];
-    phase1_small_load(L, first, m, awn, en);
-    for (int i0 = first; i0 < m; i0 += 4 * kSW) {
-        double y[4], x[4], e[4][4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            y[j] = t * awn[j];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) e[j][a] = en[j][a];
-        }
-        if (i0 + 4 * kSW < m) phase1_small_load(L, i0 + 4 * kSW, m, awn, en);
-        exp_neg4(y, x, L.e2tab);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const double v = x[j] * (1.0 - x[j]);                  // kappa_2
-            const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
-            const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
-            K[j][0] = fma(x[j], e[j][0], K[j][0]);
-            K[j][1] = fma(v, e[j][1], K[j][1]);
-            K[j][2] = fma(k3, e[j][2], K[j][2]);
-            K[j][3] = fma(k4, e[j][3], K[j][3]);
-        }
+    TokRec a[4], b[4];
+    phase1_small_load(L, first, a);
+    for (int i0 = first; i0 < m; i0 += 8 * kSW) {
+        const bool more = i0 + 4 * kSW < m;
+        if (more) phase1_small_load(L, i0 + 4 * kSW, b);
+        phase1_small_quad(K, a, t, L.e2tab);
+        if (!more) break;
+        if (i0 + 8 * kSW < m) phase1_small_load(L, i0 + 8 * kSW, a);
+        phase1_small_quad(K, b, t, L.e2tab);
     }
 }
 
@@ -297,49 +302,46 @@ __device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D +
 // Phase 3, a light token: (e^u - 1) / (1 + x (e^u - 1)) = u + (1/2 - x) u^2 + (1/6 - x + x^2) u^3 +
 // (1/24 - 7x/12 + 3x^2/2 - x^3) u^4 + ..., so the leave-one-out coefficient is a four-term sum over
 // T[n-1..n-4].  e[k] = q^k / k! (zero for k > n), so the brackets are multiplied by k!.
-// The node operands (uniform over the wave) of the next four nodes are requested before the
-// arithmetic of the current four.
-struct NodeOps { double t[4], qw[4], T[4][4]; };
-__device__ __forceinline__ void phase3_small_load(const Lds& L, int nu0, int nn, const int (&o)[4], NodeOps& r) {
+// This wave's nodes wv, wv + kSW, ..., four at a time from the node records (uniform over the wave;
+// records at or beyond nn carry weight 0); two register sets alternate as in phase 1.
+__device__ __forceinline__ void phase3_small_load(const Lds& L, int nu0, NodeRec (&r)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = L.nrec[nu0 + j * kSW];
+}
+__device__ __forceinline__ void phase3_small_quad(const NodeRec (&c)[4], const double (&e)[5], double wt, const double* tab,
+                                                  double& acc, double& at) {
+    double y[4], x[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) y[j] = c[j].t * wt;
+    exp_neg4(y, x, tab);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int nu = nu0 + j * kSW;
-        const int nv = nu < nn ? nu : nu0;
-        r.t[j] = L.tnode[nv];
-        r.qw[j] = nu < nn ? L.qwnode[nv] : 0.0;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) r.T[j][a] = L.Tl[nv * 17 + o[a]];
+        const double xx = x[j];
+        const double g2 = fma(-2.0, xx, 1.0);
+        const double g3 = fma(6.0 * xx, xx - 1.0, 1.0);
+        const double g4 = fma(xx, fma(xx, fma(-24.0, xx, 36.0), -14.0), 1.0);
+        double cn = e[1] * c[j].T[0];
+        cn = fma(e[2] * g2, c[j].T[1], cn);
+        cn = fma(e[3] * g3, c[j].T[2], cn);
+        cn = fma(e[4] * g4, c[j].T[3], cn);
+        const double term = c[j].qw * xx * cn;
+        acc += term;
+        at = fma(term, c[j].t, at);
     }
 }
-__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int n, int wv, int nn,
-                                               double& acc_t) {
+__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int wv, int nn, double& acc_t) {
     double acc = 0.0, at = 0.0;
-    const int o[4] = {n - 1, n >= 2 ? n - 2 : 0, n >= 3 ? n - 3 : 0, n >= 4 ? n - 4 : 0};
     acc_t = 0.0;
     if (wv >= nn) return acc;
-    NodeOps nx;
-    phase3_small_load(L, wv, nn, o, nx);
-    for (int nu0 = wv; nu0 < nn; nu0 += 4 * kSW) {
-        const NodeOps c = nx;
-        if (nu0 + 4 * kSW < nn) phase3_small_load(L, nu0 + 4 * kSW, nn, o, nx);
-        double y[4], x[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) y[j] = c.t[j] * wt;
-        exp_neg4(y, x, L.e2tab);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const double xx = x[j];
-            const double g2 = fma(-2.0, xx, 1.0);
-            const double g3 = fma(6.0 * xx, xx - 1.0, 1.0);
-            const double g4 = fma(xx, fma(xx, fma(-24.0, xx, 36.0), -14.0), 1.0);
-            double cn = e[1] * c.T[j][0];
-            cn = fma(e[2] * g2, c.T[j][1], cn);
-            cn = fma(e[3] * g3, c.T[j][2], cn);
-            cn = fma(e[4] * g4, c.T[j][3], cn);
-            const double term = c.qw[j] * xx * cn;
-            acc += term;
-            at = fma(term, c.t[j], at);
-        }
+    NodeRec a[4], b[4];
+    phase3_small_load(L, wv, a);
+    for (int nu0 = wv; nu0 < nn; nu0 += 8 * kSW) {
+        const bool more = nu0 + 4 * kSW < nn;
+        if (more) phase3_small_load(L, nu0 + 4 * kSW, b);
+        phase3_small_quad(a, e, wt, L.e2tab, acc, at);
+        if (!more) break;
+        if (nu0 + 8 * kSW < nn) phase3_small_load(L, nu0 + 8 * kSW, a);
+        phase3_small_quad(b, e, wt, L.e2tab, acc, at);
     }
     acc_t = at;
     return acc;
@@ -365,7 +367,8 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int nbig = L.nbig;
     double w = 0.0;
-    if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; }
+    if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; L.trec[tid].aw = w; }
+    if (tid < 16) { NodeRec z; z.t = 0.0; z.qw = 0.0; z.T[0] = z.T[1] = z.T[2] = z.T[3] = 0.0; L.nrec[64 + tid] = z; }
     const double wsum = block_sum<kSW>(tid < m ? w : 0.0, L.red);
     const double wmin = block_min<kSW>(tid < m ? w : 1e300, L.red);
     const double t_lo = kQuadLo / (slack + wsum);
@@ -464,8 +467,17 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
                 }
             }
             double tn = 0.0;
+            NodeRec rec; rec.t = t; rec.qw = qw; rec.T[0] = rec.T[1] = rec.T[2] = rec.T[3] = 0.0;
 #pragma unroll
-            for (int d = 0; d <= D; ++d) { L.Tl[lane * 17 + d] = T[d]; if (d == n) tn = T[d]; }
+            for (int d = 0; d <= D; ++d) {
+                L.Tl[lane * 17 + d] = T[d];
+                if (d == n) tn = T[d];
+                if (d == n - 1) rec.T[0] = T[d];
+                if (d == n - 2) rec.T[1] = T[d];
+                if (d == n - 3) rec.T[2] = T[d];
+                if (d == n - 4) rec.T[3] = T[d];
+            }
+            L.nrec[lane] = rec;
             r0 += wave_sum(qw * tn);
         }
         __syncthreads();
@@ -488,12 +500,15 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             acc += __shfl_xor(acc, 32); acct += __shfl_xor(acct, 32);
             if (lane < 16 && tok < nbig) { L.rpart[wv][tok] += acc; L.spart[wv][tok] += acct; }
         }
+#ifdef GR_DEBUG
+        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[7] += clock64() - c_d;
+#endif
         // light tokens
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             if (pass * 64 < m && (pass + 1) * 64 > nbig) {
                 double at;
-                racc[pass] += phase3_small(L, es[pass], ws[pass], n, wv, nn, at);
+                racc[pass] += phase3_small(L, es[pass], ws[pass], wv, nn, at);
                 sacc[pass] += at;
             }
         }
@@ -659,7 +674,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
         const double q = L.aq[tid], atot = ctx + qsum;
         double e = 1.0;
         L.etab[tid * 17] = 1.0;
-        for (int a = 1; a <= 16; ++a) { e = e * q / a; L.etab[tid * 17 + a] = e; }
+        for (int a = 1; a <= 16; ++a) { e = e * q / a; L.etab[tid * 17 + a] = e; if (a <= 4) L.trec[tid].e[a - 1] = e; }
         // light if the u^5 and later terms of its factor cannot change the z^n coefficient by more
         // than 1e-11 relative: C(n-1, 4) (q/atot)^4 / 5 < 1e-11; exact for n <= 4
         const double r = q / atot;
@@ -669,6 +684,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
         L.apd[tid] = pow_diff(atot, q, n);
     }
     if (tid < 32) L.e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
+    if (tid < 16) { TokRec z; z.aw = 1e300; z.e[0] = z.e[1] = z.e[2] = z.e[3] = 0.0; z.pad = 0.0; L.trec[m + tid] = z; }
     const int nheavy = block_sum_i<kSW>((tid < m && L.adeg[tid] != 0) ? 1 : 0, L.red);
     if (tid == 0) L.nbig = nheavy;
     __syncthreads();
@@ -692,9 +708,6 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
 #ifdef GR_DEBUG
         const long long it_c1 = clock64();
         if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
-#endif
-#ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("it %d m %d nbig %d slack %d err %.3e best %.3e hcount %d plain %d\n", it, m, L.nbig, slack, err, best_err, hcount, plain);
 #endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
@@ -934,6 +947,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             const int ta = L.ordq[me];
             const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
             int rank = 0;
+#pragma unroll 8
             for (int j = j0; j < j1; ++j) {
                 const double lhs = L.accb[j] * pa, rhs = qa * L.G0[j];   // j before me?
                 rank += (lhs > rhs) || (lhs == rhs && L.ordq[j] < ta);
@@ -1033,6 +1047,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             const int ta = L.tok[me];
             const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
             int rank = 0;
+#pragma unroll 8
             for (int j = j0; j < j1; ++j) {
                 const int same = (j < h) == mine_in;
                 const float qj = static_cast<float>(L.qd[j]);
@@ -1115,7 +1130,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
 
 #ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]);
+    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]); if (tid == 0 && blockIdx.x == GR_DEBUG) printf("p3 heavy part %lld nbig %d\n", g_dbg[7], L.nbig);
 #endif
     // ---- policy object
     int* o_order = sp.order + static_cast<size_t>(row) * KS;
