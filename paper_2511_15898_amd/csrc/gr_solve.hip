@@ -384,7 +384,9 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     long long c_a = clock64(), c_b = 0, c_c = 0, c_d = 0;
 #endif
     const double atot = ctx + qsum;
-    const double tail = step * t_lo / (exp(step) - 1.0);   // trapezoid sum of the nodes below t_lo, x = 1 there
+    const double estep = exp(step);
+    const double tail = step * t_lo / (estep - 1.0);       // trapezoid sum of the nodes below t_lo, x = 1 there
+    const double tail2 = step * t_lo * t_lo / (estep * estep - 1.0);   // the same for the integrand times t
     double fact = 1.0;
     for (int i = 2; i <= n; ++i) fact *= i;
     double r0 = 0.0;                                       // slack mass, accumulated by lane 0 of wave 0
@@ -521,7 +523,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     if (tid < m) {
         double r = L.apd[tid] * tail / fact;
         // the nodes below t_lo (x = 1 there) add tail to the integral of 1 and tail2 to that of t
-        double sq = L.apd[tid] * (step * t_lo * t_lo / (exp(2.0 * step) - 1.0)) / fact;
+        double sq = L.apd[tid] * tail2 / fact;
         for (int w2 = 0; w2 < kSW; ++w2) { r += L.rpart[w2][tid]; sq += L.spart[w2][tid]; }
         L.aR[tid] = r * L.aw[tid] * fact;
         L.aS[tid] = sq * L.aw[tid] * L.aw[tid] * fact;
@@ -541,11 +543,12 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
     const int tid = threadIdx.x;
     int nodes;
     routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
-    const double rsum = block_sum<kSW>(tid < m ? L.aR[tid] : 0.0, L.red);
+    // the sum of the routed masses is needed without slack (common term) and by the Newton iteration
+    const double rsum = (!slack || rsum_out) ? block_sum<kSW>(tid < m ? L.aR[tid] : 0.0, L.red) : 0.0;
     double f = 0.0;
     if (tid < m) {
-        f = log(L.at[tid] / L.aR[tid]);
-        f -= slack ? log(slack_target / L.R0acc) : log(tsum / rsum);
+        const double common = slack ? L.R0acc / slack_target : rsum / tsum;
+        f = log(L.at[tid] / L.aR[tid] * common);
         // The fixed-point step treats the routed mass as proportional to the weight; its true
         // logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a token loses to
         // itself), so the step of each coordinate is stretched by R / (R - S), at most kStretch.
@@ -553,7 +556,7 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
         const double stretch = (d * kStretch > R) ? R / d : kStretch;
         L.af[tid] = f * stretch;
     }
-    *rsum_out = rsum;
+    if (rsum_out) *rsum_out = rsum;
     return block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
 }
 
@@ -701,8 +704,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
 #ifdef GR_DEBUG
         const long long it_c0 = clock64();
 #endif
-        double rsum;
-        const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+        const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, nullptr);
         *evals += 1;
         double f = tid < m ? L.af[tid] : 0.0;
 #ifdef GR_DEBUG
@@ -738,33 +740,31 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
             __syncthreads();                               // Hf[cur] is complete
             {
                 // entry e of (upper triangle of the Gram matrix, then dF_a . f) goes to wave e mod 4;
-                // lanes cover the tokens, the sums of one wave are independent and overlap
+                // lanes cover the tokens.  The loop is unrolled, so the columns of an entry are constants.
                 const int wv = tid >> 6, lane = tid & 63;
-                constexpr int kPer = (kGram + kSW - 1) / kSW;
-                double pr[kPer];
 #pragma unroll
-                for (int j = 0; j < kPer; ++j) {
-                    const int e = wv + kSW * j;
+                for (int e = 0; e < kGram; ++e) {
+                    constexpr int kTri = kCols * (kCols + 1) / 2;
                     int ca = 0, cb = 0, idx = 0;
+#pragma unroll
                     for (int a2 = 0; a2 < kCols; ++a2)
+#pragma unroll
                         for (int b2 = a2; b2 < kCols; ++b2) { if (idx == e) { ca = a2; cb = b2; } ++idx; }
-                    const bool rhs = e >= idx;
-                    if (rhs) ca = e - idx;
-                    const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
+                    const bool rhs = e >= kTri;
+                    if (rhs) { ca = e - kTri; cb = 0; }
+                    if ((e % kSW) != wv) continue;
                     double acc = 0.0;
-                    if (e < kGram && ca < ncol && (rhs || cb < ncol)) {
+                    if (ca < ncol && (rhs || cb < ncol)) {
+                        const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
                         for (int i = lane; i < m; i += 64) {
                             const double fi = L.Hf[cur][i];
                             const double da = fi - L.Hf[sa][i];
                             acc = fma(da, rhs ? fi : fi - L.Hf[sb][i], acc);
                         }
+                        acc = wave_sum(acc);
                     }
-                    pr[j] = acc;
+                    if (lane == 0) L.gram[e] = acc;
                 }
-#pragma unroll
-                for (int j = 0; j < kPer; ++j) pr[j] = wave_sum(pr[j]);
-#pragma unroll
-                for (int j = 0; j < kPer; ++j) if (lane == 0 && wv + kSW * j < kGram) L.gram[wv + kSW * j] = pr[j];
             }
             __syncthreads();
             if (tid == 0) {
@@ -786,6 +786,9 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                     }
                 }
                 bool good = true;
+                double pivinv[kCols];
+#pragma unroll
+                for (int c = 0; c < kCols; ++c) pivinv[c] = 0.0;
 #pragma unroll
                 for (int c = 0; c < kCols; ++c) {
                     if (c < ncol) {
@@ -793,6 +796,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                         Gm[c][c] = Gm[c][c] * (1.0 + 1e-10) + 1e-300;
                         good = good && (Gm[c][c] > 0.0);
                         const double inv = 1.0 / Gm[c][c];
+                        pivinv[c] = inv;
 #pragma unroll
                         for (int r = c + 1; r < kCols; ++r) {
                             if (r < ncol) {
@@ -809,7 +813,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                     double sacc = Gm[c][kCols];
 #pragma unroll
                     for (int j = c + 1; j < kCols; ++j) if (j < ncol) sacc = fma(-Gm[c][j], gam[j], sacc);
-                    gam[c] = (c < ncol) ? sacc / Gm[c][c] : 0.0;
+                    gam[c] = (c < ncol) ? sacc * pivinv[c] : 0.0;
                 }
                 double gnorm = 0.0;
 #pragma unroll
