@@ -14,7 +14,7 @@ constexpr int kMaxT = GR_MAX_T;
 constexpr int kSelTile = kThreads * 4;    // tokens per streaming tile (one float4 per thread)
 constexpr int kSelCap = 2048;             // candidate keys held in LDS (>= kMaxSupport + kSelTile)
 constexpr int kMaxSplits = 8;             // workgroups that share one row in the select kernel
-constexpr int kHist = 6;                  // Anderson history length (current + 5)
+constexpr int kHist = 5;                  // Anderson history length (current + 4)
 
 // Per-row result of the solve kernel (one per row, in HBM).
 struct RowInfo {

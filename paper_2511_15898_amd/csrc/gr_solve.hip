@@ -32,7 +32,7 @@ constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
 
 #ifdef GR_DEBUG
-__device__ long long g_dbg[8];
+__device__ long long g_dbg[16];
 __device__ long long g_mark[16];
 __device__ int g_nmark;
 #define GR_MARK(name) if (threadIdx.x == 0 && blockIdx.x == GR_DEBUG) { g_mark[g_nmark++] = clock64() - kernel_c0; }
@@ -738,6 +738,10 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
             }
             // Gram matrix and right-hand side: one entry per thread, a loop over the tokens
             __syncthreads();                               // Hf[cur] is complete
+#ifdef GR_DEBUG
+            const long long mx0 = clock64();
+            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[8] += mx0 - it_c1;
+#endif
             {
                 // entry e of (upper triangle of the Gram matrix, then dF_a . f) goes to wave e mod 4;
                 // lanes cover the tokens.  The loop is unrolled, so the columns of an entry are constants.
@@ -767,6 +771,10 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                 }
             }
             __syncthreads();
+#ifdef GR_DEBUG
+            const long long mx1 = clock64();
+            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[9] += mx1 - mx0;
+#endif
             if (tid == 0) {
                 // normal equations by Gaussian elimination without pivoting (the matrix is symmetric
                 // positive definite after the ridge); fully unrolled so that it stays in registers
@@ -821,6 +829,9 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                 L.ok = (good && gnorm < 1e300) ? 1 : 0;
             }
             __syncthreads();
+#ifdef GR_DEBUG
+            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[10] += clock64() - mx1;
+#endif
             double cand = f;
 #pragma unroll
             for (int c = 0; c < kCols; ++c) cand -= (dA[c] + dF[c]) * L.gamma[c];
@@ -1134,7 +1145,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
 
 #ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]); if (tid == 0 && blockIdx.x == GR_DEBUG) printf("p3 heavy part %lld nbig %d\n", g_dbg[7], L.nbig);
+    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]); if (tid == 0 && blockIdx.x == GR_DEBUG) printf("p3 heavy part %lld nbig %d | mixing: head %lld gram %lld solve %lld\n", g_dbg[7], L.nbig, g_dbg[8], g_dbg[9], g_dbg[10]);
 #endif
     // ---- policy object
     int* o_order = sp.order + static_cast<size_t>(row) * KS;
