@@ -56,8 +56,8 @@ def main():
                     help="run one 256 MiB device-to-device copy first (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU; rows shard across GPUs without exchange "
-                 "(see DESIGN.md) and no multi-GPU figure is produced.  Use --gpus 1.")
+        sys.exit("bench.py: this build runs on ONE GPU; rows are independent and would shard across GPUs "
+                 "without any exchange, but no multi-GPU figure is produced.  Use --gpus 1.")
 
     import numpy as np
     import torch

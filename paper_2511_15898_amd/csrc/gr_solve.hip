@@ -7,6 +7,9 @@
 //   truncation sets T                                       (Alg. 1, Sec. 6.3)
 //   softmax weights of Theta_T / Phi_T by iterative scaling (Thm 6.5 / Thm 6.4)
 //
+// A second kernel (full_programs_kernel) runs the same programs for rows whose steps 1-2 were done in
+// HBM because the support is the whole vocabulary.
+//
 // The gradient of Theta_T / Phi_T is (mass routed to token j) - target_j.  The routed mass is a sum
 // over draft tuples; here it is evaluated in polynomial time from
 //     1/x = int_0^inf e^{-xt} dt,
@@ -22,7 +25,7 @@ namespace {
 constexpr int KS = kMaxSupport;
 constexpr int kST = 256;             // threads of the solve workgroup (one wave per SIMD: each may use all 512 registers)
 constexpr int kSW = kST / 64;
-constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation error ~1e-8 relative)
+constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation error ~1e-9 relative)
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
 constexpr int kNewtonMax = 32;       // largest program the Newton fallback takes
@@ -30,15 +33,6 @@ constexpr double kStretch = 4.0;      // cap on the per-coordinate stretch of th
 constexpr int kMixBudget = 60;       // evaluations given to the mixed fixed-point iteration before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
-
-#ifdef GR_DEBUG
-__device__ long long g_dbg[16];
-__device__ long long g_mark[16];
-__device__ int g_nmark;
-#define GR_MARK(name) if (threadIdx.x == 0 && blockIdx.x == GR_DEBUG) { g_mark[g_nmark++] = clock64() - kernel_c0; }
-#else
-#define GR_MARK(name)
-#endif
 
 // Operands of the light-token arithmetic, packed so that one token (phase 1) or one quadrature node
 // (phase 3) is three 16-byte LDS reads at constant offsets.
@@ -62,7 +56,7 @@ struct Lds {
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
     double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
-    double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa: aS = w dR/dw - ... (see routed_eval)
+    double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa t; aS_i = R_i - dR_i/d(log w_i)
     double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
     NodeRec nrec[64 + 16];          // nodes of the current chunk; the 16 beyond are zero (weight 0)
     TokRec trec[kMaxT + 16];        // active tokens; the 16 beyond the last have aw = 1e300 (x = 0)
@@ -363,7 +357,7 @@ __device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5
 // In: L.aq, L.aal, L.etab / L.nbig / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
 // Out: L.aR[0..m), L.R0acc (slack mass; meaningful when slack = 1).  All threads call it.
 template <int D>
-__device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum, int* nodes_used) {
+__device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int nbig = L.nbig;
     double w = 0.0;
@@ -379,10 +373,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
     if (N > 64 && range <= 0.5 * 63.0) { step = range / 63.0; N = 64; }
     if (N < 1) N = 1;
     if (N > 4096) N = 4096;
-    *nodes_used = N;
-#ifdef GR_DEBUG
-    long long c_a = clock64(), c_b = 0, c_c = 0, c_d = 0;
-#endif
     const double atot = ctx + qsum;
     const double estep = exp(step);
     const double tail = step * t_lo / (estep - 1.0);       // trapezoid sum of the nodes below t_lo, x = 1 there
@@ -412,9 +402,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
         const double t = t_lo * exp(step * node);
         const double qw = node < N ? step * t * exp_neg(slack * t) : 0.0;
         if (wv == 0) { L.tnode[lane] = t; L.qwnode[lane] = qw; }
-#ifdef GR_DEBUG
-        c_b = clock64();
-#endif
         // ---- phase 1
         if (nbig > 0) {
             double A[4][D + 1];
@@ -438,9 +425,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             for (int k = 0; k < 4; ++k) L.cum[(wv * 4 + k) * 64 + lane] = (K[0][k] + K[1][k]) + (K[2][k] + K[3][k]);
         }
         __syncthreads();
-#ifdef GR_DEBUG
-        c_c = clock64();
-#endif
         // ---- phase 2 (wave 0)
         if (wv == 0) {
             double Kt[4];
@@ -483,9 +467,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             r0 += wave_sum(qw * tn);
         }
         __syncthreads();
-#ifdef GR_DEBUG
-        c_d = clock64();
-#endif
         // ---- phase 3
         const int nn = min(64, N - c0);
         // heavy tokens: 16 per round, lane = (token, node group); this wave's nodes are wv, wv+4, ...,
@@ -502,9 +483,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             acc += __shfl_xor(acc, 32); acct += __shfl_xor(acct, 32);
             if (lane < 16 && tok < nbig) { L.rpart[wv][tok] += acc; L.spart[wv][tok] += acct; }
         }
-#ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[7] += clock64() - c_d;
-#endif
         // light tokens
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
@@ -529,9 +507,6 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
         L.aS[tid] = sq * L.aw[tid] * L.aw[tid] * fact;
     }
     __syncthreads();
-#ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) { g_dbg[0] += c_b - c_a; g_dbg[1] += c_c - c_b; g_dbg[2] += c_d - c_c; g_dbg[3] += clock64() - c_d; g_dbg[4] += 1; }
-#endif
 }
 
 // One evaluation and the stopping measure: max_i | log(target_i / routed_i) - common term |, where the
@@ -541,8 +516,7 @@ template <int D>
 __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
                               double tsum, double* rsum_out) {
     const int tid = threadIdx.x;
-    int nodes;
-    routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
+    routed_eval<D>(L, m, n, ctx, slack, qsum);
     // the sum of the routed masses is needed without slack (common term) and by the Newton iteration
     const double rsum = (!slack || rsum_out) ? block_sum<kSW>(tid < m ? L.aR[tid] : 0.0, L.red) : 0.0;
     double f = 0.0;
@@ -583,8 +557,7 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
         for (int k = 0; k < nfree; ++k) {
             if (tid == k) L.aal[k] += kFd;
             __syncthreads();
-            int nodes;
-            routed_eval<D>(L, m, n, ctx, slack, qsum, &nodes);
+            routed_eval<D>(L, m, n, ctx, slack, qsum);
             if (tid < nfree) L.J[tid * LD + k] = (L.aR[tid] - L.nR[tid]) / kFd;
             if (tid == k) L.aal[k] -= kFd;
             __syncthreads();
@@ -629,9 +602,6 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
             __syncthreads();
             slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * L.af[tid] : 0.0, L.red);
         }
-#ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) printf("newton m %d slack %d evals %d err %.3e smax %.3e slope0 %.3e\n", m, slack, *evals, err, smax, slope0);
-#endif
         if (tid < m) L.nsave[tid] = L.aal[tid];
         __syncthreads();
         // Backtracking on the slope: the objective is convex, so it decreases along the step as long
@@ -645,9 +615,6 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
             *evals += 1;
             const double ratio2 = slack ? (rsum + L.R0acc) / (tsum + slack_target) : rsum / tsum;
             const double slope = block_sum<kSW>(tid < nfree ? (L.aR[tid] - L.at[tid] * ratio2) * clip * L.nstep[tid] : 0.0, L.red);
-#ifdef GR_DEBUG
-            if (tid == 0 && blockIdx.x == GR_DEBUG) printf("   ls %d lam %.3e err2 %.3e slope %.3e\n", ls, lam, err2, slope);
-#endif
             ok = (err2 < 1e300) && (slope <= 0.5 * fabs(slope0) || err2 < err);
             if (!ok) lam *= 0.5;
         }
@@ -701,16 +668,9 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
             if (tid < m) L.aal[tid] -= amax;
             __syncthreads();
         }
-#ifdef GR_DEBUG
-        const long long it_c0 = clock64();
-#endif
         const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, nullptr);
         *evals += 1;
         double f = tid < m ? L.af[tid] : 0.0;
-#ifdef GR_DEBUG
-        const long long it_c1 = clock64();
-        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[5] += it_c1 - it_c0;
-#endif
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
             // a mixed step went astray: back to the best point, plain (monotone) steps for a while
@@ -736,12 +696,8 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                 dF[c] = on ? f - L.Hf[slot][tid] : 0.0;
                 dA[c] = on ? L.aal[tid] - L.Ha[slot][tid] : 0.0;
             }
-            // Gram matrix and right-hand side: one entry per thread, a loop over the tokens
+            // Gram matrix and right-hand side
             __syncthreads();                               // Hf[cur] is complete
-#ifdef GR_DEBUG
-            const long long mx0 = clock64();
-            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[8] += mx0 - it_c1;
-#endif
             {
                 // entry e of (upper triangle of the Gram matrix, then dF_a . f) goes to wave e mod 4;
                 // lanes cover the tokens.  The loop is unrolled, so the columns of an entry are constants.
@@ -771,10 +727,6 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                 }
             }
             __syncthreads();
-#ifdef GR_DEBUG
-            const long long mx1 = clock64();
-            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[9] += mx1 - mx0;
-#endif
             if (tid == 0) {
                 // normal equations by Gaussian elimination without pivoting (the matrix is symmetric
                 // positive definite after the ridge); fully unrolled so that it stays in registers
@@ -829,17 +781,11 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
                 L.ok = (good && gnorm < 1e300) ? 1 : 0;
             }
             __syncthreads();
-#ifdef GR_DEBUG
-            if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[10] += clock64() - mx1;
-#endif
             double cand = f;
 #pragma unroll
             for (int c = 0; c < kCols; ++c) cand -= (dA[c] + dF[c]) * L.gamma[c];
             const int solved = L.ok;
             const double cmax = block_max<kSW>(tid < m ? fabs(cand) : 0.0, L.red);
-#ifdef GR_DEBUG
-            (void)0;
-#endif
             // a mixed step longer than 3 in log weight is cut to that length (the same cap as the
             // Newton fallback); a failed solve drops the history
             if (solved && cmax < 1e300) stepv = cmax > 3.0 ? cand * (3.0 / cmax) : cand;
@@ -852,9 +798,6 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
         if (tid < m) L.aal[tid] += stepv;
         ++hcount;
         __syncthreads();
-#ifdef GR_DEBUG
-        if (tid == 0 && blockIdx.x == GR_DEBUG) g_dbg[6] += clock64() - it_c1;
-#endif
     }
     __syncthreads();
     if (result != 0 && mix_iters < max_iter && best_err < 1e300) {
@@ -895,9 +838,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     const int tid = threadIdx.x;
     const int row = blockIdx.x;
     const int n = sp.n, V = sp.V;
-#ifdef GR_DEBUG
-    const long long kernel_c0 = clock64();
-#endif
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
     info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0;
@@ -947,8 +887,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     // unsorted: token ids in ordq, q in accb (exact float values), p gathered into G0
     if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ordq[tid]]);
     __syncthreads();
-
-    GR_MARK("merged");
     // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id.
     // Rank counting; `parts` threads share a token (each counts over a stretch of the others).
     {
@@ -977,8 +915,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         }
         __syncthreads();
     }
-
-    GR_MARK("ranked");
     // ---- prefix sums in the order, sequentially (bit-reproducible), then F(m) = P_m - Q_m^n
     {
 #pragma clang fp contract(off)
@@ -994,8 +930,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         }
         __syncthreads();
     }
-
-    GR_MARK("prefix");
     // ---- H*: the smallest minimising prefix
     double fmin_local = 1e300;
     for (int m = tid; m <= kk; m += kST) fmin_local = fmin(fmin_local, L.F[m]);
@@ -1003,8 +937,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     double hcand = 1e9;
     for (int m = tid; m <= kk; m += kST) if (L.F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
     const int h = static_cast<int>(block_min<kSW>(hcand, L.red));
-
-    GR_MARK("hstar");
     // ---- G = suffix minima of F (Hillis-Steele over kk+1 entries)
     for (int m = tid; m <= kk; m += kST) L.G0[m] = L.F[m];
     __syncthreads();
@@ -1047,8 +979,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         if (m < kk) L.blk[m] = (m >= h) ? L.cnt0[m] : 0; // token m (rank m+1) lies after record cnt0[m]
     }
     __syncthreads();
-
-    GR_MARK("records");
     // ---- truncation sets: fewest tokens by decreasing q with gamma_T <= tau / epsilon_T <= tau
     {
         const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
@@ -1091,7 +1021,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             L.inT[tid] = (tid < h) ? ((ipow(Qh, n) - an) > sp.tau) : ((1.0 - an) > sp.tau);
         }
     }
-    GR_MARK("trunc");
     // ---- start weights: target / Pr[token drawn within its system], inner ones in the slack's gauge
     if (tid < kk) {
         const int hi = (tid < h) ? h : L.blo[L.blk[tid] + 1];
@@ -1102,9 +1031,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
 
-#ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) { printf("prologue done at %lld cycles (kk %d h %d) marks:", clock64() - kernel_c0, kk, h); for (int i = 0; i < g_nmark; ++i) printf(" %lld", g_mark[i]); printf("\n"); }
-#endif
     // ---- the convex programs: program 0 = inner system, then every outer block of two or more tokens
     int status = GR_ROW_OK, evals = 0;
     for (int b = (h > 0 ? 0 : 1); b <= nblk && status != GR_ROW_TRUNC_CAP; ++b) {
@@ -1144,9 +1070,6 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         __syncthreads();
     }
 
-#ifdef GR_DEBUG
-    if (tid == 0 && blockIdx.x == GR_DEBUG) printf("programs done at %lld cycles evals %d | setup %lld p1 %lld p2 %lld p3 %lld (evals %lld) defect_eval %lld mixing %lld\n", clock64() - kernel_c0, evals, g_dbg[0], g_dbg[1], g_dbg[2], g_dbg[3], g_dbg[4], g_dbg[5], g_dbg[6]); if (tid == 0 && blockIdx.x == GR_DEBUG) printf("p3 heavy part %lld nbig %d | mixing: head %lld gram %lld solve %lld\n", g_dbg[7], L.nbig, g_dbg[8], g_dbg[9], g_dbg[10]);
-#endif
     // ---- policy object
     int* o_order = sp.order + static_cast<size_t>(row) * KS;
     int* o_block = sp.block + static_cast<size_t>(row) * KS;
