@@ -49,7 +49,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--tol", type=float, default=1e-4, help="the paper's error threshold tau")
-    ap.add_argument("--workload", default="large", choices=["large", "llm", "small"])
+    ap.add_argument("--workload", default="large", choices=["large", "llm", "small", "stress"],
+                    help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -63,7 +64,7 @@ def main():
     import torch
     from paper_2511_15898_amd import binding as gr, workloads as W
 
-    wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small}[args.workload]()
+    wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small, "stress": W.stress}[args.workload]()
     dev = torch.device("cuda:0")
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     d = torch.from_numpy(wl.drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)

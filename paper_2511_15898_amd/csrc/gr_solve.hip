@@ -29,7 +29,8 @@ constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation 
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
 constexpr int kNewtonMax = 32;       // largest program the Newton fallback takes
-constexpr double kStretch = 4.0;      // cap on the per-coordinate stretch of the fixed-point step
+constexpr double kStretch = 4.0;      // first cap on the per-coordinate stretch of the fixed-point step
+constexpr int kStall = 3;            // iterations without a better point before the cap is halved
 constexpr int kMixBudget = 60;       // evaluations given to the mixed fixed-point iteration before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
@@ -52,7 +53,7 @@ struct Lds {
     int adeg[kMaxT];                // degree at which the token's exponential series may be cut
     // Newton fallback (programs of at most kNewtonMax variables)
     double J[kNewtonMax * (kNewtonMax + 1)]; double nR[kNewtonMax]; double nstep[kNewtonMax]; double nsave[kNewtonMax];
-    double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT];
+    double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
     double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
@@ -511,7 +512,8 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
 
 // One evaluation and the stopping measure: max_i | log(target_i / routed_i) - common term |, where the
 // common term is log(slack_target / slack mass) with slack, log(sum target / sum routed) without
-// (the latter is zero in exact arithmetic and removes the common quadrature error).  f -> L.af.
+// (the latter is zero in exact arithmetic and removes the common quadrature error).  f -> L.af;
+// L.aR and L.aS stay valid until the next evaluation.
 template <int D>
 __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
                               double tsum, double* rsum_out) {
@@ -523,12 +525,7 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
     if (tid < m) {
         const double common = slack ? L.R0acc / slack_target : rsum / tsum;
         f = log(L.at[tid] / L.aR[tid] * common);
-        // The fixed-point step treats the routed mass as proportional to the weight; its true
-        // logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a token loses to
-        // itself), so the step of each coordinate is stretched by R / (R - S), at most kStretch.
-        const double R = L.aR[tid], d = R - L.aS[tid];
-        const double stretch = (d * kStretch > R) ? R / d : kStretch;
-        L.af[tid] = f * stretch;
+        L.af[tid] = f;
     }
     if (rsum_out) *rsum_out = rsum;
     return block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
@@ -658,8 +655,8 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
     const int nheavy = block_sum_i<kSW>((tid < m && L.adeg[tid] != 0) ? 1 : 0, L.red);
     if (tid == 0) L.nbig = nheavy;
     __syncthreads();
-    int hcount = 0, plain = 0;
-    double best_err = 1e300;
+    int hcount = 0, plain = 0, since = 0;
+    double best_err = 1e300, cap = kStretch;
     int result = 1;
     const int mix_iters = (m <= kNewtonMax && max_iter > kMixBudget) ? kMixBudget : max_iter;
     for (int it = 1; it <= mix_iters; ++it) {
@@ -670,17 +667,33 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
         }
         const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, nullptr);
         *evals += 1;
-        double f = tid < m ? L.af[tid] : 0.0;
+        // The fixed-point step log(target / routed) treats the routed mass as proportional to the
+        // weight; its true logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a
+        // token loses to itself), so the step of each coordinate is stretched by R / (R - S), at most
+        // `cap`.  The stretched iteration is no longer monotone: when kStall iterations bring no
+        // better point it returns to the best one with half the cap; at cap 1 (the plain step, whose
+        // stopping measure need not fall at every step) it is left alone.
+        double f = 0.0, ratio = 1.0;
+        if (tid < m) {
+            f = L.af[tid];
+            const double R = L.aR[tid], d = R - L.aS[tid];
+            ratio = (d > 0.0) ? fmin(R / d, 1e30) : 1e30;
+        }
         if (err <= rel_tol) { result = 0; break; }
         if (!(err < 1e300) || err > 100.0 * best_err) {
-            // a mixed step went astray: back to the best point, plain (monotone) steps for a while
+            // a mixed step went astray: back to the best point, unmixed steps for a while
             if (!(best_err < 1e300)) break;        // no finite point seen: give up on this program
-            if (tid < m) { L.aal[tid] = L.aBest[tid]; f = L.fBest[tid]; }
-            hcount = 0; plain = 20;
+            if (tid < m) { L.aal[tid] = L.aBest[tid]; f = L.fBest[tid]; ratio = L.rBest[tid]; }
+            hcount = 0; plain = 20; since = 0;
         } else if (err < best_err) {
-            best_err = err;
-            if (tid < m) { L.aBest[tid] = L.aal[tid]; L.fBest[tid] = f; }
+            best_err = err; since = 0;
+            if (tid < m) { L.aBest[tid] = L.aal[tid]; L.fBest[tid] = f; L.rBest[tid] = ratio; }
+        } else if (cap > 1.0 && ++since >= kStall) {
+            if (tid < m) { L.aal[tid] = L.aBest[tid]; f = L.fBest[tid]; ratio = L.rBest[tid]; }
+            hcount = 0; since = 0;
+            cap = fmax(1.0, 0.5 * cap);
         }
+        f *= fmin(ratio, cap);
         const int cur = it % kHist;
         if (tid < m) { L.Ha[cur][tid] = L.aal[tid]; L.Hf[cur][tid] = f; }
         const int ncol = plain > 0 ? 0 : min(hcount, kHist - 1);
