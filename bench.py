@@ -99,6 +99,20 @@ def main():
     node_tokens = float(stats["node_tokens"].sum().item())
     gr.gr_destroy(h)
 
+    # what a plain device copy of the same number of bytes reaches on this machine (read + write counted)
+    nbytes = 8 * wl.V * wl.B
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev); dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        dst.copy_(src)
+    e1.record(); torch.cuda.synchronize()
+    copy_gbs = 2.0 * nbytes / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9
+    del src, dst
+
     ms_per_step = dt / args.steps * 1e3
     algo_bytes = 8.0 * wl.V * wl.B                 # one read of the p row and of the q row per solve
     roofline = None
@@ -126,6 +140,8 @@ def main():
         roofline["events_steps"] = prof["steps"]
         roofline["select_hbm_frac"] = algo_bytes / (kernels["select_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS
         roofline["step_hbm_frac"] = algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+        roofline["device_copy_GBs"] = copy_gbs
+        roofline["select_vs_device_copy"] = algo_bytes / (kernels["select_kernel"] * 1e-3) / 1e9 / copy_gbs
     out = {
         "metric": "verifier solves/sec",
         "value": wl.B * args.steps / dt,
