@@ -916,7 +916,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 #pragma unroll 8
             for (int j = j0; j < j1; ++j) {
                 const double lhs = L.accb[j] * pa, rhs = qa * L.G0[j];   // j before me?
-                rank += (lhs > rhs) || (lhs == rhs && L.ordq[j] < ta);
+                rank += static_cast<int>(lhs > rhs) | (static_cast<int>(lhs == rhs) & static_cast<int>(L.ordq[j] < ta));
             }
             if (parts > 1) atomicAdd(&L.cnt0[me], rank); else L.cnt0[me] = rank;
         }
@@ -1009,7 +1009,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             for (int j = j0; j < j1; ++j) {
                 const int same = (j < h) == mine_in;
                 const float qj = static_cast<float>(L.qd[j]);
-                rank += same && ((qj > qa) || (qj == qa && L.tok[j] < ta));
+                rank += same & (static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & static_cast<int>(L.tok[j] < ta)));
             }
             if (parts > 1) atomicAdd(&L.cnt1[me], rank); else L.cnt1[me] = rank;
         }

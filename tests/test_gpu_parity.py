@@ -61,3 +61,15 @@ def test_stress_cells(n, k):
     rows = sorted(set([0, 17, 50]) | set(int(x) for x in near))
     compare_rows(wl, out, rows, 1e-6)
     assert np.all(np.abs(out["pi"].sum(1) - 1.0) < 1e-4)
+
+
+def test_stress_cell_at_full_batch():
+    """One config 5 cell at its own size (1024 rows x 128256 tokens, n = 8, top-k 128), the launch
+    shape `bench.py --workload stress` times: alpha* on every 16th row, everything on sampled rows."""
+    wl = W.stress()
+    out = run_gpu(wl, 1e-4, want_slice=False)
+    assert np.all(out["status"] == 0)
+    sub = W.Workload(wl.name, 64, wl.V, wl.n, wl.k, wl.p[::16], wl.q[::16], wl.drafts[::16], wl.uniforms[::16])
+    check_alpha_all_rows(sub, {"accept_prob": out["accept_prob"][::16]})
+    near = np.flatnonzero(wl.meta["near"])[:2]
+    compare_rows(wl, out, sorted(set([0, 333, 1023]) | set(int(x) for x in near)), 1e-4)
