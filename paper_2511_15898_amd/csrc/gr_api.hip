@@ -15,6 +15,7 @@ struct gr_handle_s {
     // scratch of the select kernel
     unsigned long long* cand = nullptr; int* cand_count = nullptr;
     double* part_psum = nullptr; double* part_qsum = nullptr; int* part_bad = nullptr;
+    double* newton_ws = nullptr;   // [max_B, kMaxT * (kMaxT + 1)] Jacobian scratch of the solver's Newton fallback
     double* piece_psum = nullptr; int piece_stride = 0;   // float64 sums of p per 256 tokens, [max_B, piece_stride]
     // policy object of the last solve
     int* order = nullptr; int* block = nullptr; double* weight = nullptr; double* rho = nullptr; double* pnorm = nullptr;
@@ -46,7 +47,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->newton_ws, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -131,6 +132,7 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* 
               dev_alloc(&h->info, rows);
     h->piece_stride = (max_V + kSelTile - 1) / kSelTile * (kSelTile / 256) + kMaxSplits * (kSelTile / 256);
     ok = ok && dev_alloc(&h->piece_psum, rows * h->piece_stride);
+    ok = ok && dev_alloc(&h->newton_ws, rows * kMaxT * (kMaxT + 1));
     if (!ok) { free_all(h); delete h; (void)hipGetLastError(); return GR_ENOMEM; }
     if (cfg && (cfg->flags & GR_FLAG_PROFILE)) {
         h->profile = true;
@@ -166,7 +168,7 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         FullParams& f = h->full;
         f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.max_T = h->max_T; f.max_iter = h->max_iter;
         f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
-        f.info = h->info; f.accept_prob = accept_prob; f.status = status;
+        f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
         mark(h, 0, stream);
         mark(h, 1, stream);
         launch_full_prologue(f, stream);
@@ -192,7 +194,7 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
     sp.part_bad = h->part_bad;
     sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
-    sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status;
+    sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status; sp.newton_ws = h->newton_ws;
     if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
     mark(h, 2, stream);
     h->solved = true; h->p = p; h->B = B; h->V = V; h->n = n;

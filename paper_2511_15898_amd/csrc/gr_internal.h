@@ -45,6 +45,7 @@ struct SolveParams {
     int* order; int* block; double* weight; double* rho; double* pnorm;   // [B, kMaxSupport]
     RowInfo* info;                    // [B]
     float* accept_prob; int* status;  // caller's outputs [B]
+    double* newton_ws;                // [B, kMaxT * (kMaxT + 1)] Jacobian scratch of the Newton fallback
 };
 
 // Workspace and arguments of the full-vocabulary path (no top-k).  Per-token arrays are row-major with
@@ -63,6 +64,7 @@ struct FullParams {
     int* nblk;         // [B] number of outer blocks
     int* tcount;       // [B, 2] sizes of the two truncation sets
     RowInfo* info; float* accept_prob; int* status;
+    double* newton_ws; // [B, kMaxT * (kMaxT + 1)] Jacobian scratch of the Newton fallback
 };
 constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 9 * 8 + 5 * 4 + 4 + 8;
 

@@ -28,10 +28,9 @@ constexpr int kSW = kST / 64;
 constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation error ~1e-9 relative)
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
-constexpr int kNewtonMax = 32;       // largest program the Newton fallback takes
 constexpr double kStretch = 4.0;      // first cap on the per-coordinate stretch of the fixed-point step
 constexpr int kStall = 3;            // iterations without a better point before the cap is halved
-constexpr int kMixBudget = 60;       // evaluations given to the mixed fixed-point iteration before Newton takes over
+constexpr int kMixBudget = 60;       // the mixed fixed-point iteration gets kMixBudget + m evaluations before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
 
@@ -51,8 +50,8 @@ struct Lds {
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
     double etab[kMaxT * 17];        // q^a / a!, a = 0..16
     int adeg[kMaxT];                // degree at which the token's exponential series may be cut
-    // Newton fallback (programs of at most kNewtonMax variables)
-    double J[kNewtonMax * (kNewtonMax + 1)]; double nR[kNewtonMax]; double nstep[kNewtonMax]; double nsave[kNewtonMax];
+    // Newton fallback (its Jacobian lives in a per-row HBM scratch)
+    double nR[kMaxT]; double nstep[kMaxT]; double nsave[kMaxT]; int nused[kMaxT]; int ncolof[kMaxT];
     double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
@@ -532,15 +531,17 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
 }
 
 // Damped Newton iteration on routed(alpha) = target with a finite-difference Jacobian (the Hessian of
-// Theta_T / Phi_T in alpha), for programs of at most kNewtonMax variables on which the fixed-point
-// iteration is slow (a target that nearly exhausts the tuples containing its token).  Without slack
-// the last weight is pinned (the system is singular along the common shift).  Starts from L.aal.
+// Theta_T / Phi_T in alpha), for programs on which the fixed-point iteration is slow (a target that
+// nearly exhausts the tuples containing its token).  One step costs one evaluation per variable, so
+// it only takes over when the mixed iteration has used up its budget.  Without slack the last weight
+// is pinned (the system is singular along the common shift).  Starts from L.aal.
+// J: this row's scratch in HBM, kMaxT rows of kMaxT + 1 doubles (the last column is the right-hand side).
 template <int D>
-__device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
+__device__ int newton_program(Lds& L, double* J, int m, int n, double ctx, int slack, double slack_target, double qsum,
                               double tsum, double rel_tol, int max_evals, int* evals) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int nfree = slack ? m : m - 1;
-    constexpr int LD = kNewtonMax + 1;
+    constexpr int LD = kMaxT + 1;
     constexpr double kFd = 1e-6;
     double rsum;
     double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
@@ -555,36 +556,32 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
             if (tid == k) L.aal[k] += kFd;
             __syncthreads();
             routed_eval<D>(L, m, n, ctx, slack, qsum);
-            if (tid < nfree) L.J[tid * LD + k] = (L.aR[tid] - L.nR[tid]) / kFd;
+            if (tid < nfree) J[tid * LD + k] = (L.aR[tid] - L.nR[tid]) / kFd;
             if (tid == k) L.aal[k] -= kFd;
             __syncthreads();
         }
         *evals += nfree;
-        if (tid < nfree) L.J[tid * LD + kNewtonMax] = L.at[tid] * ratio - L.nR[tid];
+        if (tid < nfree) { J[tid * LD + kMaxT] = L.at[tid] * ratio - L.nR[tid]; L.nused[tid] = 0; L.ncolof[tid] = -1; L.nstep[tid] = 0.0; }
         __syncthreads();
-        // Gauss-Jordan with partial pivoting in wave 0: lane r owns row r
-        if (tid < 64) {
-            bool used = false;
-            int my_col = -1;
-            for (int c = 0; c < nfree; ++c) {
-                double mag = (lane < nfree && !used) ? fabs(L.J[lane * LD + c]) : -1.0;
-                double best = mag; int who = lane;
-                for (int o = 32; o > 0; o >>= 1) {
-                    const double ob = __shfl_xor(best, o); const int ow = __shfl_xor(who, o);
-                    if (ob > best || (ob == best && ow < who)) { best = ob; who = ow; }
-                }
-                const double piv = L.J[who * LD + c];
-                if (lane == who) { used = true; my_col = c; }
-                if (lane < nfree && lane != who && piv != 0.0) {
-                    const double fct = L.J[lane * LD + c] / piv;
-                    for (int j = c; j <= kNewtonMax; ++j)
-                        if (j < nfree || j == kNewtonMax) L.J[lane * LD + j] -= fct * L.J[who * LD + j];
-                }
+        // Gauss-Jordan with partial pivoting: thread r owns row r
+        for (int c = 0; c < nfree; ++c) {
+            const double mag = (tid < nfree && !L.nused[tid]) ? fabs(J[tid * LD + c]) : -1.0;
+            const double best = block_max<kSW>(mag, L.red);
+            if (!(best > 0.0)) continue;                   // no pivot left in this column: its step stays 0
+            const int who = static_cast<int>(block_min<kSW>(mag == best ? static_cast<double>(tid) : 1e9, L.red));
+            const double piv = J[who * LD + c];
+            if (tid < nfree && tid != who) {
+                const double fct = J[tid * LD + c] / piv;
+                for (int j = c; j < nfree; ++j) J[tid * LD + j] -= fct * J[who * LD + j];
+                J[tid * LD + kMaxT] -= fct * J[who * LD + kMaxT];
             }
-            if (lane < nfree && my_col >= 0) {
-                const double dg = L.J[lane * LD + my_col];
-                L.nstep[my_col] = dg != 0.0 ? L.J[lane * LD + kNewtonMax] / dg : 0.0;
-            }
+            if (tid == who) { L.nused[tid] = 1; L.ncolof[tid] = c; }
+            __syncthreads();
+        }
+        if (tid < nfree && L.ncolof[tid] >= 0) {
+            const int my_col = L.ncolof[tid];
+            const double dg = J[tid * LD + my_col];
+            L.nstep[my_col] = dg != 0.0 ? J[tid * LD + kMaxT] / dg : 0.0;
         }
         __syncthreads();
         const double smax = block_max<kSW>(tid < nfree ? fabs(L.nstep[tid]) : 0.0, L.red);
@@ -630,9 +627,20 @@ __device__ int newton_program(Lds& L, int m, int n, double ctx, int slack, doubl
 // In: L.aq, L.at (targets, already scaled to the tuple mass), L.aal (start log weights).
 // Out: L.aal.  `evals` counts evaluator calls.
 template <int D>
-__device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, int slack, double slack_target,
+__device__ __forceinline__ int solve_program(Lds& L, double* newton_ws, int m, int n, double ctx, int slack, double slack_target,
                              double rel_tol, int max_iter, int* evals) {
     const int tid = threadIdx.x;
+    if (n == 1) {
+        // One draft: a tuple is a single token, so the routed mass of token i is q_i w_i / (1 + w_i)
+        // with the slack term (the single-draft rule, w_i = t_i / (q_i - t_i) in closed form; a token
+        // whose target exhausts its draws takes everything) and q_i whatever the weights without it.
+        if (slack && tid < m) {
+            const double d = L.aq[tid] - L.at[tid];
+            L.aal[tid] = (d > 0.0) ? log(L.at[tid] / d) : 690.0;
+        }
+        __syncthreads();
+        return 0;
+    }
     const double qsum = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
     const double tsum = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
     if (tid < m) {
@@ -658,7 +666,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
     int hcount = 0, plain = 0, since = 0;
     double best_err = 1e300, cap = kStretch;
     int result = 1;
-    const int mix_iters = (m <= kNewtonMax && max_iter > kMixBudget) ? kMixBudget : max_iter;
+    const int mix_iters = (max_iter > kMixBudget + m) ? kMixBudget + m : max_iter;
     for (int it = 1; it <= mix_iters; ++it) {
         if (!slack) {
             const double amax = block_max<kSW>(tid < m ? L.aal[tid] : -1e300, L.red);
@@ -816,7 +824,7 @@ __device__ __forceinline__ int solve_program(Lds& L, int m, int n, double ctx, i
     if (result != 0 && mix_iters < max_iter && best_err < 1e300) {
         if (tid < m) L.aal[tid] = L.aBest[tid];
         __syncthreads();
-        result = newton_program<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, rel_tol, max_iter, evals);
+        result = newton_program<D>(L, newton_ws, m, n, ctx, slack, slack_target, qsum, tsum, rel_tol, max_iter, evals);
     }
     return result;
 }
@@ -1075,7 +1083,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         const double w0sum = block_sum<kSW>(tid < m ? L.wgt[L.apos[tid]] : 0.0, L.red);
         if (tid < m) L.at[tid] *= scale;
         __syncthreads();
-        const int rc = solve_program<D>(L, m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
+        const int rc = solve_program<D>(L, sp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
         if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
         const double wv = (tid < m) ? exp(L.aal[tid]) : 0.0;
         const double wsum = block_sum<kSW>(wv, L.red);
@@ -1176,7 +1184,7 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
             const double slack_target = -Fh * scale;
             if (tid < m) L.at[tid] *= scale;
             __syncthreads();
-            const int rc = solve_program<D>(L, m, n, ctx, 1, slack_target, fp.rel_tol, fp.max_iter, &evals);
+            const int rc = solve_program<D>(L, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 1, slack_target, fp.rel_tol, fp.max_iter, &evals);
             if (rc != 0) status = GR_ROW_ITER_CAP;
             if (tid < m) weight[L.apos[tid]] = exp(L.aal[tid]);
             __syncthreads();
@@ -1229,7 +1237,7 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
             const double w0sum = block_sum<kSW>(tid < m ? exp(L.aal[tid]) : 0.0, L.red);
             if (tid < m) L.at[tid] *= scale;
             __syncthreads();
-            const int rc = solve_program<D>(L, m, n, ctx, 0, 0.0, fp.rel_tol, fp.max_iter, &evals);
+            const int rc = solve_program<D>(L, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 0, 0.0, fp.rel_tol, fp.max_iter, &evals);
             if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
             const double wvv = (tid < m) ? exp(L.aal[tid]) : 0.0;
             const double wsum = block_sum<kSW>(wvv, L.red);

@@ -123,3 +123,27 @@ def test_call_level_errors():
             gr.gr_solve(h, p.double(), p, 2, 8, 1e-6)
     finally:
         gr.gr_destroy(h)
+
+
+def test_one_draft_with_a_large_support_uses_the_closed_form():
+    """n = 1 on a 256-token support: tokens near the edge of H* have targets that almost exhaust
+    their draws, where a fixed-point iteration crawls; the single-draft weights are closed-form."""
+    wl = W.llm_shaped(B=4, V=915, n=1, k=256, temperature=(0.4, 1.6), near_identical_frac=0.2, seed_sub=956657)
+    out = run_gpu(wl, 1e-7)
+    assert np.all(out["status"] <= 1) and np.any(out["status"] == 0) and out["iterations"].max() == 0
+    compare_rows(wl, out, range(wl.B), 1e-7)
+    # closed form of the acceptance at n = 1: sum_i min(p_i, q_i) over the renormalised top-k row
+    for b in range(wl.B):
+        sup = W.topk_support(wl.q[b], wl.k)
+        qs = wl.q[b, sup].astype(np.float64); qs /= qs.sum()
+        ps = wl.p[b, sup].astype(np.float64) / float(np.sum(wl.p[b], dtype=np.float64))
+        assert abs(out["accept_prob"][b] - np.minimum(ps, qs).sum()) < 1e-5
+
+
+def test_hard_program_beyond_32_variables_reaches_the_newton_fallback():
+    """A 54-variable inner program on which the mixed fixed-point iteration needs thousands of
+    steps: the Newton fallback (Jacobian in device scratch) must finish it within the cap."""
+    wl = W.small(B=7, V=1045, n=2, k=64, seed_sub=226351)
+    out = run_gpu(wl, 1e-6)
+    assert np.all(out["status"] == 0)
+    compare_rows(wl, out, range(wl.B), 1e-6)
