@@ -52,7 +52,7 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_MAX_N         16    /* largest number of drafts */
 
 typedef struct {
-    int    max_iter;   /* iteration cap per convex program; <= 0 selects 1000 */
+    int    max_iter;   /* cap on the evaluations of the routed masses per convex program; <= 0 selects 1000 */
     int    max_T;      /* cap on the variables of one program; <= 0 or > GR_MAX_T selects GR_MAX_T */
     double rel_tol;    /* stop when every routed mass is within this relative distance of its
                           target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-8, an order
@@ -62,7 +62,10 @@ typedef struct {
 
 #define GR_FLAG_PROFILE 1      /* record HIP events around every kernel launch (see gr_profile_read) */
 
-/* Create a handle able to serve up to max_B rows of up to max_V tokens.  cfg may be NULL. */
+/* Create a handle able to serve up to max_B rows of up to max_V tokens.  cfg may be NULL.
+ * Device memory held by the handle: about 150 KB per row (candidate keys, the policy object of
+ * GR_MAX_SUPPORT entries, the Jacobian scratch of the solver's Newton fallback) plus 8 bytes per
+ * 256 tokens and row; GR_ENOMEM if it cannot be allocated. */
 int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* cfg);
 int gr_destroy(gr_handle h);
 
