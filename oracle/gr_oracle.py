@@ -267,7 +267,11 @@ def newton_polish(n, ctx, slack, q, target, slack_target, alpha, rtol, max_iter,
             J[:, k] = (evaluator(n, ctx, slack, q, np.exp(a2))[0] - R) / 1e-6
         evals += free
         scale = 1.0 if slack else R.sum() / target.sum()
-        step = np.linalg.solve(J[:free, :], (target * scale - R)[:free])
+        try:
+            step = np.linalg.solve(J[:free, :], (target * scale - R)[:free])
+        except np.linalg.LinAlgError:
+            # a weight so large that its difference quotients vanish: minimum-norm step instead
+            step = np.linalg.lstsq(J[:free, :], (target * scale - R)[:free], rcond=None)[0]
         step = step * min(1.0, 2.0 / max(1e-300, float(np.max(np.abs(step)))))
         lam = 1.0
         while True:

@@ -23,6 +23,9 @@ struct Slice {
     int tok[GR_MAX_N];         // in order of first appearance
     int pos[GR_MAX_N];         // rank position in the support, -1 if absent
     double pi[GR_MAX_N];       // probability of each distinct draft
+    double wv[GR_MAX_N];       // its weight, its probability under p, its block (loaded by one thread each)
+    double pv[GR_MAX_N];
+    int bv[GR_MAX_N];
     double acc;                // sum of pi over the drafts
     double scale;              // multiplies the residual weight of every other token
     int mode;
@@ -58,6 +61,13 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
         }
     }
     __syncthreads();
+    if (tid < S.nd) {
+        const int pos = S.pos[tid];
+        S.wv[tid] = pos >= 0 ? weight[pos] : 0.0;
+        S.bv[tid] = pos >= 0 ? block[pos] : -1;
+        S.pv[tid] = static_cast<double>(prow[S.tok[tid]]);
+    }
+    __syncthreads();
     if (tid == 0) {
         const int nd = S.nd;
         if (S.mode == kBadDraft) {
@@ -65,7 +75,7 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
             S.acc = 0.0; S.scale = 0.0;
         } else if (info.status != GR_ROW_OK) {
             double a = 0.0;
-            for (int i = 0; i < nd; ++i) { S.pi[i] = static_cast<double>(prow[S.tok[i]]) / info.p_total; a += S.pi[i]; }
+            for (int i = 0; i < nd; ++i) { S.pi[i] = S.pv[i] / info.p_total; a += S.pi[i]; }
             S.acc = a; S.scale = 1.0; S.mode = kFallback;
         } else {
             int mmax = -1; bool missing = false;
@@ -75,20 +85,21 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
                 S.acc = 0.0; S.scale = 0.0; S.mode = kBadDraft;
             } else if (mmax < info.h) {
                 double s = 0.0;
-                for (int i = 0; i < nd; ++i) s += weight[S.pos[i]];
+                for (int i = 0; i < nd; ++i) s += S.wv[i];
                 const double den = 1.0 + s;
-                for (int i = 0; i < nd; ++i) S.pi[i] = weight[S.pos[i]] / den;
+                for (int i = 0; i < nd; ++i) S.pi[i] = S.wv[i] / den;
                 S.acc = 1.0 - 1.0 / den;
                 S.scale = info.res_total > 0.0 ? (1.0 / den) / info.res_total : 0.0;
                 S.mode = kInner;
             } else {
-                const int b = block[mmax];
+                int b = -1;
+                for (int i = 0; i < nd; ++i) if (S.pos[i] == mmax) b = S.bv[i];
                 double s = 0.0; int members = 0;
                 for (int i = 0; i < nd; ++i)
-                    if (S.pos[i] >= info.h && block[S.pos[i]] == b) { s += weight[S.pos[i]]; ++members; }
+                    if (S.pos[i] >= info.h && S.bv[i] == b) { s += S.wv[i]; ++members; }
                 for (int i = 0; i < nd; ++i) {
-                    const bool in = S.pos[i] >= info.h && block[S.pos[i]] == b;
-                    S.pi[i] = in ? (s > 0.0 ? weight[S.pos[i]] / s : 1.0 / members) : 0.0;
+                    const bool in = S.pos[i] >= info.h && S.bv[i] == b;
+                    S.pi[i] = in ? (s > 0.0 ? S.wv[i] / s : 1.0 / members) : 0.0;
                 }
                 S.acc = 1.0; S.scale = 0.0; S.mode = kOuter;
             }
