@@ -39,7 +39,7 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_ENOMEM       (-2)   /* device allocation failed */
 #define GR_ESTATE       (-3)   /* gr_verify / gr_policy_* before a successful gr_solve */
 #define GR_EHIP         (-4)   /* a HIP runtime call failed */
-#define GR_EUNSUPPORTED (-5)   /* a top-k above GR_MAX_SUPPORT and below V; dense export of a full-V policy */
+#define GR_EUNSUPPORTED (-5)   /* V >= 2^24 with a support above GR_MAX_SUPPORT; dense export of such a policy */
 
 /* per-row status written by gr_solve */
 #define GR_ROW_OK         0
@@ -73,9 +73,9 @@ int gr_destroy(gr_handle h);
  * p, q        [B, V] float32 row-major, each row a distribution (q before top-k).
  * n           number of i.i.d. drafts per row, 1..GR_MAX_N.
  * k           top-k applied to q (ties: lower token id); k <= 0 or k >= V means none.
- *             A top-k above GR_MAX_SUPPORT and below V is refused with GR_EUNSUPPORTED.
- *             Without top-k on V > GR_MAX_SUPPORT the support lives in a device workspace that
- *             this call allocates or grows (136 bytes per token and row); V must stay below 2^24.
+ *             A support above GR_MAX_SUPPORT (no top-k on a larger V, or a larger top-k) lives in a
+ *             device workspace that this call allocates or grows (136 bytes per token of V and
+ *             row); V must then stay below 2^24, otherwise GR_EUNSUPPORTED.
  * tol         the paper's error threshold tau (Alg. 1), >= 0: truncation sets are the fewest
  *             tokens by decreasing q with gamma_T <= tol (inner) / epsilon_T <= tol (outer).
  * accept_prob [B] float32 out: alpha* (Thm 3.1).       status [B] int32 out: GR_ROW_*.
@@ -113,7 +113,7 @@ int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double
 
 /* One row of the policy object, the first `count` ranks (count <= the row's support): the same
  * arrays as gr_policy_export.  This is the only export of a policy over a support above
- * GR_MAX_SUPPORT (no top-k), whose rows hold up to V entries.  Device pointers, any may be NULL. */
+ * GR_MAX_SUPPORT, whose rows hold up to V entries.  Device pointers, any may be NULL. */
 int gr_policy_export_row(gr_handle h, int row, int count, int* order, int* block, double* weight,
                          double* rho, void* hip_stream);
 

@@ -160,13 +160,13 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     const int k_eff = (k <= 0 || k >= V) ? V : k;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (k_eff > kMaxSupport) {
-        // no top-k on a vocabulary above GR_MAX_SUPPORT: the HBM-resident path
-        if (k_eff != V || V >= (1 << 24)) return GR_EUNSUPPORTED;
+        // a support above GR_MAX_SUPPORT (no top-k, or a large one): the HBM-resident path
+        if (V >= (1 << 24)) return GR_EUNSUPPORTED;
         h->solved = false;
         const int rc = prepare_full(h, B, V);
         if (rc != GR_OK) return rc;
         FullParams& f = h->full;
-        f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.max_T = h->max_T; f.max_iter = h->max_iter;
+        f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.k = k_eff; f.max_T = h->max_T; f.max_iter = h->max_iter;
         f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
         f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
         mark(h, 0, stream);
@@ -320,7 +320,7 @@ extern "C" const char* gr_strerror(int code) {
         case GR_ENOMEM: return "device allocation failed";
         case GR_ESTATE: return "no solved policy in this handle";
         case GR_EHIP: return "HIP runtime error";
-        case GR_EUNSUPPORTED: return "support larger than GR_MAX_SUPPORT with a top-k below V, or a dense export of a full-vocabulary policy";
+        case GR_EUNSUPPORTED: return "a vocabulary of 2^24 tokens or more with a support above GR_MAX_SUPPORT, or a dense export of such a policy";
         default: return "unknown error";
     }
 }

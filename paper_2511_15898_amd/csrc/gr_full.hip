@@ -1,6 +1,6 @@
 // Full-vocabulary support: steps 1 and 2 of the verifier (Sec. 5.1 ratio order and prefix psi, Sec. 6
 // H*, alpha*, outer residuals of Thm 6.2, records, truncation sets of Alg. 1) for a draft distribution
-// without top-k, where the support (up to V tokens) does not fit LDS.
+// without top-k or with a top-k above GR_MAX_SUPPORT, where the support (up to V tokens) does not fit LDS.
 //
 // Every per-token array lives in a per-handle HBM workspace, row-major with stride V + 2; one
 // 256-thread workgroup works through a row.  The arithmetic that decides integers (prefix sums, F,
@@ -130,7 +130,8 @@ __device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot
 
 }  // namespace
 
-// ---- kernel 1: row sums and validity, the support in token order, sort by decreasing q/p (ties by id).
+// ---- kernel 1: row sums and validity, the support (all positive entries of q, or the k largest) in
+// token order, sort by decreasing q/p (ties by id).
 // The sort key is the correctly rounded float64 quotient q/p: for float32 inputs two different
 // ratios differ by at least 2^-48 relative, so their quotients differ and keep their order, and equal
 // ratios give equal quotients -- the same order as the exact cross-product comparison (Sec. 5.1).
@@ -159,12 +160,44 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
         if (tid == 0) mark_bad(fp, row, ptot, qtot);
         return;
     }
-    // the support (q > 0) in token order, with its keys
+    // With a top-k below the number of positive entries: order the positive entries by decreasing q
+    // (ties by token id) and flag the first k of them; the support is then the flagged tokens.
+    int* member = fp.flag + row * vs;                       // by token id here; reused by rank later
+    bool by_flag = false;
+    if (fp.k < V) {
+        int cnt = 0;
+        for (int t0 = 0; t0 < V; t0 += kThreads) {
+            const int i = t0 + tid;
+            const float qv = i < V ? qr[i] : 0.f;
+            const bool in = qv > 0.f;
+            const unsigned long long mask = __ballot(in);
+            if (lane == 0) wtot[wv] = __popcll(mask);
+            __syncthreads();
+            int off = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+            int tile_total = 0;
+            for (int w = 0; w < kWaves; ++w) { if (w < wv) off += wtot[w]; tile_total += wtot[w]; }
+            if (in) {
+                k0[off] = (static_cast<unsigned long long>(~__float_as_uint(qv)) << 24) | static_cast<unsigned long long>(i);
+                v0[off] = i;
+            }
+            if (i < V) member[i] = 0;
+            cnt += tile_total;
+            __syncthreads();
+        }
+        if (cnt > fp.k) {
+            const int res = block_radix_sort(k0, v0, k1, v1, cnt, S);
+            const int* sorted = res ? v1 : v0;
+            for (int r = tid; r < fp.k; r += kThreads) member[sorted[r]] = 1;
+            by_flag = true;
+        }
+        __syncthreads();
+    }
+    // the support in token order, with its keys
     int kk = 0;
     for (int t0 = 0; t0 < V; t0 += kThreads) {
         const int i = t0 + tid;
         const float qv = i < V ? qr[i] : 0.f;
-        const bool in = qv > 0.f;
+        const bool in = by_flag ? (i < V && member[i] != 0) : qv > 0.f;
         const unsigned long long mask = __ballot(in);
         if (lane == 0) wtot[wv] = __popcll(mask);
         __syncthreads();

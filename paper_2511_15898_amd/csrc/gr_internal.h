@@ -53,6 +53,7 @@ struct SolveParams {
 struct FullParams {
     const float* p; const float* q;
     int B, V, n, max_T, max_iter;
+    int k;             // top-k on q (V: none)
     double tau, rel_tol;
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p

@@ -1127,7 +1127,6 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
     if (info.status == GR_ROW_BAD) return;
     const int kk = info.support, h = info.h;
     const float* pr = fp.p + static_cast<size_t>(row) * V;
-    const float* qr = fp.q + static_cast<size_t>(row) * V;
     const int* order = fp.order + row * vs; const int* byq = fp.byq + row * vs;
     const double* qn = fp.qn + row * vs; const double* Q = fp.Q + row * vs; const double* F = fp.F + row * vs;
     const double* rho = fp.rho + row * vs; const double* tgt = fp.tgt + row * vs;
@@ -1137,9 +1136,8 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
     const double Fh = F[h];
 
     // tokens outside the support keep all of p as residual; then the support by rank
-    for (int i = tid; i < V; i += kST) {
-        if (!(qr[i] > 0.f)) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
-    }
+    for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
+    __syncthreads();
     for (int r = tid; r < kk; r += kST) {
         const int hi = (r < h) ? h : blo[blk[r] + 1];
         const double top = Q[hi];

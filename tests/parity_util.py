@@ -9,12 +9,12 @@ EDGE_TOL = 1e-5         # a uniform this close to a CDF edge may fall either way
 
 
 def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=None, export_rows=None):
-    """Run the HIP path.  A policy over more than GR_MAX_SUPPORT tokens (no top-k on a large V) has no
+    """Run the HIP path.  A policy over more than GR_MAX_SUPPORT tokens (no top-k on a large V, or a large top-k) has no
     dense export: its rows listed in `export_rows` are fetched one by one into out["rows"]."""
     import torch
     from paper_2511_15898_amd import binding as gr
     dev = torch.device("cuda:0")
-    full = (wl.k <= 0 or wl.k >= wl.V) and wl.V > gr.GR_MAX_SUPPORT
+    full = (wl.V if (wl.k <= 0 or wl.k >= wl.V) else wl.k) > gr.GR_MAX_SUPPORT
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     d = torch.from_numpy(wl.drafts if drafts is None else drafts).to(dev)
     u = torch.from_numpy(wl.uniforms).to(dev)

@@ -94,9 +94,9 @@ def test_bad_rows_bad_drafts_and_determinism():
         assert np.array_equal(a["rows"][r]["weight"], b["rows"][r]["weight"])
 
 
-def test_uniform_rows_at_full_size_and_refused_top_k():
-    """p = q uniform over 128256 tokens: all ratios tie (order = token id), alpha* = 1.  A top-k between
-    GR_MAX_SUPPORT and V is refused."""
+def test_uniform_rows_at_full_size():
+    """p = q uniform over 128256 tokens: all ratios tie (order = token id), alpha* = 1; with a top-k of
+    1000 all q tie as well and the support is the 1000 lowest token ids."""
     import torch
     from paper_2511_15898_amd import binding as gr
     dev = torch.device("cuda:0")
@@ -113,9 +113,10 @@ def test_uniform_rows_at_full_size_and_refused_top_k():
         assert np.allclose(acc.cpu().numpy(), 1.0, atol=1e-6)
         assert np.array_equal(row["order"].cpu().numpy(), np.arange(V))
         assert np.all(tok.cpu().numpy() >= 0) and np.all(tok.cpu().numpy() < V)
-        with pytest.raises(gr.GrError) as e:
-            gr.gr_solve(h, p, p, 4, 1000, 1e-6)
-        assert e.value.code == gr.GR_EUNSUPPORTED
+        acc, st = gr.gr_solve(h, p, p, 4, 1000, 1e-6)    # ties in q: the 1000 lowest token ids
+        row = gr.gr_policy_export_row(h, 1, 1000, dev)
+        torch.cuda.synchronize()
+        assert np.array_equal(row["order"].cpu().numpy(), np.arange(1000))
     finally:
         gr.gr_destroy(h)
 
@@ -137,3 +138,15 @@ def test_stress_full_vocab_cell_at_full_batch():
         _, _, F = G.prefix_psi(wl.p[b][order].astype(np.float64) / pt, wl.q[b][order], wl.n)
         assert abs(out["accept_prob"][b] - (1.0 + F.min())) < 1e-5
         assert out["h_size"][b] == int(np.argmin(F)) or np.sort(F)[1] - np.sort(F)[0] < 1e-13
+
+
+@pytest.mark.parametrize("V,n,k,tol", [(5000, 4, 300, 1e-4), (3000, 2, 1000, 1e-4), (1200, 8, 257, 1e-3)])
+def test_top_k_above_the_lds_capacity(V, n, k, tol):
+    """A top-k between GR_MAX_SUPPORT and V: the k largest q (ties by token id) are selected by a sort
+    in HBM, everything after that is the full-vocabulary path."""
+    wl = W.llm_shaped(B=12, V=V, n=n, k=k, seed_sub=60 + n)
+    out = run_gpu(wl, tol, export_rows=range(wl.B))
+    assert np.all(out["support"] == k)
+    check_alpha_all_rows(wl, out)
+    stats = compare_rows(wl, out, range(wl.B), tol)
+    assert stats["rows"] == wl.B

@@ -24,7 +24,7 @@ def _case(rng):
         wl = W.tiny(B=B, V=V, n=min(n, 4) if V ** min(n, 4) < 1e6 else 2, seed_sub=sub)
         wl = dataclasses.replace(wl, k=k, drafts=W.draw_drafts(wl.q, k, wl.n, rng))
     elif kind == 1:
-        V = int(rng.integers(40, 3000)); k = min(int(rng.choice([1, 3, 8, 32, 100, 256, 0])), V)
+        V = int(rng.integers(40, 3000)); k = min(int(rng.choice([1, 3, 8, 32, 100, 256, 300, 1000, 0])), V)
         wl = W.llm_shaped(B=B, V=V, n=n, k=k, temperature=(0.4, 1.6), near_identical_frac=0.2, seed_sub=sub)
     elif kind == 2:
         V = int(rng.integers(300, 2500))
@@ -49,7 +49,7 @@ def test_random_configurations(seed):
     rows = 0
     for _ in range(40):
         wl, tol, max_T = _case(rng)
-        full = (wl.k <= 0 or wl.k >= wl.V) and wl.V > 256
+        full = (wl.V if (wl.k <= 0 or wl.k >= wl.V) else wl.k) > 256
         out = run_gpu(wl, tol, max_T=max_T, export_rows=range(wl.B) if full else None)
         try:
             stats = compare_rows(wl, out, range(wl.B), tol, max_T=max_T)
