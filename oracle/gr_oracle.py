@@ -302,13 +302,16 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
         # One draft: a tuple is a single token, so Theta_T separates: routed_i = q_i w_i / (1 + w_i)
         # and the stationary point is w_i = target_i / (q_i - target_i) (the single-draft rule);
         # without slack routed_i = q_i whatever the weights, and the start weights are kept.
+        # The point is exact wherever every target lies below its token's draw probability (no defect
+        # is measured: re-evaluating it would lose all digits when a weight is huge); a target at or
+        # above it has no finite weight and the program counts as not converged.
         w = np.asarray(w0, np.float64).copy()
         if slack:
             gap = q - target
-            w = np.where(gap > 0, target / np.where(gap > 0, gap, 1.0), 1e300)
-        R, R0 = evaluator(n, ctx, slack, q, w)
-        f = np.log(target / R) - (math.log(slack_target / R0) if slack else math.log(target.sum() / R.sum()))
-        return w, 0, float(np.max(np.abs(f)))
+            if not np.all(gap > 0):
+                return np.where(gap > 0, target / np.where(gap > 0, gap, 1.0), 1e300), 0, float("inf")
+            w = target / gap
+        return w, 0, 0.0
     alpha = np.log(np.asarray(w0, np.float64))
     hist_a, hist_f = [], []
     err = np.inf

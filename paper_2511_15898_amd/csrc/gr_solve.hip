@@ -632,14 +632,17 @@ __device__ __forceinline__ int solve_program(Lds& L, double* newton_ws, int m, i
     const int tid = threadIdx.x;
     if (n == 1) {
         // One draft: a tuple is a single token, so the routed mass of token i is q_i w_i / (1 + w_i)
-        // with the slack term (the single-draft rule, w_i = t_i / (q_i - t_i) in closed form; a token
-        // whose target exhausts its draws takes everything) and q_i whatever the weights without it.
+        // with the slack term (the single-draft rule, w_i = t_i / (q_i - t_i) in closed form) and q_i
+        // whatever the weights without it.
+        // A scaled target at or above its token's draw probability has no finite weight: the program
+        // is reported as not converged, like an iteration that ran into its cap.
+        int stuck = 0;
         if (slack && tid < m) {
             const double d = L.aq[tid] - L.at[tid];
-            L.aal[tid] = (d > 0.0) ? log(L.at[tid] / d) : 690.0;
+            stuck = !(d > 0.0);
+            L.aal[tid] = stuck ? 690.0 : log(L.at[tid] / d);
         }
-        __syncthreads();
-        return 0;
+        return block_sum_i<kSW>(stuck, L.red) ? 1 : 0;
     }
     const double qsum = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
     const double tsum = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
