@@ -27,7 +27,7 @@ FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) on the default
 # workload, scaled by what the same counters read for a 256 MiB device copy in the same run
 # (profiles/hbm_traffic_large_vocab.md).  Only valid for that workload at the default tau.
-MEASURED_TRAFFIC_BYTES = {"select_kernel": 266625000, "solve_kernel": 8870000, "verify_kernel": 498000}
+MEASURED_TRAFFIC_BYTES = {"select_kernel": 266632000, "solve_kernel": 8921000, "verify_kernel": 603000}
 
 
 def cpu_baseline(wl, tol, budget_s=15.0):
