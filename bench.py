@@ -5,6 +5,12 @@ One "step" = the whole hot path over one batch of synthetic input already reside
 gr_solve (streaming support selection + per-row solve) followed by gr_verify.  Default workload:
 the large-vocabulary configuration (B=256 rows, V=128256, n=8 drafts, top-k 128).
 
+Two timed regions of the same K steps: first on one stream with HIP events around every launch (per-
+kernel launch durations, the roofline), then with the steps dealt round-robin to --streams handles on
+their own HIP streams (independent batches: a solve launch lasts as long as its slowest row, and the
+next batch's kernels fill the CUs that its finished rows have freed).  `value` is the second region's
+throughput; the first region's is reported beside it.
+
 Prints ONE JSON line: solves/s, ms per step, the roofline of the dominant kernel (durations from
 HIP events recorded around every launch of the timed region) and the CPU checker timed on a
 bounded sample of the same rows.
@@ -53,6 +59,9 @@ def main():
                     help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="handles / HIP streams the steps of the second timed region are dealt to (1: skip that region); "
+                         "three of them plus the default stream fill the four hardware queues of a process")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -98,6 +107,34 @@ def main():
     status = st.cpu().numpy(); iters = stats["evaluations"].cpu().numpy()
     node_tokens = float(stats["node_tokens"].sum().item())
     gr.gr_destroy(h)
+    single = {"value": wl.B * args.steps / dt, "ms_per_step": dt / args.steps * 1e3}
+
+    # second region: the same K steps dealt to several handles, each on its own stream
+    ns = max(1, min(args.streams, 8))
+    if ns > 1:
+        hs = [gr.gr_create(wl.B, wl.V) for _ in range(ns)]
+        ss = [torch.cuda.Stream() for _ in range(ns)]
+        outs = [(torch.empty_like(acc), torch.empty_like(st), torch.empty_like(tok), torch.empty_like(ok)) for _ in range(ns)]
+
+        def pstep(i):
+            j = i % ns
+            a, s_, t_, o_ = outs[j]
+            gr.gr_solve(hs[j], p, q, wl.n, wl.k, args.tol, a, s_, stream=ss[j])
+            gr.gr_verify(hs[j], d, u, t_, o_, stream=ss[j])
+
+        for i in range(max(args.warmup, 2 * ns)):
+            pstep(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            pstep(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        same = all(torch.equal(tok, o[2]) and torch.equal(acc, o[0]) for o in outs)
+        for hh in hs:
+            gr.gr_destroy(hh)
+        if not same:
+            sys.exit("bench.py: the pipelined region gave different results than the single-stream region")
 
     # what a plain device copy of the same number of bytes reaches on this machine (read + write counted)
     nbytes = 8 * wl.V * wl.B
@@ -136,6 +173,7 @@ def main():
         if args.workload == "large" and abs(args.tol - 1e-4) < 1e-12:
             roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dom)
             roofline["traffic_all_kernels"] = MEASURED_TRAFFIC_BYTES or None
+        roofline["region"] = "single-stream region (launch durations; in the multi-stream region kernels of different steps overlap)"
         roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
         roofline["events_steps"] = prof["steps"]
         roofline["select_hbm_frac"] = algo_bytes / (kernels["select_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS
@@ -151,7 +189,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
-                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol},
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "streams": ns},
+        "single_stream": single,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],
         "solver_evaluations_mean": float(iters.mean()), "solver_evaluations_max": int(iters.max()),
         "roofline": roofline,
