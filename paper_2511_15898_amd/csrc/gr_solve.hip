@@ -39,7 +39,11 @@ constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the 
 struct alignas(16) NodeRec { double t, qw, T[4]; };          // abscissa, weight, total series at degrees n-1 .. n-4
 struct alignas(16) TokRec { double aw, e[4], pad; };         // weight, q^k / k! for k = 1..4
 
+// D: the series degree of the kernel (>= n): the per-token and per-node series hold D + 1 terms, so the
+// kernels of small D leave LDS for a streaming workgroup of the next batch beside a live row.
+template <int D>
 struct Lds {
+    static constexpr int kS = D + 1;  // stride of a series
     // support, in ratio order
     int tok[KS]; int blk[KS]; int inT[KS]; int ordq[KS]; int apos[kMaxT];
     int flag[KS + 2]; int cnt0[KS + 2]; int cnt1[KS + 2]; int blo[KS + 2];
@@ -48,14 +52,14 @@ struct Lds {
     // one convex program
     double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aw[kMaxT]; double aR[kMaxT]; double af[kMaxT];
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
-    double etab[kMaxT * 17];        // q^a / a!, a = 0..16
+    double etab[kMaxT * kS];        // q^a / a!, a = 0..D
     int adeg[kMaxT];                // degree at which the token's exponential series may be cut
     // Newton fallback (its Jacobian lives in a per-row HBM scratch)
     double nR[kMaxT]; double nstep[kMaxT]; double nsave[kMaxT]; int nused[kMaxT]; int ncolof[kMaxT];
     double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
-    double tnode[64]; double qwnode[64]; double Tl[64 * 17]; double rpart[kSW][kMaxT];
+    double tnode[64]; double qwnode[64]; double Tl[64 * kS]; double rpart[kSW][kMaxT];
     double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa t; aS_i = R_i - dR_i/d(log w_i)
     double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
     NodeRec nrec[64 + 16];          // nodes of the current chunk; the 16 beyond are zero (weight 0)
@@ -67,7 +71,7 @@ struct Lds {
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
         unsigned long long keys[kSelCap];
-        double part[kSW * 17 * 64];
+        double part[kSW * kS * 64];
     } u;
 };
 
@@ -212,7 +216,7 @@ __device__ __forceinline__ void loo_coeff4(const double (&T)[4][D + 1], const do
 // Phase 1, tokens that keep their full factor: tokens i0, i0+4, i0+8, i0+12 (below `bound`) into the
 // four running products.
 template <int D>
-__device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, int i0, int bound, double t) {
+__device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds<D>& L, int i0, int bound, double t) {
     double y[4], x[4], e[4][D + 1];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -220,7 +224,7 @@ __device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, 
         const int ii = i < bound ? i : i0;
         y[j] = i < bound ? t * L.aw[ii] : 1000.0;             // a missing token gets x = 0: its factor is 1
 #pragma unroll
-        for (int a = 1; a <= D; ++a) e[j][a] = L.etab[ii * 17 + a];
+        for (int a = 1; a <= D; ++a) e[j][a] = L.etab[ii * (D + 1) + a];
     }
     exp_neg4(y, x, L.e2tab);
     mul_factor4<D, D>(A, x, e);
@@ -231,7 +235,8 @@ __device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds& L, 
 // Tokens first, first + kSW, ... below m, four at a time (records beyond m contribute nothing); two
 // register sets alternate so that the LDS operands of the next four are requested before the
 // arithmetic of the current four.
-__device__ __forceinline__ void phase1_small_load(const Lds& L, int i0, TokRec (&r)[4]) {
+template <class LdsT>
+__device__ __forceinline__ void phase1_small_load(const LdsT& L, int i0, TokRec (&r)[4]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) r[j] = L.trec[i0 + j * kSW];
 }
@@ -251,7 +256,8 @@ __device__ __forceinline__ void phase1_small_quad(double (&K)[4][4], const TokRe
         K[j][3] = fma(k4, r[j].e[3], K[j][3]);
     }
 }
-__device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, int first, int m, double t) {
+template <class LdsT>
+__device__ __forceinline__ void phase1_small(double (&K)[4][4], const LdsT& L, int first, int m, double t) {
     if (first >= m) return;
     TokRec a[4], b[4];
     phase1_small_load(L, first, a);
@@ -267,7 +273,7 @@ __device__ __forceinline__ void phase1_small(double (&K)[4][4], const Lds& L, in
 
 // Phase 3, a token with its full factor at the four nodes nu0 + j*stride (j = 0..3).
 template <int D>
-__device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D + 1], double wt, int n, int nu0,
+__device__ __forceinline__ double phase3_big(const Lds<D>& L, const double (&e)[D + 1], double wt, int n, int nu0,
                                              int stride, int nn, double& acc_t) {
     double T[4][D + 1], y[4], x[4], qq[4], cn[4], tt[4];
 #pragma unroll
@@ -278,7 +284,7 @@ __device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D +
         y[j] = tt[j] * wt;
         qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
 #pragma unroll
-        for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * 17 + d];
+        for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * (D + 1) + d];
     }
     exp_neg4(y, x, L.e2tab);
     loo_coeff4<D, D>(T, x, e, n, cn);
@@ -298,7 +304,8 @@ __device__ __forceinline__ double phase3_big(const Lds& L, const double (&e)[D +
 // T[n-1..n-4].  e[k] = q^k / k! (zero for k > n), so the brackets are multiplied by k!.
 // This wave's nodes wv, wv + kSW, ..., four at a time from the node records (uniform over the wave;
 // records at or beyond nn carry weight 0); two register sets alternate as in phase 1.
-__device__ __forceinline__ void phase3_small_load(const Lds& L, int nu0, NodeRec (&r)[4]) {
+template <class LdsT>
+__device__ __forceinline__ void phase3_small_load(const LdsT& L, int nu0, NodeRec (&r)[4]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) r[j] = L.nrec[nu0 + j * kSW];
 }
@@ -323,7 +330,8 @@ __device__ __forceinline__ void phase3_small_quad(const NodeRec (&c)[4], const d
         at = fma(term, c[j].t, at);
     }
 }
-__device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5], double wt, int wv, int nn, double& acc_t) {
+template <class LdsT>
+__device__ __forceinline__ double phase3_small(const LdsT& L, const double (&e)[5], double wt, int wv, int nn, double& acc_t) {
     double acc = 0.0, at = 0.0;
     acc_t = 0.0;
     if (wv >= nn) return acc;
@@ -357,7 +365,7 @@ __device__ __forceinline__ double phase3_small(const Lds& L, const double (&e)[5
 // In: L.aq, L.aal, L.etab / L.nbig / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
 // Out: L.aR[0..m), L.R0acc (slack mass; meaningful when slack = 1).  All threads call it.
 template <int D>
-__device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, int slack, double qsum) {
+__device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx, int slack, double qsum) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int nbig = L.nbig;
     double w = 0.0;
@@ -392,7 +400,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
         const int tk = tok < m ? tok : 0;
         ws[pass] = m > 0 ? L.aw[tk] : 0.0;
 #pragma unroll
-        for (int a = 1; a <= 4; ++a) es[pass][a] = (a <= n && m > 0) ? L.etab[tk * 17 + a] : 0.0;
+        for (int a = 1; a <= 4; ++a) es[pass][a] = (a <= n && a <= D && m > 0) ? L.etab[tk * (D + 1) + (a <= D ? a : 0)] : 0.0;
         es[pass][0] = 0.0;
     }
     __syncthreads();
@@ -456,7 +464,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             NodeRec rec; rec.t = t; rec.qw = qw; rec.T[0] = rec.T[1] = rec.T[2] = rec.T[3] = 0.0;
 #pragma unroll
             for (int d = 0; d <= D; ++d) {
-                L.Tl[lane * 17 + d] = T[d];
+                L.Tl[lane * (D + 1) + d] = T[d];
                 if (d == n) tn = T[d];
                 if (d == n - 1) rec.T[0] = T[d];
                 if (d == n - 2) rec.T[1] = T[d];
@@ -476,7 +484,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
             const int tk = tok < nbig ? tok : 0;
             double e[D + 1];
 #pragma unroll
-            for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * 17 + a];
+            for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * (D + 1) + a];
             double acct;
             double acc = phase3_big<D>(L, e, L.aw[tk], n, wv + kSW * (lane >> 4), 4 * kSW, nn, acct);
             acc += __shfl_xor(acc, 16); acct += __shfl_xor(acct, 16);
@@ -514,7 +522,7 @@ __device__ __forceinline__ void routed_eval(Lds& L, int m, int n, double ctx, in
 // (the latter is zero in exact arithmetic and removes the common quadrature error).  f -> L.af;
 // L.aR and L.aS stay valid until the next evaluation.
 template <int D>
-__device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
+__device__ double defect_eval(Lds<D>& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
                               double tsum, double* rsum_out) {
     const int tid = threadIdx.x;
     routed_eval<D>(L, m, n, ctx, slack, qsum);
@@ -537,7 +545,7 @@ __device__ double defect_eval(Lds& L, int m, int n, double ctx, int slack, doubl
 // is pinned (the system is singular along the common shift).  Starts from L.aal.
 // J: this row's scratch in HBM, kMaxT rows of kMaxT + 1 doubles (the last column is the right-hand side).
 template <int D>
-__device__ int newton_program(Lds& L, double* J, int m, int n, double ctx, int slack, double slack_target, double qsum,
+__device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, int slack, double slack_target, double qsum,
                               double tsum, double rel_tol, int max_evals, int* evals) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int nfree = slack ? m : m - 1;
@@ -627,7 +635,7 @@ __device__ int newton_program(Lds& L, double* J, int m, int n, double ctx, int s
 // In: L.aq, L.at (targets, already scaled to the tuple mass), L.aal (start log weights).
 // Out: L.aal.  `evals` counts evaluator calls.
 template <int D>
-__device__ __forceinline__ int solve_program(Lds& L, double* newton_ws, int m, int n, double ctx, int slack, double slack_target,
+__device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m, int n, double ctx, int slack, double slack_target,
                              double rel_tol, int max_iter, int* evals) {
     const int tid = threadIdx.x;
     if (n == 1) {
@@ -651,8 +659,12 @@ __device__ __forceinline__ int solve_program(Lds& L, double* newton_ws, int m, i
         // coefficient by less than 1e-11 relative: C(n-1, c) (q/atot)^c / (c+1) < 1e-11
         const double q = L.aq[tid], atot = ctx + qsum;
         double e = 1.0;
-        L.etab[tid * 17] = 1.0;
-        for (int a = 1; a <= 16; ++a) { e = e * q / a; L.etab[tid * 17 + a] = e; if (a <= 4) L.trec[tid].e[a - 1] = e; }
+        L.etab[tid * (D + 1)] = 1.0;
+        for (int a = 1; a <= (D > 4 ? D : 4); ++a) {
+            e = e * q / a;
+            if (a <= D) L.etab[tid * (D + 1) + a] = e;
+            if (a <= 4) L.trec[tid].e[a - 1] = e;
+        }
         // light if the u^5 and later terms of its factor cannot change the z^n coefficient by more
         // than 1e-11 relative: C(n-1, 4) (q/atot)^4 / 5 < 1e-11; exact for n <= 4
         const double r = q / atot;
@@ -835,7 +847,8 @@ __device__ __forceinline__ int solve_program(Lds& L, double* newton_ws, int m, i
 // Build the active list of one program: the support positions in [lo, hi) that belong to T and have
 // a positive target, in decreasing q (L.ordq lists the positions of H* and of the rest in that
 // order).  Returns m (possibly > kMaxT, in which case nothing was written beyond kMaxT).
-__device__ int compact_active(Lds& L, int lo, int hi, int kk) {
+template <class LdsT>
+__device__ int compact_active(LdsT& L, int lo, int hi, int kk) {
     const int tid = threadIdx.x;
     const int j = tid < kk ? L.ordq[tid] : -1;           // kk <= KS <= kST
     const int on = (j >= lo && j < hi && L.inT[j] && L.tgt[j] > 0.0) ? 1 : 0;
@@ -858,7 +871,7 @@ __device__ int compact_active(Lds& L, int lo, int hi, int kk) {
 template <int D>
 __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds& L = *reinterpret_cast<Lds*>(lds_raw);
+    Lds<D>& L = *reinterpret_cast<Lds<D>*>(lds_raw);
     const int tid = threadIdx.x;
     const int row = blockIdx.x;
     const int n = sp.n, V = sp.V;
@@ -1122,7 +1135,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 template <int D>
 __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds& L = *reinterpret_cast<Lds*>(lds_raw);
+    Lds<D>& L = *reinterpret_cast<Lds<D>*>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
     const int n = fp.n, V = fp.V;
     const size_t vs = static_cast<size_t>(V) + 2;
@@ -1256,26 +1269,25 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
 
 hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream) {
     const dim3 grid(fp.B), block(kST);
-    if (fp.n <= 2) hipLaunchKernelGGL(full_programs_kernel<2>, grid, block, sizeof(Lds), stream, fp);
-    else if (fp.n <= 4) hipLaunchKernelGGL(full_programs_kernel<4>, grid, block, sizeof(Lds), stream, fp);
-    else if (fp.n <= 8) hipLaunchKernelGGL(full_programs_kernel<8>, grid, block, sizeof(Lds), stream, fp);
-    else hipLaunchKernelGGL(full_programs_kernel<16>, grid, block, sizeof(Lds), stream, fp);
+    if (fp.n <= 2) hipLaunchKernelGGL(full_programs_kernel<2>, grid, block, sizeof(Lds<2>), stream, fp);
+    else if (fp.n <= 4) hipLaunchKernelGGL(full_programs_kernel<4>, grid, block, sizeof(Lds<4>), stream, fp);
+    else if (fp.n <= 8) hipLaunchKernelGGL(full_programs_kernel<8>, grid, block, sizeof(Lds<8>), stream, fp);
+    else hipLaunchKernelGGL(full_programs_kernel<16>, grid, block, sizeof(Lds<16>), stream, fp);
     return hipGetLastError();
 }
 
-static_assert(sizeof(Lds) <= 160 * 1024, "the solve workgroup's state must fit the CU's LDS");
+static_assert(sizeof(Lds<16>) <= 160 * 1024, "the solve workgroup's state must fit the CU's LDS");
+static_assert(sizeof(Lds<8>) + 20 * 1024 <= 160 * 1024, "up to 8 drafts: a streaming workgroup of the next batch fits beside a row");
 
 hipError_t solve_kernel_setup() {
-    const void* kernels[4] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
-                              reinterpret_cast<const void*>(solve_kernel<8>), reinterpret_cast<const void*>(solve_kernel<16>)};
-    for (const void* k : kernels) {
-        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
-        if (e != hipSuccess) return e;
-    }
-    const void* full_kernels[4] = {reinterpret_cast<const void*>(full_programs_kernel<2>), reinterpret_cast<const void*>(full_programs_kernel<4>),
-                                   reinterpret_cast<const void*>(full_programs_kernel<8>), reinterpret_cast<const void*>(full_programs_kernel<16>)};
-    for (const void* k : full_kernels) {
-        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizeof(Lds)));
+    const void* kernels[8] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
+                              reinterpret_cast<const void*>(solve_kernel<8>), reinterpret_cast<const void*>(solve_kernel<16>),
+                              reinterpret_cast<const void*>(full_programs_kernel<2>), reinterpret_cast<const void*>(full_programs_kernel<4>),
+                              reinterpret_cast<const void*>(full_programs_kernel<8>), reinterpret_cast<const void*>(full_programs_kernel<16>)};
+    const size_t sizes[8] = {sizeof(Lds<2>), sizeof(Lds<4>), sizeof(Lds<8>), sizeof(Lds<16>),
+                             sizeof(Lds<2>), sizeof(Lds<4>), sizeof(Lds<8>), sizeof(Lds<16>)};
+    for (int i = 0; i < 8; ++i) {
+        const hipError_t e = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(sizes[i]));
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1284,10 +1296,10 @@ hipError_t solve_kernel_setup() {
 // One kernel per series degree D >= n (2, 4, 8, 16), so that each keeps its series in registers.
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream) {
     const dim3 grid(sp.B), block(kST);
-    if (sp.n <= 2) hipLaunchKernelGGL(solve_kernel<2>, grid, block, sizeof(Lds), stream, sp);
-    else if (sp.n <= 4) hipLaunchKernelGGL(solve_kernel<4>, grid, block, sizeof(Lds), stream, sp);
-    else if (sp.n <= 8) hipLaunchKernelGGL(solve_kernel<8>, grid, block, sizeof(Lds), stream, sp);
-    else hipLaunchKernelGGL(solve_kernel<16>, grid, block, sizeof(Lds), stream, sp);
+    if (sp.n <= 2) hipLaunchKernelGGL(solve_kernel<2>, grid, block, sizeof(Lds<2>), stream, sp);
+    else if (sp.n <= 4) hipLaunchKernelGGL(solve_kernel<4>, grid, block, sizeof(Lds<4>), stream, sp);
+    else if (sp.n <= 8) hipLaunchKernelGGL(solve_kernel<8>, grid, block, sizeof(Lds<8>), stream, sp);
+    else hipLaunchKernelGGL(solve_kernel<16>, grid, block, sizeof(Lds<16>), stream, sp);
     return hipGetLastError();
 }
 
