@@ -46,9 +46,9 @@ struct Lds {
     static constexpr int kS = D + 1;  // stride of a series
     // support, in ratio order
     int tok[KS]; int blk[KS]; int inT[KS]; int ordq[KS]; int apos[kMaxT];
-    int flag[KS + 2]; int cnt0[KS + 2]; int cnt1[KS + 2]; int blo[KS + 2];
-    double qd[KS]; double qn[KS]; double pn[KS]; double rho[KS]; double tgt[KS]; double wgt[KS]; double accb[KS];
-    double P[KS + 1]; double S[KS + 1]; double Q[KS + 1]; double F[KS + 2]; double G0[KS + 2]; double G1[KS + 2];
+    int flag[KS + 2]; int blo[KS + 2];
+    double qn[KS]; double pn[KS]; double rho[KS]; double tgt[KS]; double wgt[KS];
+    double Q[KS + 1]; double F[KS + 2];
     // one convex program
     double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aw[kMaxT]; double aR[kMaxT]; double af[kMaxT];
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
@@ -59,9 +59,22 @@ struct Lds {
     double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
     double gram[kGram]; double gamma[kCols];
     // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
-    double tnode[64]; double qwnode[64]; double Tl[64 * kS]; double rpart[kSW][kMaxT];
-    double spart[kSW][kMaxT]; double aS[kMaxT];   // the same sums weighted by the node abscissa t; aS_i = R_i - dR_i/d(log w_i)
-    double cum[kSW * 4 * 64];       // per-wave cumulant sums of the light tokens, per node
+    double tnode[64]; double qwnode[64]; double Tl[64 * kS];
+    double aS[kMaxT];               // routed mass weighted by the node abscissa t; aS_i = R_i - dR_i/d(log w_i)
+    // scans and counters of the prologue (dead once the first program starts) share their bytes with the
+    // evaluator's per-wave partial sums
+    union {
+        struct {
+            int cnt0[KS + 2]; int cnt1[KS + 2];
+            double qd[KS]; double accb[KS];
+            double P[KS + 1]; double S[KS + 1]; double G0[KS + 2]; double G1[KS + 2];
+        };
+        struct {
+            double rpart[kSW][kMaxT];
+            double spart[kSW][kMaxT];   // the same sums weighted by t
+            double cum[kSW * 4 * 64];   // per-wave cumulant sums of the light tokens, per node
+        };
+    };
     NodeRec nrec[64 + 16];          // nodes of the current chunk; the 16 beyond are zero (weight 0)
     TokRec trec[kMaxT + 16];        // active tokens; the 16 beyond the last have aw = 1e300 (x = 0)
     double e2tab[32];               // 2^(-j/32)
@@ -1276,8 +1289,8 @@ hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream) {
     return hipGetLastError();
 }
 
-static_assert(sizeof(Lds<16>) <= 160 * 1024, "the solve workgroup's state must fit the CU's LDS");
-static_assert(sizeof(Lds<8>) + 20 * 1024 <= 160 * 1024, "up to 8 drafts: a streaming workgroup of the next batch fits beside a row");
+static_assert(sizeof(Lds<16>) + 20 * 1024 <= 160 * 1024,
+              "the solve workgroup's state and one streaming workgroup of the next batch must fit the CU's LDS together");
 
 hipError_t solve_kernel_setup() {
     const void* kernels[8] = {reinterpret_cast<const void*>(solve_kernel<2>), reinterpret_cast<const void*>(solve_kernel<4>),
