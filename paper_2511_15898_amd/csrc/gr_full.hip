@@ -12,70 +12,125 @@ namespace gr {
 
 namespace {
 
+constexpr int kSortItems = 4;                      // keys per thread and tile
+constexpr int kSortWaves = kSortItems * kWaves;    // 64-key groups of one tile, in index order
+
 struct SortLds {
-    int hist[256]; int base[256]; int wcnt[kWaves][256]; int flag;
+    int hist[8][256];                              // digit histograms of all eight passes
+    int base[2][256];                              // first output slot of each digit for the current tile
+    unsigned short wcnt[2][kSortWaves][256];       // per 64-key group: keys with this digit, then their offset within the tile
+    int skip[8];
 };
 
 // Stable least-significant-digit radix sort of `count` (key, value) pairs of one row, ascending in the
 // 64-bit key, 8 bits per pass, between the buffer pairs (k0, v0) and (k1, v1).  Returns 0 or 1: the pair
-// that holds the result.  Passes whose digit is the same for every key are skipped.  All threads call.
+// that holds the result.  The histograms of all passes come from one read of the keys (they do not depend
+// on the order); passes whose digit is the same for every key are skipped.  A pass moves tiles of 1024
+// keys, four per thread, with two barriers per tile: the per-group counters and the digit bases are
+// double-buffered, and thread d carries the running base of digit d in a register.  All threads call.
 __device__ int block_radix_sort(unsigned long long* k0, int* v0, unsigned long long* k1, int* v1, int count,
                                 SortLds& S) {
+    constexpr int kTile = kThreads * kSortItems;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    for (int j = 0; j < 8; ++j) S.hist[j][tid] = 0;
+    if (tid < 8) S.skip[tid] = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < count; i0 += kThreads) {
+        const int i = i0 + tid;
+        const bool valid = i < count;
+        const unsigned long long key = valid ? k0[i] : 0ull;
+        const unsigned long long vm = __ballot(valid);
+        if (vm == 0ull) continue;                               // wave-uniform; lane 0 is valid otherwise
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int d = static_cast<int>((key >> (8 * j)) & 255ull);
+            const int d0 = __builtin_amdgcn_readfirstlane(d);
+            if (__ballot(valid && d == d0) == vm) {             // one digit in the whole wave: one update
+                if (lane == 0) atomicAdd(&S.hist[j][d0], __popcll(vm));
+            } else if (valid) {
+                atomicAdd(&S.hist[j][d], 1);
+            }
+        }
+    }
+    __syncthreads();
+    for (int j = 0; j < 8; ++j) if (S.hist[j][tid] == count) S.skip[j] = 1;
+    __syncthreads();
+
     int cur = 0;
-    for (int shift = 0; shift < 64; shift += 8) {
+    for (int pass = 0; pass < 8; ++pass) {
+        if (S.skip[pass]) continue;
+        const int shift = 8 * pass;
         const unsigned long long* ks = cur ? k1 : k0; const int* vs = cur ? v1 : v0;
         unsigned long long* kd = cur ? k0 : k1; int* vd = cur ? v0 : v1;
-        S.hist[tid] = 0;
-        for (int w = 0; w < kWaves; ++w) S.wcnt[w][tid] = 0;
-        if (tid == 0) S.flag = 0;
-        __syncthreads();
-        for (int i = tid; i < count; i += kThreads) atomicAdd(&S.hist[static_cast<int>((ks[i] >> shift) & 255ull)], 1);
-        __syncthreads();
-        if (S.hist[tid] == count) S.flag = 1;
         if (wv == 0) {
-            // exclusive scan of the histogram: lane l owns digits 4l .. 4l+3
+            // exclusive scan of the histogram: lane l owns digits 4l .. 4l+3; the result goes to base[1]
+            // (unused until the second tile) and from there to the owners' registers
             int c[4]; int tot = 0;
-            for (int j = 0; j < 4; ++j) { c[j] = S.hist[4 * lane + j]; tot += c[j]; }
+            for (int j = 0; j < 4; ++j) { c[j] = S.hist[pass][4 * lane + j]; tot += c[j]; }
             int incl = tot;
             for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
             int run = incl - tot;
-            for (int j = 0; j < 4; ++j) { S.base[4 * lane + j] = run; run += c[j]; }
+            for (int j = 0; j < 4; ++j) { S.base[1][4 * lane + j] = run; run += c[j]; }
         }
+        for (int w = 0; w < kSortWaves; ++w) { S.wcnt[0][w][tid] = 0; S.wcnt[1][w][tid] = 0; }
         __syncthreads();
-        if (S.flag) { __syncthreads(); continue; }
-        const int ntiles = (count + kThreads - 1) / kThreads;
-        unsigned long long knext = 0ull; int vnext = 0;
-        if (tid < count) { knext = ks[tid]; vnext = vs[tid]; }
-        for (int t = 0; t < ntiles; ++t) {
-            const int i = t * kThreads + tid;
-            const bool valid = i < count;
-            const unsigned long long key = knext; const int val = vnext;
-            if (i + kThreads < count) { knext = ks[i + kThreads]; vnext = vs[i + kThreads]; }
-            const int d = static_cast<int>((key >> shift) & 255ull);
-            // lanes of this wave that hold the same digit
-            unsigned long long peers = __ballot(valid);
+        int mybase = S.base[1][tid];                            // running first slot of digit `tid`
+        __syncthreads();
+        unsigned long long kn[kSortItems]; int vn[kSortItems];
 #pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const bool bit = (d >> b) & 1;
-                const unsigned long long m = __ballot(valid && bit);
-                peers &= bit ? m : ~m;
+        for (int j = 0; j < kSortItems; ++j) {
+            const int i = j * kThreads + tid;
+            kn[j] = 0ull; vn[j] = 0;
+            if (i < count) { kn[j] = ks[i]; vn[j] = vs[i]; }
+        }
+        int buf = 0;
+        for (int t0 = 0; t0 < count; t0 += kTile, buf ^= 1) {
+            unsigned long long key[kSortItems]; int val[kSortItems]; int dig[kSortItems]; int rank[kSortItems];
+#pragma unroll
+            for (int j = 0; j < kSortItems; ++j) { key[j] = kn[j]; val[j] = vn[j]; }
+#pragma unroll
+            for (int j = 0; j < kSortItems; ++j) {
+                const int i = t0 + kTile + j * kThreads + tid;
+                if (i < count) { kn[j] = ks[i]; vn[j] = vs[i]; }
             }
-            const int rank = __popcll(peers & ((1ull << lane) - 1ull));
-            if (valid && rank == 0) S.wcnt[wv][d] = __popcll(peers);
-            __syncthreads();
-            if (valid) {
-                int off = S.base[d] + rank;
-                for (int w = 0; w < wv; ++w) off += S.wcnt[w][d];
-                kd[off] = key; vd[off] = val;
+#pragma unroll
+            for (int j = 0; j < kSortItems; ++j) {
+                const bool valid = t0 + j * kThreads + tid < count;
+                const int d = static_cast<int>((key[j] >> shift) & 255ull);
+                // lanes of this wave that hold the same digit
+                unsigned long long peers = __ballot(valid);
+#pragma unroll
+                for (int b = 0; b < 8; ++b) {
+                    const bool bit = (d >> b) & 1;
+                    const unsigned long long m = __ballot(valid && bit);
+                    peers &= bit ? m : ~m;
+                }
+                dig[j] = d;
+                rank[j] = __popcll(peers & ((1ull << lane) - 1ull));
+                if (valid && rank[j] == 0) S.wcnt[buf][j * kWaves + wv][d] = static_cast<unsigned short>(__popcll(peers));
             }
             __syncthreads();
             {
-                int add = 0;
-                for (int w = 0; w < kWaves; ++w) { add += S.wcnt[w][tid]; S.wcnt[w][tid] = 0; }
-                S.base[tid] += add;
+                // digit `tid`: counts of the groups -> offsets within the tile; clear the other buffer for the next tile
+                S.base[buf][tid] = mybase;
+                int run = 0;
+#pragma unroll
+                for (int w = 0; w < kSortWaves; ++w) {
+                    const int c = S.wcnt[buf][w][tid];
+                    S.wcnt[buf][w][tid] = static_cast<unsigned short>(run);
+                    run += c;
+                    S.wcnt[buf ^ 1][w][tid] = 0;
+                }
+                mybase += run;
             }
             __syncthreads();
+#pragma unroll
+            for (int j = 0; j < kSortItems; ++j) {
+                if (t0 + j * kThreads + tid < count) {
+                    const int off = S.base[buf][dig[j]] + S.wcnt[buf][j * kWaves + wv][dig[j]] + rank[j];
+                    kd[off] = key[j]; vd[off] = val[j];
+                }
+            }
         }
         cur ^= 1;
         __syncthreads();
