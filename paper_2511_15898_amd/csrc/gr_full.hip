@@ -138,6 +138,27 @@ __device__ int block_radix_sort(unsigned long long* k0, int* v0, unsigned long l
     return cur;
 }
 
+#pragma clang fp contract(off)
+// The running sums of wave_sequential_scan for operands in LDS: every lane reads x[j] (one address
+// for the whole wave: a broadcast read) and adds it, so all lanes hold the same sums, in the order of
+// a sequential loop; lane 0 stores them.  x must be readable and zero, out writable, up to the next
+// multiple of 64 beyond `count`.  out[0] = start, out[i + 1] = start + x[0] + ... + x[i].
+__device__ __forceinline__ void wave_sequential_scan_padded(const double* x, double* out, int count, double start) {
+    const int lane = threadIdx.x & 63;
+    double acc = start;
+    if (lane == 0) out[0] = start;
+    for (int base = 0; base < count; base += 64) {
+        double a[64];
+#pragma unroll
+        for (int j = 0; j < 64; ++j) { acc = acc + x[base + j]; a[j] = acc; }
+        if (lane == 0) {
+#pragma unroll
+            for (int j = 0; j < 64; ++j) out[base + j + 1] = a[j];
+        }
+    }
+}
+#pragma clang fp contract(fast)
+
 // Exclusive suffix minimum over the 256 threads: min of v over the threads after this one (1e300 for
 // the last); *total = min over all.  buf0, buf1: LDS double[256].
 __device__ double block_suffix_min_excl(double v, double* buf0, double* buf1, double* total) {
@@ -193,7 +214,7 @@ __device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot
 __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     __shared__ SortLds S;
     __shared__ double red[kWaves];
-    __shared__ int wtot[kWaves];
+    __shared__ int wtot[4 * kWaves];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
     const int V = fp.V;
     const size_t vs = static_cast<size_t>(V) + 2;
@@ -221,22 +242,34 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     bool by_flag = false;
     if (fp.k < V) {
         int cnt = 0;
-        for (int t0 = 0; t0 < V; t0 += kThreads) {
-            const int i = t0 + tid;
-            const float qv = i < V ? qr[i] : 0.f;
-            const bool in = qv > 0.f;
-            const unsigned long long mask = __ballot(in);
-            if (lane == 0) wtot[wv] = __popcll(mask);
-            __syncthreads();
-            int off = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-            int tile_total = 0;
-            for (int w = 0; w < kWaves; ++w) { if (w < wv) off += wtot[w]; tile_total += wtot[w]; }
-            if (in) {
-                k0[off] = (static_cast<unsigned long long>(~__float_as_uint(qv)) << 24) | static_cast<unsigned long long>(i);
-                v0[off] = i;
+        for (int t0 = 0; t0 < V; t0 += 4 * kThreads) {           // 1024 tokens per round
+            float qv[4]; unsigned long long mask[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { const int i = t0 + j * kThreads + tid; qv[j] = i < V ? qr[i] : 0.f; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                mask[j] = __ballot(qv[j] > 0.f);
+                if (lane == 0) wtot[j * kWaves + wv] = __popcll(mask[j]);
             }
-            if (i < V) member[i] = 0;
-            cnt += tile_total;
+            __syncthreads();
+            int run = 0, offs[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < 4 * kWaves; ++g) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) if (g == j * kWaves + wv) offs[j] = run;
+                run += wtot[g];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = t0 + j * kThreads + tid;
+                if (qv[j] > 0.f) {
+                    const int off = cnt + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
+                    k0[off] = (static_cast<unsigned long long>(~__float_as_uint(qv[j])) << 24) | static_cast<unsigned long long>(i);
+                    v0[off] = i;
+                }
+                if (i < V) member[i] = 0;
+            }
+            cnt += run;
             __syncthreads();
         }
         if (cnt > fp.k) {
@@ -249,22 +282,37 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     }
     // the support in token order, with its keys
     int kk = 0;
-    for (int t0 = 0; t0 < V; t0 += kThreads) {
-        const int i = t0 + tid;
-        const float qv = i < V ? qr[i] : 0.f;
-        const bool in = by_flag ? (i < V && member[i] != 0) : qv > 0.f;
-        const unsigned long long mask = __ballot(in);
-        if (lane == 0) wtot[wv] = __popcll(mask);
-        __syncthreads();
-        int off = kk + __popcll(mask & ((1ull << lane) - 1ull));
-        int tile_total = 0;
-        for (int w = 0; w < kWaves; ++w) { if (w < wv) off += wtot[w]; tile_total += wtot[w]; }
-        if (in) {
-            const double ratio = static_cast<double>(qv) / static_cast<double>(pr[i]);   // p = 0 gives +inf: first
-            k0[off] = ~static_cast<unsigned long long>(__double_as_longlong(ratio));
-            v0[off] = i;
+    for (int t0 = 0; t0 < V; t0 += 4 * kThreads) {               // 1024 tokens per round
+        float qv[4], pv[4]; bool in[4]; unsigned long long mask[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = t0 + j * kThreads + tid;
+            qv[j] = i < V ? qr[i] : 0.f; pv[j] = i < V ? pr[i] : 1.f;
+            in[j] = by_flag ? (i < V && member[i] != 0) : qv[j] > 0.f;
         }
-        kk += tile_total;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            mask[j] = __ballot(in[j]);
+            if (lane == 0) wtot[j * kWaves + wv] = __popcll(mask[j]);
+        }
+        __syncthreads();
+        int run = 0, offs[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int g = 0; g < 4 * kWaves; ++g) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (g == j * kWaves + wv) offs[j] = run;
+            run += wtot[g];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (in[j]) {
+                const int off = kk + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
+                const double ratio = static_cast<double>(qv[j]) / static_cast<double>(pv[j]);   // p = 0 gives +inf: first
+                k0[off] = ~static_cast<unsigned long long>(__double_as_longlong(ratio));
+                v0[off] = t0 + j * kThreads + tid;
+            }
+        }
+        kk += run;
         __syncthreads();
     }
     if (kk == 0) {
@@ -307,35 +355,70 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
     int* flag = fp.flag + row * vs; int* blk = fp.blk + row * vs; int* blo = fp.blo + row * vs;
     int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
 
-    for (int r = tid; r < kk; r += kThreads) {
-        const int id = order[r];
-        pn[r] = static_cast<double>(pr[id]) / info.p_total;
-        qn[r] = static_cast<double>(qr[id]);                     // raw q for now
-        inT[r] = 0;
+    for (int r0 = tid; r0 < kk; r0 += 4 * kThreads) {           // four independent gathers per thread in flight
+        int id[4]; float pv[4], qv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const int r = r0 + j * kThreads; id[j] = r < kk ? order[r] : 0; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { pv[j] = pr[id[j]]; qv[j] = qr[id[j]]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + j * kThreads;
+            if (r < kk) {
+                pn[r] = static_cast<double>(pv[j]) / info.p_total;
+                qn[r] = static_cast<double>(qv[j]);              // raw q for now
+                inT[r] = 0;
+            }
+        }
     }
     if (tid == 0) { P[0] = 0.0; Q[0] = 0.0; }
     __syncthreads();
-    // sequential prefix sums, a tile at a time through LDS (wave 0: p, wave 1: q)
+    // sequential prefix sums, a tile at a time through LDS (wave 0: p, wave 1: q); the next tile is
+    // loaded into registers while the two waves scan
     double carry_p = 0.0, carry_q = 0.0;
+    double np_[4], nq_[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int i = j * kThreads + tid;
+        np_[j] = i < kk ? pn[i] : 0.0; nq_[j] = i < kk ? qn[i] : 0.0;
+    }
     for (int t0 = 0; t0 < kk; t0 += kTile) {
         const int cnt = min(kTile, kk - t0);
-        for (int i = tid; i < cnt; i += kThreads) { xin[0][i] = pn[t0 + i]; xin[1][i] = qn[t0 + i]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { xin[0][j * kThreads + tid] = np_[j]; xin[1][j * kThreads + tid] = nq_[j]; }   // zeros beyond cnt
         __syncthreads();
-        if (wv == 0) wave_sequential_scan(xin[0], xout[0], cnt, carry_p);
-        if (wv == 1) wave_sequential_scan(xin[1], xout[1], cnt, carry_q);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = t0 + kTile + j * kThreads + tid;
+            np_[j] = i < kk ? pn[i] : 0.0; nq_[j] = i < kk ? qn[i] : 0.0;
+        }
+        if (wv == 0) wave_sequential_scan_padded(xin[0], xout[0], cnt, carry_p);
+        if (wv == 1) wave_sequential_scan_padded(xin[1], xout[1], cnt, carry_q);
         __syncthreads();
         for (int i = tid; i < cnt; i += kThreads) { P[t0 + i + 1] = xout[0][i + 1]; Q[t0 + i + 1] = xout[1][i + 1]; }
         carry_p = xout[0][cnt]; carry_q = xout[1][cnt];
-        __syncthreads();
+        // the next tile's scan, which overwrites xout, starts behind the next barrier
     }
     const double stot = carry_q;
     {
 #pragma clang fp contract(off)
-        for (int m = tid; m <= kk; m += kThreads) {
-            const double Qm = Q[m] / stot;
-            Q[m] = Qm;
-            F[m] = (m == 0) ? 0.0 : P[m] - ipow(Qm, n);
-            if (m < kk) qn[m] = qn[m] / stot;
+        for (int m0 = tid; m0 <= kk; m0 += 4 * kThreads) {
+            double Qv[4], Pv[4], qv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + j * kThreads;
+                Qv[j] = m <= kk ? Q[m] : 0.0; Pv[j] = m <= kk ? P[m] : 0.0; qv[j] = m < kk ? qn[m] : 0.0;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + j * kThreads;
+                if (m <= kk) {
+                    const double Qm = Qv[j] / stot;
+                    Q[m] = Qm;
+                    F[m] = (m == 0) ? 0.0 : Pv[j] - ipow(Qm, n);
+                    if (m < kk) qn[m] = qv[j] / stot;
+                }
+            }
         }
     }
     __syncthreads();
@@ -414,6 +497,8 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
 __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     __shared__ SortLds S;
     __shared__ int cnt_in, cnt_out, act_in, capped;
+    __shared__ double wx[2][64];
+    __shared__ double wo[2][65];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
     const int V = fp.V, n = fp.n;
     const size_t vs = static_cast<size_t>(V) + 2;
@@ -429,12 +514,22 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     const int* blk = fp.blk + row * vs; const int* blo = fp.blo + row * vs;
     int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
 
-    // ranks by (inside H* first, decreasing q, token id)
-    for (int r = tid; r < kk; r += kThreads) {
-        const int id = order[r];
-        const unsigned long long qb = static_cast<unsigned long long>(~__float_as_uint(qr[id]));
-        k0[r] = (static_cast<unsigned long long>(r < h ? 0 : 1) << 56) | (qb << 24) | static_cast<unsigned long long>(id);
-        v0[r] = r;
+    // ranks by (inside H* first, decreasing q, token id); four independent gathers per thread in flight
+    for (int r0 = tid; r0 < kk; r0 += 4 * kThreads) {
+        int id[4]; float qv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const int r = r0 + j * kThreads; id[j] = r < kk ? order[r] : 0; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qv[j] = qr[id[j]];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + j * kThreads;
+            if (r < kk) {
+                const unsigned long long qb = static_cast<unsigned long long>(~__float_as_uint(qv[j]));
+                k0[r] = (static_cast<unsigned long long>(r < h ? 0 : 1) << 56) | (qb << 24) | static_cast<unsigned long long>(id[j]);
+                v0[r] = r;
+            }
+        }
     }
     if (tid == 0) { cnt_in = 0; cnt_out = 0; act_in = 0; capped = 0; }
     __syncthreads();
@@ -444,45 +539,71 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     __syncthreads();
     const double Qh = Q[h];
     // wave 0 walks H* by decreasing q, wave 1 the other tokens: a token joins T while the mass before
-    // it leaves more than tau (running sums added one after the other, as a sequential loop would)
+    // it leaves more than tau (running sums added one after the other, as a sequential loop would).
+    // The walk only counts; the ranks and masses of the next two rounds are already on their way.
     if (wv < 2) {
 #pragma clang fp contract(off)
         const int first = wv == 0 ? 0 : h;
         const int len = wv == 0 ? h : kk - h;
         const double bound = wv == 0 ? ipow(Qh, n) : 1.0;
         double acc = wv == 0 ? 0.0 : Qh;
-        int taken = 0, active = 0;
+        int taken = 0;
         bool done = false;
+        int r1 = (lane < len) ? byq[first + lane] : 0;                        // ranks of round 0
+        int r2 = (64 + lane < len) ? byq[first + 64 + lane] : 0;              // ranks of round 1
+        double m1 = (lane < len) ? qn[r1] : 0.0;                              // masses of round 0
         for (int base = 0; base < len && !done; base += 64) {
             const bool valid = base + lane < len;
-            const int r = valid ? byq[first + base + lane] : 0;
-            const double mine = valid ? qn[r] : 0.0;
-            double before = 0.0;
-#pragma unroll
-            for (int j = 0; j < 64; ++j) {
-                if (lane == j) before = acc;
-                acc = acc + __shfl(mine, j);
-            }
+            const double mine = m1;
+            m1 = (base + 64 + lane < len) ? qn[r2] : 0.0;
+            r2 = (base + 128 + lane < len) ? byq[first + base + 128 + lane] : 0;
+            // running sums through a wave-private LDS strip (broadcast reads; see the padded scan)
+            wx[wv][lane] = mine;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier();
+            wave_sequential_scan_padded(wx[wv], wo[wv], 64, acc);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier();
+            const double before = wo[wv][lane];
+            acc = wo[wv][64];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier();
             const double bn = (before > 0.0) ? ipow(before, n) : 0.0;
             const bool in = valid && (bound - bn > fp.tau);
             const unsigned long long out_mask = __ballot(valid && !in);
             int upto = 64;                                       // lanes below `upto` join T
             if (out_mask) { upto = __ffsll(static_cast<long long>(out_mask)) - 1; done = true; }
-            const bool join = valid && lane < upto;
-            if (join) inT[r] = 1;
-            const bool act = join && tgt[r] > 0.0;
-            taken += __popcll(__ballot(join));
-            active += __popcll(__ballot(act));
-            if (wv == 1 && act) {
-                const int b = blk[r];
-                if (blo[b + 1] - blo[b] >= 2) {
-                    const int old = atomicAdd(&bcount[b], 1);
+            taken += __popcll(__ballot(valid && lane < upto));
+        }
+        if (lane == 0) { if (wv == 0) cnt_in = taken; else cnt_out = taken; }
+    }
+    __syncthreads();
+    // mark the members of both sets; count the active ones per program
+    {
+        const int nin = cnt_in, nout = cnt_out;
+        int act = 0;
+        for (int i0 = tid; i0 < nin; i0 += 4 * kThreads) {
+            int r[4]; double t[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { const int i = i0 + j * kThreads; r[j] = i < nin ? byq[i] : -1; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = r[j] >= 0 ? tgt[r[j]] : 0.0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (r[j] >= 0) { inT[r[j]] = 1; act += t[j] > 0.0; }
+        }
+        if (act) atomicAdd(&act_in, act);
+        for (int i0 = tid; i0 < nout; i0 += 4 * kThreads) {
+            int r[4]; double t[4]; int bl[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { const int i = i0 + j * kThreads; r[j] = i < nout ? byq[h + i] : -1; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { t[j] = r[j] >= 0 ? tgt[r[j]] : 0.0; bl[j] = r[j] >= 0 ? blk[r[j]] : 0; }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (r[j] < 0) continue;
+                inT[r[j]] = 1;
+                if (t[j] > 0.0 && blo[bl[j] + 1] - blo[bl[j]] >= 2) {
+                    const int old = atomicAdd(&bcount[bl[j]], 1);
                     if (old + 1 > fp.max_T) capped = 1;
                 }
             }
-        }
-        if (lane == 0) {
-            if (wv == 0) { cnt_in = taken; act_in = active; } else { cnt_out = taken; }
         }
     }
     __syncthreads();
