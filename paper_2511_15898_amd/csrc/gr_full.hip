@@ -264,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
                 const int i = t0 + j * kThreads + tid;
                 if (qv[j] > 0.f) {
                     const int off = cnt + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
-                    k0[off] = (static_cast<unsigned long long>(~__float_as_uint(qv[j])) << 24) | static_cast<unsigned long long>(i);
+                    k0[off] = static_cast<unsigned long long>(~__float_as_uint(qv[j]));   // ties: the sort is stable and this is token order
                     v0[off] = i;
                 }
                 if (i < V) member[i] = 0;
@@ -525,8 +525,9 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
         for (int j = 0; j < 4; ++j) {
             const int r = r0 + j * kThreads;
             if (r < kk) {
-                const unsigned long long qb = static_cast<unsigned long long>(~__float_as_uint(qv[j]));
-                k0[r] = (static_cast<unsigned long long>(r < h ? 0 : 1) << 56) | (qb << 24) | static_cast<unsigned long long>(id[j]);
+                // q < 2, so bit 31 of ~bits(q) is always set: it carries the class instead (seven digits, not eight)
+                const unsigned long long qb = static_cast<unsigned long long>((~__float_as_uint(qv[j]) & 0x7FFFFFFFu) | (r < h ? 0u : 0x80000000u));
+                k0[r] = (qb << 24) | static_cast<unsigned long long>(id[j]);
                 v0[r] = r;
             }
         }
