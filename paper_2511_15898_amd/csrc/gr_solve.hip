@@ -1167,14 +1167,28 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
     // tokens outside the support keep all of p as residual; then the support by rank
     for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
     __syncthreads();
-    for (int r = tid; r < kk; r += kST) {
-        const int hi = (r < h) ? h : blo[blk[r] + 1];
-        const double top = Q[hi];
-        const double gauge = (r < h) ? ipow(top, n) / (-Fh) : 1.0;
-        const double t = tgt[r];
-        weight[r] = (t > 0.0) ? gauge * t / pow_diff(top, qn[r], n) : 0.0;
-        const int id = order[r];
-        rank_of[id] = r; rho_id[id] = rho[r];
+    for (int r0 = tid; r0 < kk; r0 += 4 * kST) {             // four independent chains of gathers per thread in flight
+        int bl[4], hi[4], id[4]; double top[4], t[4], qv[4], rv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + j * kST;
+            const bool ok = r < kk;
+            bl[j] = (ok && r >= h) ? blk[r] : 0;
+            t[j] = ok ? tgt[r] : 0.0; qv[j] = ok ? qn[r] : 0.0; rv[j] = ok ? rho[r] : 0.0; id[j] = ok ? order[r] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const int r = r0 + j * kST; hi[j] = (r < h || r >= kk) ? h : blo[bl[j] + 1]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) top[j] = Q[hi[j]];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + j * kST;
+            if (r < kk) {
+                const double gauge = (r < h) ? ipow(top[j], n) / (-Fh) : 1.0;
+                weight[r] = (t[j] > 0.0) ? gauge * t[j] / pow_diff(top[j], qv[j], n) : 0.0;
+                rank_of[id[j]] = r; rho_id[id[j]] = rv[j];
+            }
+        }
     }
     if (info.status != GR_ROW_OK) return;
     if (tid == 0) L.work = 0.0;
