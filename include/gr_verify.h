@@ -129,6 +129,8 @@ int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens, void* hip
  * the streaming selection kernel, the per-row solve kernel (both launched by gr_solve) and the
  * verification kernel, over the gr_solve + gr_verify pairs issued since the last read (at most
  * 512 are kept), from HIP events recorded on the caller's stream.  Waits for the last of them.
+ * With a support above GR_MAX_SUPPORT, select_ms covers the ordering, scan and truncation kernels
+ * in HBM and solve_ms the kernel that runs the convex programs.
  * All four outputs are HOST pointers. */
 int gr_profile_read(gr_handle h, double* select_ms, double* solve_ms, double* verify_ms, int* steps);
 

@@ -170,9 +170,9 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
         f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
         mark(h, 0, stream);
-        mark(h, 1, stream);
         launch_full_prologue(f, stream);
         if (hipGetLastError() != hipSuccess) return GR_EHIP;
+        mark(h, 1, stream);
         if (launch_full_programs(f, stream) != hipSuccess) return GR_EHIP;
         mark(h, 2, stream);
         h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
