@@ -84,6 +84,25 @@ def pow_diff(a, d, n):
     return d * s
 
 
+def acceptance_sweep(p, q, ks, ns):
+    """Optimal acceptance alpha*(k, n) = 1 + min_H psi(H) (Thm 3.1) of one decode position for every
+    top-k size in `ks` and every number of i.i.d. drafts in `ns`: the quantity of the paper's
+    acceptance-versus-(k, n) study (Sec. 7, first experiment).  For each k: the support V_0 of the
+    top-k draft (App. "Top-k Sampling ..."), the order by decreasing q/p and the best prefix
+    (Sec. 5.1).  p is divided by its float64 row sum, as in solve_row.  Returns [len(ks), len(ns)]."""
+    p = np.asarray(p); q = np.asarray(q)
+    pt = float(np.sum(p, dtype=np.float64))
+    out = np.zeros((len(ks), len(ns)))
+    for a, k in enumerate(ks):
+        order = ratio_order(p, q, topk_support(q, int(k)))
+        ps = p[order].astype(np.float64) / pt
+        qs = q[order]
+        for b, n in enumerate(ns):
+            _, _, F = prefix_psi(ps, qs, int(n))
+            out[a, b] = 1.0 + float(F.min())
+    return out
+
+
 @dataclass
 class Block:
     """One transport sub-system: tokens at sorted positions lo..hi-1 (0-based), the mass

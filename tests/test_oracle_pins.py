@@ -225,3 +225,24 @@ def test_zero_probability_tokens():
     sol = _check_coupling(p, q, 2, 0, 0.0, 1e-9, 1e-9)
     assert [int(t) for t in sol.order[:2]] == [1, 4]          # p = 0, q > 0 rank first
     assert 2 not in sol.pos_of and 5 not in sol.pos_of        # q = 0 is never drafted
+
+
+def test_acceptance_sweep_against_subset_enumeration_and_closed_forms():
+    """acceptance_sweep over (k, n): every cell equals 1 + min over ALL subsets of psi for the
+    top-k restricted draft (Thm 3.1 by enumeration); n = 1 is sum_i min(p_i, q'_i) (single-draft
+    rule, App. A); rows are nondecreasing in n; k >= V is the problem without top-k."""
+    ks, ns = [1, 2, 3, 5, 8], [1, 2, 3, 5]
+    for p, q in _random_rows(77, 12, 8):
+        got = G.acceptance_sweep(p, q, ks, ns)
+        p64 = _norm64(p)
+        for a, k in enumerate(ks):
+            qk = np.zeros(8)
+            keep = sorted(range(8), key=lambda i: (-float(q[i]), i))[:k]
+            qk[keep] = np.asarray(q, np.float64)[keep]
+            qk = qk / qk.sum()
+            for b, n in enumerate(ns):
+                value, _ = brute.psi_min_all_subsets(p64, qk, n)
+                assert abs(got[a, b] - (1.0 + value)) < 1e-12, (k, n)
+            assert abs(got[a, 0] - np.minimum(p64, qk).sum()) < 1e-12
+            assert np.all(np.diff(got[a]) >= -1e-15)
+        assert np.array_equal(got[-1], G.acceptance_sweep(p, q, [0], ns)[0])
