@@ -11,6 +11,7 @@
  *              decreasing q/p and H*, alpha* = 1 + psi(H*) (Thm 3.1, Sec. 5.1), the outer
  *              targets p_i (Thm 6.2, Lemma 6.3), the softmax weights that minimise
  *              Theta_T (Thm 6.5) and Phi_T (Thm 6.4, solved per block of the outer system).
+ *   gr_accept_sweep  alpha* alone over a grid of top-k sizes and draft counts (Thm 3.1, Sec. 5.1).
  *   gr_verify  the transport slice pi(.|drafts) (Eq. "cases" / Eq. "approx-c") and one
  *              inverse-CDF draw from it (App. A, multi-draft procedure, step 3).
  *
@@ -83,6 +84,26 @@ int gr_destroy(gr_handle h);
  */
 int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float tol,
              int B, int V, float* accept_prob, int* status, void* hip_stream);
+
+/*
+ * Acceptance-only sweep: alpha*(k, n) = 1 + min_H psi(H) (Thm 3.1; by the order of decreasing q/p
+ * and the best prefix, Sec. 5.1) for every top-k size in ks and every number of i.i.d. drafts in ns,
+ * from one streaming pass over p and q: the quantity of the paper's acceptance-versus-(k, n) study
+ * (Sec. 7, first experiment; top-k as in App. "Top-k Sampling for the Relaxed OTLP").  No convex
+ * program runs.
+ * p, q        [B, V] float32 device arrays, as for gr_solve.
+ * ks          HOST array of nk top-k sizes, 1 <= nk <= GR_SWEEP_MAX_K, each 1..GR_MAX_SUPPORT.
+ * ns          HOST array of nn draft counts, 1 <= nn <= GR_SWEEP_MAX_N, each 1..GR_SWEEP_MAX_DRAFTS.
+ * accept_prob [B, nk, nn] float32 device out (NaN for a bad row).   status [B] int32 device out:
+ *             GR_ROW_OK or GR_ROW_BAD.
+ * Overwrites the handle's selection scratch: the policy of an earlier gr_solve is gone
+ * (gr_verify returns GR_ESTATE until the next gr_solve).
+ */
+#define GR_SWEEP_MAX_K        8
+#define GR_SWEEP_MAX_N       16
+#define GR_SWEEP_MAX_DRAFTS  64
+int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
+                    int B, int V, float* accept_prob, int* status, void* hip_stream);
 
 /*
  * drafts   [B, n] int32 token ids drawn from the top-k renormalised q rows.

@@ -18,7 +18,7 @@ GR_MAX_N = 16
 GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_accept_sweep", "gr_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -50,6 +50,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.POINTER(GrConfig)]
     lib.gr_destroy.argtypes = [vp]
     lib.gr_solve.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
+    lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
@@ -111,6 +112,29 @@ def gr_solve(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: int, tol:
                                  _stream(stream))
     if rc != GR_OK:
         raise GrError(rc, "gr_solve")
+    return accept_prob, status
+
+
+def gr_accept_sweep(handle: int, p: torch.Tensor, q: torch.Tensor, ks, ns,
+                    accept_prob: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None):
+    """alpha* over a grid: ks top-k sizes, ns draft counts (host sequences of ints).
+    Returns (accept_prob [B, len(ks), len(ns)] float32, status [B] int32)."""
+    if p.dim() != 2 or p.shape != q.shape:
+        raise TypeError("gr_accept_sweep: p and q must both be [B, V]")
+    B, V = p.shape
+    ks = [int(k) for k in ks]; ns = [int(n) for n in ns]
+    if accept_prob is None:
+        accept_prob = torch.empty((B, len(ks), len(ns)), dtype=torch.float32, device=p.device)
+    elif tuple(accept_prob.shape) != (B, len(ks), len(ns)):
+        raise TypeError("gr_accept_sweep: accept_prob must be [B, len(ks), len(ns)]")
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=p.device)
+    ka = (ctypes.c_int * len(ks))(*ks); na = (ctypes.c_int * len(ns))(*ns)
+    rc = load_library().gr_accept_sweep(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), ka, len(ks), na, len(ns),
+                                        B, V, _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
+                                        _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_accept_sweep")
     return accept_prob, status
 
 

@@ -7,7 +7,7 @@ import subprocess
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libgr_verify.so")
-SOURCES = ["gr_select.hip", "gr_solve.hip", "gr_full.hip", "gr_verify.hip", "gr_api.hip"]
+SOURCES = ["gr_select.hip", "gr_solve.hip", "gr_full.hip", "gr_sweep.hip", "gr_verify.hip", "gr_api.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

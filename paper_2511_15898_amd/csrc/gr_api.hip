@@ -201,6 +201,40 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     return GR_OK;
 }
 
+extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
+                               int B, int V, float* accept_prob, int* status, void* hip_stream) {
+    if (!h || !p || !q || !ks || !ns || !accept_prob || !status) return GR_EINVAL;
+    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
+    if (nk < 1 || nk > kSweepMaxK || nn < 1 || nn > kSweepMaxN) return GR_EINVAL;
+    SweepParams sw;
+    sw.kmax = 0;
+    for (int i = 0; i < nk; ++i) {
+        if (ks[i] < 1 || ks[i] > kMaxSupport) return GR_EINVAL;
+        sw.ks[i] = ks[i];
+        if (ks[i] > sw.kmax) sw.kmax = ks[i];
+    }
+    for (int i = 0; i < nn; ++i) {
+        if (ns[i] < 1 || ns[i] > kSweepMaxDrafts) return GR_EINVAL;
+        sw.ns[i] = ns[i];
+    }
+    if (sw.kmax > V) sw.kmax = V;                        // a top-k of V or more keeps every positive entry
+    for (int i = nk; i < kSweepMaxK; ++i) sw.ks[i] = 0;
+    for (int i = nn; i < kSweepMaxN; ++i) sw.ns[i] = 1;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int splits = choose_splits(B, V);
+    int slice_len = (V + splits - 1) / splits;
+    slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;
+    h->solved = false;                                   // the selection scratch of the handle is overwritten
+    launch_select(p, q, B, V, sw.kmax, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
+                  h->part_bad, h->piece_psum, h->piece_stride, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    sw.p = p; sw.V = V; sw.splits = splits;
+    sw.cand = h->cand; sw.cand_count = h->cand_count; sw.part_psum = h->part_psum; sw.part_qsum = h->part_qsum;
+    sw.part_bad = h->part_bad; sw.nk = nk; sw.nn = nn; sw.accept_prob = accept_prob; sw.status = status;
+    if (launch_sweep(sw, B, stream) != hipSuccess) return GR_EHIP;
+    return GR_OK;
+}
+
 extern "C" int gr_verify(gr_handle h, const int* drafts, const float* uniforms, int* token,
                          unsigned char* accepted, void* hip_stream) {
     if (!h || !drafts || !uniforms || !token || !accepted) return GR_EINVAL;

@@ -89,6 +89,21 @@ void launch_verify(const float* p, int B, int V, int n, const PolicyView& pv, co
 void launch_slice(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                   float* pi, float* accept_given, hipStream_t stream);
 hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream);
+
+// Acceptance-only sweep over a grid of top-k sizes and draft counts (one selection pass with kmax).
+constexpr int kSweepMaxK = 8;     // top-k sizes per call
+constexpr int kSweepMaxN = 16;    // draft counts per call
+constexpr int kSweepMaxDrafts = 64;
+struct SweepParams {
+    const float* p; int V; int splits;
+    const unsigned long long* cand; const int* cand_count;
+    const double* part_psum; const double* part_qsum; const int* part_bad;
+    int kmax, nk, nn;
+    int ks[kSweepMaxK]; int ns[kSweepMaxN];
+    float* accept_prob;           // [B, nk, nn]
+    int* status;                  // [B]
+};
+hipError_t launch_sweep(const SweepParams& sw, int B, hipStream_t stream);
 hipError_t solve_kernel_setup();
 
 // ---------------------------------------------------------------- device helpers
