@@ -49,13 +49,62 @@ def cpu_baseline(wl, tol, budget_s=15.0):
             "sample": f"first {rows} rows of the same batch, {dt:.1f} s, single thread"}
 
 
+def bench_sweep(args):
+    """Side measurement: gr_accept_sweep (alpha* over a grid of top-k sizes and draft counts) on the
+    large-vocabulary batch.  One step = one call = one streaming pass over p and q plus the per-row grid."""
+    import numpy as np
+    import torch
+    from paper_2511_15898_amd import binding as gr, workloads as W
+    wl = W.large_vocab()
+    ks, ns = [8, 16, 32, 64, 128, 256], list(range(1, 11))
+    dev = torch.device("cuda:0")
+    p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
+    acc = torch.empty((wl.B, len(ks), len(ns)), dtype=torch.float32, device=dev)
+    st = torch.empty(wl.B, dtype=torch.int32, device=dev)
+    h = gr.gr_create(wl.B, wl.V)
+    for _ in range(args.warmup):
+        gr.gr_accept_sweep(h, p, q, ks, ns, acc, st)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)   # the calls run on torch's current stream
+    t0 = time.perf_counter(); e0.record()
+    for _ in range(args.steps):
+        gr.gr_accept_sweep(h, p, q, ks, ns, acc, st)
+    e1.record(); torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    call_ms = e0.elapsed_time(e1) / args.steps
+    gr.gr_destroy(h)
+    algo_bytes = 8.0 * wl.V * wl.B
+    achieved = algo_bytes / (call_ms * 1e-3) / 1e9
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gr_oracle as G
+        c0 = time.perf_counter(); rows = 0
+        while rows < wl.B and time.perf_counter() - c0 < 10.0:
+            G.acceptance_sweep(wl.p[rows], wl.q[rows], ks, ns); rows += 1
+        cdt = time.perf_counter() - c0
+        cpu = {"value": rows / cdt, "unit": "rows/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {rows} rows of the same batch, {cdt:.1f} s, single thread"}
+    print(json.dumps({
+        "metric": "acceptance-sweep rows/sec", "value": wl.B * args.steps / dt, "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"sweep on {wl.name}: B={wl.B} rows x V={wl.V} vocab, top-k in {ks}, drafts in {ns}",
+                   "B": wl.B, "V": wl.V, "ks": ks, "ns": ns, "cells_per_row": len(ks) * len(ns)},
+        "status_histogram": [int(x) for x in np.bincount(st.cpu().numpy(), minlength=4)],
+        "roofline": {"bound": "hbm", "kernel": "select_kernel + sweep_kernel (one gr_accept_sweep call)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "call_ms": call_ms},
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--tol", type=float, default=1e-4, help="the paper's error threshold tau")
-    ap.add_argument("--workload", default="large", choices=["large", "llm", "small", "stress", "stress_full"],
+    ap.add_argument("--workload", default="large", choices=["large", "llm", "small", "stress", "stress_full", "sweep"],
                     help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
@@ -68,6 +117,9 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; rows are independent and would shard across GPUs "
                  "without any exchange, but no multi-GPU figure is produced.  Use --gpus 1.")
+
+    if args.workload == "sweep":
+        return bench_sweep(args)
 
     import numpy as np
     import torch

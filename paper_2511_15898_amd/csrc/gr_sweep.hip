@@ -23,7 +23,7 @@ struct SweepLds {
     int rqr[kMaxSupport];                 // by ratio rank: the token's rank by decreasing q
     int ids[kMaxSupport];
     double wtot[2][kWaves];
-    double red[kWaves];
+    double cell[kSweepMaxN][kWaves];      // per draft count: the waves' minima of F
     int hist[256]; int pick[4]; int count;
 };
 
@@ -118,12 +118,20 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams sw) {
         double P = on ? myp : 0.0, S = on ? myq : 0.0, Ptot, Stot;
         block_scan2(P, S, L.wtot, &Ptot, &Stot);
         const double Q = S / Stot;                            // Stot > 0: the largest q is positive
+        // a rank outside this support repeats the prefix before it (or the empty prefix, F = 0);
+        // the minima of all draft counts meet in LDS behind one barrier
         for (int b = 0; b < sw.nn; ++b) {
-            // a rank outside this support repeats the prefix before it (or the empty prefix, F = 0)
             const double F = have ? P - ipow(Q, sw.ns[b]) : 0.0;
-            const double Fmin = block_min(fmin(F, 0.0), L.red);
-            if (tid == 0) out[a * sw.nn + b] = static_cast<float>(1.0 + Fmin);
+            const double m = wave_min(fmin(F, 0.0));
+            if ((tid & 63) == 0) L.cell[b][tid >> 6] = m;
         }
+        __syncthreads();
+        if (tid < sw.nn) {
+            double t = L.cell[tid][0];
+            for (int w = 1; w < kWaves; ++w) t = fmin(t, L.cell[tid][w]);
+            out[a * sw.nn + tid] = static_cast<float>(1.0 + t);
+        }
+        // L.cell is written again only behind the two barriers of the next scan
     }
     if (tid == 0) sw.status[row] = GR_ROW_OK;
 }
