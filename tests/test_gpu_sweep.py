@@ -113,3 +113,31 @@ def test_argument_checks_and_handle_state():
         torch.cuda.synchronize()
     finally:
         gr.gr_destroy(h)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_grids(seed):
+    """Seeded random shapes, generators, exact zeros and grids (top-k sizes 1..256, draft counts 1..64)."""
+    rng = np.random.default_rng(9000 + seed)
+    for case in range(30):
+        B = int(rng.integers(1, 7))
+        V = int(rng.integers(2, 3000)) if case % 10 else int(rng.integers(20000, 140000))
+        ss = int(rng.integers(1e6))
+        gen = int(rng.integers(0, 3))
+        if gen == 0:
+            wl = W.llm_shaped(B=B, V=V, n=2, k=0, temperature=(0.3, 2.0), near_identical_frac=0.2, seed_sub=ss)
+        elif gen == 1:
+            wl = W.small(B=B, V=V, n=2, k=0, seed_sub=ss)
+        else:
+            wl = W.tiny(B=B, V=V, n=2, seed_sub=ss)
+        p, q = wl.p.copy(), wl.q.copy()
+        if rng.random() < 0.4:
+            zq = rng.random(q.shape) < rng.choice([0.05, 0.5, 0.9]); zq[np.arange(B), q.argmax(1)] = False; q[zq] = 0
+            zp = rng.random(p.shape) < 0.1; zp[np.arange(B), p.argmax(1)] = False; p[zp] = 0
+            q = (q / q.sum(1, keepdims=True, dtype=np.float32)).astype(np.float32)
+            p = (p / p.sum(1, keepdims=True, dtype=np.float32)).astype(np.float32)
+        ks = [int(x) for x in rng.integers(1, 257, size=int(rng.integers(1, 9)))]
+        ns = [int(x) for x in rng.integers(1, 65, size=int(rng.integers(1, 17)))]
+        acc, st = _sweep(np.ascontiguousarray(p), np.ascontiguousarray(q), ks, ns)
+        assert np.all(st == 0), (seed, case)
+        _check(p, q, ks, ns, range(B), acc)
