@@ -400,6 +400,7 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
         // the next tile's scan, which overwrites xout, starts behind the next barrier
     }
     const double stot = carry_q;
+    double fmin_local = 1e300, hcand = 1e18;                    // this thread's smallest F and the first rank that has it
     {
 #pragma clang fp contract(off)
         for (int m0 = tid; m0 <= kk; m0 += 4 * kThreads) {
@@ -415,7 +416,9 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
                 if (m <= kk) {
                     const double Qm = Qv[j] / stot;
                     Q[m] = Qm;
-                    F[m] = (m == 0) ? 0.0 : Pv[j] - ipow(Qm, n);
+                    const double Fm = (m == 0) ? 0.0 : Pv[j] - ipow(Qm, n);
+                    F[m] = Fm;
+                    if (Fm < fmin_local) { fmin_local = Fm; hcand = static_cast<double>(m); }   // ranks rise within a thread
                     if (m < kk) qn[m] = qv[j] / stot;
                 }
             }
@@ -423,12 +426,8 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
     }
     __syncthreads();
     // H*: the smallest minimising prefix
-    double fmin_local = 1e300;
-    for (int m = tid; m <= kk; m += kThreads) fmin_local = fmin(fmin_local, F[m]);
     const double Fmin = block_min(fmin_local, red);
-    double hcand = 1e18;
-    for (int m = tid; m <= kk; m += kThreads) if (F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
-    const int h = static_cast<int>(block_min(hcand, red));
+    const int h = static_cast<int>(block_min(fmin_local == Fmin ? hcand : 1e18, red));
     // G = suffix minima of F over m = 0..kk, tiles of 1024 from the top down (4 consecutive entries per thread)
     {
         double later = 1e300;                                   // min of F over the tiles above
