@@ -75,7 +75,7 @@ int gr_destroy(gr_handle h);
  * n           number of i.i.d. drafts per row, 1..GR_MAX_N.
  * k           top-k applied to q (ties: lower token id); k <= 0 or k >= V means none.
  *             A support above GR_MAX_SUPPORT (no top-k on a larger V, or a larger top-k) lives in a
- *             device workspace that this call allocates or grows (136 bytes per token of V and
+ *             device workspace that this call allocates or grows (128 bytes per token of V and
  *             row); V must then stay below 2^24, otherwise GR_EUNSUPPORTED.
  * tol         the paper's error threshold tau (Alg. 1), >= 0: truncation sets are the fewest
  *             tokens by decreasing q with gamma_T <= tol (inner) / epsilon_T <= tol (outer).

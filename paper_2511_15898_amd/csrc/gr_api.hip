@@ -100,7 +100,7 @@ int prepare_full(gr_handle h, int B, int V) {
     f.key0 = static_cast<unsigned long long*>(take(cnt * 8)); f.key1 = static_cast<unsigned long long*>(take(cnt * 8));
     f.val0 = static_cast<int*>(take(cnt * 4)); f.val1 = static_cast<int*>(take(cnt * 4));
     f.order = static_cast<int*>(take(cnt * 4)); f.byq = static_cast<int*>(take(cnt * 4));
-    double** dbl[] = {&f.pn, &f.qn, &f.P, &f.Q, &f.F, &f.G, &f.rho, &f.tgt, &f.weight, &f.rho_id};
+    double** dbl[] = {&f.pn, &f.qn, &f.P, &f.Q, &f.F, &f.rho, &f.tgt, &f.weight, &f.rho_id};
     for (double** d : dbl) *d = static_cast<double*>(take(cnt * 8));
     int** ints[] = {&f.flag, &f.blk, &f.blo, &f.inT, &f.bcount, &f.rank_of};
     for (int** d : ints) *d = static_cast<int*>(take(cnt * 4));

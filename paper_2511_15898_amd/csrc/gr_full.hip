@@ -350,7 +350,7 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
     const float* qr = fp.q + static_cast<size_t>(row) * V;
     const int* order = fp.order + row * vs;
     double* pn = fp.pn + row * vs; double* qn = fp.qn + row * vs;
-    double* P = fp.P + row * vs; double* Q = fp.Q + row * vs; double* F = fp.F + row * vs; double* G = fp.G + row * vs;
+    double* P = fp.P + row * vs; double* Q = fp.Q + row * vs; double* F = fp.F + row * vs;
     double* rho = fp.rho + row * vs; double* tgt = fp.tgt + row * vs;
     int* flag = fp.flag + row * vs; int* blk = fp.blk + row * vs; int* blo = fp.blo + row * vs;
     int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
@@ -428,31 +428,35 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
     // H*: the smallest minimising prefix
     const double Fmin = block_min(fmin_local, red);
     const int h = static_cast<int>(block_min(fmin_local == Fmin ? hcand : 1e18, red));
-    // G = suffix minima of F over m = 0..kk, tiles of 1024 from the top down (4 consecutive entries per thread)
+    // G = suffix minima of F over m = 0..kk, tiles of 1024 from the top down (4 consecutive entries per
+    // thread); G is only needed here, so residuals, targets and records (F(m) <= G(m+1) for m >= h;
+    // m = kk always) are taken in the same sweep and G is never stored
     {
         double later = 1e300;                                   // min of F over the tiles above
         const int ntile = (kk + 1 + kTile - 1) / kTile;
         for (int t = ntile - 1; t >= 0; --t) {
             const int m0 = t * kTile + tid * 4;
-            double a[4];
+            double a[4], pv[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = (m0 + j <= kk) ? F[m0 + j] : 1e300;
+            for (int j = 0; j < 4; ++j) { a[j] = (m0 + j <= kk) ? F[m0 + j] : 1e300; pv[j] = (m0 + j < kk) ? pn[m0 + j] : 0.0; }
             double s[4];
             s[3] = a[3]; s[2] = fmin(a[2], s[3]); s[1] = fmin(a[1], s[2]); s[0] = fmin(a[0], s[1]);
             double total;
-            const double after = fmin(block_suffix_min_excl(s[0], dbuf[0], dbuf[1], &total), later);
+            const double after = fmin(block_suffix_min_excl(s[0], dbuf[0], dbuf[1], &total), later);   // G(m0 + 4)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) if (m0 + j <= kk) G[m0 + j] = fmin(s[j], after);
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + j;
+                if (m <= kk) {
+                    const double g = fmin(s[j], after);                                  // G(m)
+                    const double gn = (j < 3) ? fmin(s[j + 1], after) : after;           // G(m + 1), unused at m = kk
+                    flag[m] = (m >= h && (m == kk || a[j] <= gn)) ? 1 : 0;
+                    if (m < kk) {
+                        const double r = (m >= h) ? gn - g : 0.0;
+                        rho[m] = r; tgt[m] = pv[j] - r;
+                    }
+                }
+            }
             later = fmin(later, total);
-        }
-    }
-    __syncthreads();
-    // residuals, targets, records (F(m) <= G(m+1) for m >= h; m = kk always)
-    for (int m = tid; m <= kk; m += kThreads) {
-        flag[m] = (m >= h && (m == kk || F[m] <= G[m + 1])) ? 1 : 0;
-        if (m < kk) {
-            const double r = (m >= h) ? G[m + 1] - G[m] : 0.0;
-            rho[m] = r; tgt[m] = pn[m] - r;
         }
     }
     __syncthreads();

@@ -58,7 +58,7 @@ struct FullParams {
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p
     int* byq;          // ranks by (inside H* first, decreasing q, token id)
-    double* pn; double* qn; double* P; double* Q; double* F; double* G; double* rho; double* tgt; double* weight;
+    double* pn; double* qn; double* P; double* Q; double* F; double* rho; double* tgt; double* weight;
     int* flag; int* blk; int* blo; int* inT; int* bcount;
     int* rank_of;      // [B, V + 2] rank of each token id, -1 outside the support
     double* rho_id;    // [B, V + 2] residual p(i) - p_i by token id (0 inside H*)
@@ -67,7 +67,7 @@ struct FullParams {
     RowInfo* info; float* accept_prob; int* status;
     double* newton_ws; // [B, kMaxT * (kMaxT + 1)] Jacobian scratch of the Newton fallback
 };
-constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 9 * 8 + 5 * 4 + 4 + 8;
+constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 8 * 8 + 5 * 4 + 4 + 8;
 
 void launch_full_prologue(const FullParams& fp, hipStream_t stream);
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
