@@ -347,6 +347,22 @@ extern "C" int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens
     return hipGetLastError() == hipSuccess ? GR_OK : GR_EHIP;
 }
 
+#ifdef GR_PHASE_CLOCKS
+namespace {
+__global__ void clocks_kernel(const RowInfo* info, int B, long long* out) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    for (int i = 0; i < 16; ++i) out[b * 16 + i] = info[b].clk[i];
+}
+}  // namespace
+// Profiling builds only: cycles of thread 0 per phase of the last solve, [B, 16] int64 device array.
+extern "C" int gr_debug_clocks(gr_handle h, long long* out, void* hip_stream) {
+    if (!h || !out || !h->solved) return GR_EINVAL;
+    hipLaunchKernelGGL(clocks_kernel, dim3((h->B + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream), h->info, h->B, out);
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_EHIP;
+}
+#endif
+
 extern "C" const char* gr_strerror(int code) {
     switch (code) {
         case GR_OK: return "ok";

@@ -399,6 +399,7 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
         carry_p = xout[0][cnt]; carry_q = xout[1][cnt];
         // the next tile's scan, which overwrites xout, starts behind the next barrier
     }
+    __syncthreads();                                            // P and Q are read back below by other threads than wrote them
     const double stot = carry_q;
     double fmin_local = 1e300, hcand = 1e18;                    // this thread's smallest F and the first rank that has it
     {

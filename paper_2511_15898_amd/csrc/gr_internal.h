@@ -27,6 +27,9 @@ struct RowInfo {
     double p_total;     // float64 row sum of p
     double q_total;     // float64 row sum of q (before top-k)
     double node_tokens; // sum over evaluator calls of (quadrature nodes x active tokens)
+#ifdef GR_PHASE_CLOCKS
+    long long clk[16];  // shader-clock cycles of thread 0 per phase of the solve kernel (profiling builds only)
+#endif
 };
 
 struct SolveParams {

@@ -22,6 +22,14 @@ namespace gr {
 
 namespace {
 
+// Optional cycle accounting (builds with -DGR_PHASE_CLOCKS only): thread 0 adds the shader-clock cycles since
+// its previous mark to one of 16 slots; the totals per row are written to RowInfo::clk.
+#ifdef GR_PHASE_CLOCKS
+#define GR_CLK(L, slot) do { if (threadIdx.x == 0) { const long long now_ = clock64(); (L).clk[slot] += now_ - (L).clk_last; (L).clk_last = now_; } } while (0)
+#else
+#define GR_CLK(L, slot) do {} while (0)
+#endif
+
 constexpr int KS = kMaxSupport;
 constexpr int kST = 256;             // threads of the solve workgroup (one wave per SIMD: each may use all 512 registers)
 constexpr int kSW = kST / 64;
@@ -80,6 +88,9 @@ struct Lds {
     double e2tab[32];               // 2^(-j/32)
     int nbig;                       // number of heavy tokens of the current program
     double work;                    // sum over evaluator calls of nodes x active tokens (thread 0 only)
+#ifdef GR_PHASE_CLOCKS
+    long long clk[16]; long long clk_last;
+#endif
     double red[kSW]; double R0acc; int ok; int pick[4]; int count; int hist[256];
     // unsorted candidates (select merge), later the per-wave partial products of the evaluator
     union {
@@ -381,6 +392,7 @@ template <int D>
 __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx, int slack, double qsum) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int nbig = L.nbig;
+    GR_CLK(L, 12);
     double w = 0.0;
     if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; L.trec[tid].aw = w; }
     if (tid < 16) { NodeRec z; z.t = 0.0; z.qw = 0.0; z.T[0] = z.T[1] = z.T[2] = z.T[3] = 0.0; L.nrec[64 + tid] = z; }
@@ -417,6 +429,7 @@ __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx,
         es[pass][0] = 0.0;
     }
     __syncthreads();
+    GR_CLK(L, 6);
 
     for (int c0 = 0; c0 < N; c0 += 64) {
         const int node = c0 + lane;
@@ -446,6 +459,7 @@ __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx,
             for (int k = 0; k < 4; ++k) L.cum[(wv * 4 + k) * 64 + lane] = (K[0][k] + K[1][k]) + (K[2][k] + K[3][k]);
         }
         __syncthreads();
+        GR_CLK(L, 7);
         // ---- phase 2 (wave 0)
         if (wv == 0) {
             double Kt[4];
@@ -488,6 +502,7 @@ __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx,
             r0 += wave_sum(qw * tn);
         }
         __syncthreads();
+        GR_CLK(L, 8);
         // ---- phase 3
         const int nn = min(64, N - c0);
         // heavy tokens: 16 per round, lane = (token, node group); this wave's nodes are wv, wv+4, ...,
@@ -514,6 +529,7 @@ __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx,
             }
         }
         __syncthreads();                                   // part / cum / Tl / tnode are rewritten by the next chunk
+        GR_CLK(L, 9);
     }
     if (lane < m && lane >= nbig) { L.rpart[wv][lane] = racc[0]; L.spart[wv][lane] = sacc[0]; }
     if (64 + lane < m && 64 + lane >= nbig) { L.rpart[wv][64 + lane] = racc[1]; L.spart[wv][64 + lane] = sacc[1]; }
@@ -528,6 +544,10 @@ __device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx,
         L.aS[tid] = sq * L.aw[tid] * L.aw[tid] * fact;
     }
     __syncthreads();
+    GR_CLK(L, 10);
+#ifdef GR_PHASE_CLOCKS
+    if (tid == 0) L.clk[15] += 1;
+#endif
 }
 
 // One evaluation and the stopping measure: max_i | log(target_i / routed_i) - common term |, where the
@@ -548,7 +568,9 @@ __device__ double defect_eval(Lds<D>& L, int m, int n, double ctx, int slack, do
         L.af[tid] = f;
     }
     if (rsum_out) *rsum_out = rsum;
-    return block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
+    const double worst = block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
+    GR_CLK(L, 11);
+    return worst;
 }
 
 // Damped Newton iteration on routed(alpha) = target with a finite-difference Jacobian (the Hessian of
@@ -691,6 +713,7 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m
     const int nheavy = block_sum_i<kSW>((tid < m && L.adeg[tid] != 0) ? 1 : 0, L.red);
     if (tid == 0) L.nbig = nheavy;
     __syncthreads();
+    GR_CLK(L, 5);
     int hcount = 0, plain = 0, since = 0;
     double best_err = 1e300, cap = kStretch;
     int result = 1;
@@ -849,10 +872,12 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m
         __syncthreads();
     }
     __syncthreads();
+    GR_CLK(L, 12);
     if (result != 0 && mix_iters < max_iter && best_err < 1e300) {
         if (tid < m) L.aal[tid] = L.aBest[tid];
         __syncthreads();
         result = newton_program<D>(L, newton_ws, m, n, ctx, slack, slack_target, qsum, tsum, rel_tol, max_iter, evals);
+        GR_CLK(L, 13);
     }
     return result;
 }
@@ -922,6 +947,9 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         }
     }
     if (tid == 0) { L.count = 0; L.work = 0.0; }
+#ifdef GR_PHASE_CLOCKS
+    if (tid == 0) { for (int i = 0; i < 16; ++i) L.clk[i] = 0; L.clk_last = clock64(); }
+#endif
     __syncthreads();
     unsigned long long theta = 0ull;
     if (total > sp.k) theta = block_kth_largest<kST>(L.u.keys, total, sp.k, L.hist, L.pick);
@@ -937,6 +965,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     // unsorted: token ids in ordq, q in accb (exact float values), p gathered into G0
     if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ordq[tid]]);
     __syncthreads();
+    GR_CLK(L, 0);
     // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id.
     // Rank counting; `parts` threads share a token (each counts over a stretch of the others).
     {
@@ -965,6 +994,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         }
         __syncthreads();
     }
+    GR_CLK(L, 1);
     // ---- prefix sums in the order, sequentially (bit-reproducible), then F(m) = P_m - Q_m^n
     {
 #pragma clang fp contract(off)
@@ -1029,6 +1059,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         if (m < kk) L.blk[m] = (m >= h) ? L.cnt0[m] : 0; // token m (rank m+1) lies after record cnt0[m]
     }
     __syncthreads();
+    GR_CLK(L, 2);
     // ---- truncation sets: fewest tokens by decreasing q with gamma_T <= tau / epsilon_T <= tau
     {
         const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
@@ -1081,6 +1112,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
     }
     __syncthreads();
 
+    GR_CLK(L, 3);
     // ---- the convex programs: program 0 = inner system, then every outer block of two or more tokens
     int status = GR_ROW_OK, evals = 0;
     for (int b = (h > 0 ? 0 : 1); b <= nblk && status != GR_ROW_TRUNC_CAP; ++b) {
@@ -1112,6 +1144,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         const double w0sum = block_sum<kSW>(tid < m ? L.wgt[L.apos[tid]] : 0.0, L.red);
         if (tid < m) L.at[tid] *= scale;
         __syncthreads();
+        GR_CLK(L, 4);
         const int rc = solve_program<D>(L, sp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
         if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
         const double wv = (tid < m) ? exp(L.aal[tid]) : 0.0;
@@ -1135,6 +1168,9 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         info.alpha_star = 1.0 + L.F[h];
         info.res_total = -L.F[h];
         info.node_tokens = L.work;
+#ifdef GR_PHASE_CLOCKS
+        { const long long now_ = clock64(); L.clk[14] += now_ - L.clk_last; for (int i = 0; i < 16; ++i) info.clk[i] = L.clk[i]; }
+#endif
         sp.info[row] = info;
         sp.accept_prob[row] = static_cast<float>(1.0 + L.F[h]);
         sp.status[row] = status;
