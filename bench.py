@@ -5,11 +5,11 @@ One "step" = the whole hot path over one batch of synthetic input already reside
 gr_solve (streaming support selection + per-row solve) followed by gr_verify.  Default workload:
 the large-vocabulary configuration (B=256 rows, V=128256, n=8 drafts, top-k 128).
 
-Two timed regions of the same K steps: first on one stream with HIP events around every launch (per-
-kernel launch durations, the roofline), then with the steps dealt round-robin to --streams handles on
-their own HIP streams (independent batches: a solve launch lasts as long as its slowest row, and the
-next batch's kernels fill the CUs that its finished rows have freed).  `value` is the second region's
-throughput; the first region's is reported beside it.
+The timed region: K steps on ONE stream, one batch at a time, between two device synchronisations, with HIP
+events around every step and around every kernel launch; `value` = B K / wall time of that region, the
+median step duration is reported beside it (`step_events`).  A second region deals the same K steps
+round-robin to --streams handles on their own HIP streams and input copies (several batches in flight);
+it is reported under `pipelined` and is not the headline.
 
 Prints ONE JSON line: solves/s, ms per step, the roofline of the dominant kernel (durations from
 HIP events recorded around every launch of the timed region) and the CPU checker timed on a
@@ -36,17 +36,45 @@ FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64
 MEASURED_TRAFFIC_BYTES = {"select_kernel": 266632000, "solve_kernel": 8921000, "verify_kernel": 603000}
 
 
-def cpu_baseline(wl, tol, budget_s=15.0):
-    """The CPU checker as it stands, single thread, on the first rows of the same batch."""
+def _oracle_row(job):
+    """One row through the CPU checker (a worker of the all-cores leg; also the single-thread leg's body)."""
     from oracle import gr_oracle as G
+    p, q, n, k, tol, drafts, u = job
+    sol = G.solve_row(p, q, n, k, tol=tol)
+    G.verify_row(sol, p, drafts, u)
+    return 1
+
+
+def _worker_init():
+    try:                                       # one thread per worker: the rows are the parallel axis
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+
+
+def cpu_baseline(wl, tol, budget_s=10.0):
+    """The CPU checker as it stands on the first rows of the same batch: single thread, then the same rows
+    farmed over the host cores the box gives this job (plain row-level multiprocessing; call it before the
+    GPU is initialised: the workers are forked)."""
+    import multiprocessing as mp
+    jobs = [(wl.p[b], wl.q[b], wl.n, wl.k, tol, wl.drafts[b], wl.uniforms[b]) for b in range(wl.B)]
     t0 = time.perf_counter(); rows = 0
     while rows < wl.B and time.perf_counter() - t0 < budget_s:
-        sol = G.solve_row(wl.p[rows], wl.q[rows], wl.n, wl.k, tol=tol)
-        G.verify_row(sol, wl.p[rows], wl.drafts[rows], wl.uniforms[rows])
-        rows += 1
+        _oracle_row(jobs[rows]); rows += 1
     dt = time.perf_counter() - t0
-    return {"value": rows / dt, "unit": "solves/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {rows} rows of the same batch, {dt:.1f} s, single thread"}
+    single = rows / dt
+    cores = max(1, min(16, os.cpu_count() or 1))
+    sample = min(wl.B, max(cores, int(single * budget_s * cores * 0.8)))
+    t1 = time.perf_counter()
+    with mp.get_context("fork").Pool(cores, initializer=_worker_init) as pool:
+        done = sum(pool.imap_unordered(_oracle_row, jobs[:sample], chunksize=1))
+    dt_all = time.perf_counter() - t1
+    return {"value": single, "unit": "solves/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {rows} rows of the same batch, {dt:.1f} s, single thread",
+            "all_cores": {"value": done / dt_all, "unit": "solves/s", "cores": cores, "kind": "oracle",
+                          "sample": f"first {done} rows of the same batch over {cores} worker processes, {dt_all:.1f} s "
+                                    f"(pool start-up included)"}}
 
 
 def bench_sweep(args):
@@ -127,12 +155,13 @@ def main():
 
     wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small, "stress": W.stress,
           "stress_full": lambda: W.stress(k=0)}[args.workload]()     # stress_full: no top-k, the support is the whole row
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.tol)      # before the GPU is touched: it forks workers
     dev = torch.device("cuda:0")
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     d = torch.from_numpy(wl.drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)
     acc = torch.empty(wl.B, dtype=torch.float32, device=dev); st = torch.empty(wl.B, dtype=torch.int32, device=dev)
     tok = torch.empty(wl.B, dtype=torch.int32, device=dev); ok = torch.empty(wl.B, dtype=torch.uint8, device=dev)
-    h = gr.gr_create(wl.B, wl.V, flags=0 if args.no_events else gr.GR_FLAG_PROFILE)
+    h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, flags=0 if args.no_events else gr.GR_FLAG_PROFILE)
 
     def step():
         gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
@@ -149,30 +178,44 @@ def main():
     torch.cuda.synchronize()
     if not args.no_events:
         gr.gr_profile_read(h)                      # drop the warm-up events
+    # HIP events around every step on the stream the kernels are launched on (torch's current stream)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if not args.no_events else None
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        if marks:
+            marks[i].record()
         step()
+    if marks:
+        marks[args.steps].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)) if marks else None
     prof = None if args.no_events else gr.gr_profile_read(h)
     stats = gr.gr_solve_stats(h, wl.B, dev)
     torch.cuda.synchronize()
     status = st.cpu().numpy(); iters = stats["evaluations"].cpu().numpy()
     node_tokens = float(stats["node_tokens"].sum().item())
     gr.gr_destroy(h)
-    single = {"value": wl.B * args.steps / dt, "ms_per_step": dt / args.steps * 1e3}
+    single_dt = dt
+    step_events = None
+    if step_ms:
+        med = step_ms[len(step_ms) // 2]
+        step_events = {"launches": len(step_ms), "median_ms": med, "mean_ms": sum(step_ms) / len(step_ms), "min_ms": step_ms[0],
+                       "max_ms": step_ms[-1], "solves_per_s_at_median": wl.B / (med * 1e-3)}
 
     # second region: the same K steps dealt to several handles, each on its own stream
     ns = max(1, min(args.streams, 8))
+    pipelined = None
     if ns > 1:
-        hs = [gr.gr_create(wl.B, wl.V) for _ in range(ns)]
+        hs = [gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n) for _ in range(ns)]
         ss = [torch.cuda.Stream() for _ in range(ns)]
         outs = [(torch.empty_like(acc), torch.empty_like(st), torch.empty_like(tok), torch.empty_like(ok)) for _ in range(ns)]
+        ins = [(p, q)] + [(p.clone(), q.clone()) for _ in range(ns - 1)]      # every stream reads its own copy of the batch
 
         def pstep(i):
             j = i % ns
             a, s_, t_, o_ = outs[j]
-            gr.gr_solve(hs[j], p, q, wl.n, wl.k, args.tol, a, s_, stream=ss[j])
+            gr.gr_solve(hs[j], ins[j][0], ins[j][1], wl.n, wl.k, args.tol, a, s_, stream=ss[j])
             gr.gr_verify(hs[j], d, u, t_, o_, stream=ss[j])
 
         for i in range(max(args.warmup, 2 * ns)):
@@ -182,12 +225,18 @@ def main():
         for i in range(args.steps):
             pstep(i)
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        pdt = time.perf_counter() - t0
         same = all(torch.equal(tok, o[2]) and torch.equal(acc, o[0]) for o in outs)
         for hh in hs:
             gr.gr_destroy(hh)
+        del ins
         if not same:
             sys.exit("bench.py: the pipelined region gave different results than the single-stream region")
+        pipelined = {"streams": ns, "value": wl.B * args.steps / pdt, "unit": "solves/s", "ms_per_step": pdt / args.steps * 1e3,
+                     "step_hbm_frac": 8.0 * wl.V * wl.B / (pdt / args.steps) / 1e9 / HBM_PEAK_GBS,
+                     "note": "the same K steps dealt round-robin to independent handles, each on its own HIP stream with its own "
+                             "copy of the inputs: several batches in flight, not the one-batch step of the headline"}
+    dt = single_dt
 
     # what a plain device copy of the same number of bytes reaches on this machine (read + write counted)
     nbytes = 8 * wl.V * wl.B
@@ -230,11 +279,13 @@ def main():
         if args.workload == "large" and abs(args.tol - 1e-4) < 1e-12:
             roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dom)
             roofline["traffic_all_kernels"] = MEASURED_TRAFFIC_BYTES or None
-        roofline["region"] = "single-stream region (launch durations; in the multi-stream region kernels of different steps overlap)"
+        roofline["region"] = "the timed region: one stream, one batch at a time (launch durations from HIP events)"
         roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
         roofline["events_steps"] = prof["steps"]
         roofline["select_hbm_frac"] = algo_bytes / (kernels[first] * 1e-3) / 1e9 / HBM_PEAK_GBS
         roofline["step_hbm_frac"] = algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+        if step_events:
+            roofline["step_hbm_frac_median"] = algo_bytes / (step_events["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
         roofline["device_copy_GBs"] = copy_gbs
         roofline["select_vs_device_copy"] = algo_bytes / (kernels[first] * 1e-3) / 1e9 / copy_gbs
     out = {
@@ -246,12 +297,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
-                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "streams": ns},
-        "single_stream": single,
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "streams": 1},
+        "step_events": step_events,
+        "pipelined": pipelined,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],
         "solver_evaluations_mean": float(iters.mean()), "solver_evaluations_max": int(iters.max()),
         "roofline": roofline,
-        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(wl, args.tol),
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

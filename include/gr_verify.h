@@ -19,9 +19,14 @@
  *   - every pointer argument except `out`, `cfg` and host-side scalars is a DEVICE pointer
  *     owned by the caller; the library never frees or keeps them beyond what is stated;
  *   - all work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream) and the calls do not synchronise with the host;
- *   - return value 0 = success, negative = call-level error (see GR_E*), nothing was
- *     enqueued in that case; per-row conditions never fail a call, they set status[b].
+ *     default stream); gr_solve, gr_accept_sweep, gr_verify and the inspection calls neither
+ *     allocate nor synchronise with the host (gr_create / gr_destroy allocate and free, and
+ *     gr_profile_read waits for its events);
+ *   - return value 0 = success, negative = call-level error (see GR_E*).  Argument and state errors
+ *     (GR_EINVAL, GR_ESTATE, GR_EUNSUPPORTED) are found before anything is enqueued; GR_EHIP reports
+ *     a failed launch, possibly after earlier kernels of the same call were enqueued: the handle then
+ *     holds no policy (GR_ESTATE until the next successful gr_solve).  Per-row conditions never fail a
+ *     call, they set status[b].
  *   - calls on one handle must not overlap in time (the handle owns scratch and the
  *     policy of the last gr_solve).
  */
@@ -53,7 +58,8 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_MAX_N         16    /* largest number of drafts */
 
 typedef struct {
-    int    max_iter;   /* cap on the evaluations of the routed masses per convex program; <= 0 selects 1000 */
+    int    max_iter;   /* cap on the evaluations of the routed masses of ONE convex program (App. "Truncated Solver
+                          Details": iteration cap of the minimiser); <= 0 selects 1000 */
     int    max_T;      /* cap on the variables of one program; <= 0 or > GR_MAX_T selects GR_MAX_T */
     double rel_tol;    /* stop when every routed mass is within this relative distance of its
                           target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-8, an order
@@ -63,20 +69,24 @@ typedef struct {
 
 #define GR_FLAG_PROFILE 1      /* record HIP events around every kernel launch (see gr_profile_read) */
 
-/* Create a handle able to serve up to max_B rows of up to max_V tokens.  cfg may be NULL.
- * Device memory held by the handle: about 150 KB per row (candidate keys, the policy object of
- * GR_MAX_SUPPORT entries, the Jacobian scratch of the solver's Newton fallback) plus 8 bytes per
- * 256 tokens and row; GR_ENOMEM if it cannot be allocated. */
-int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* cfg);
+/* Create a handle able to serve up to max_B rows of up to max_V tokens, supports (top-k sizes, App. "Top-k
+ * Sampling for the Relaxed OTLP") of up to max_k tokens (max_k <= 0 or >= max_V: whole rows, no top-k) and
+ * up to max_n drafts (1..GR_MAX_N).  cfg may be NULL.
+ * Device memory held by the handle until gr_destroy: about 150 KB per row (candidate keys, the policy
+ * object of GR_MAX_SUPPORT entries, the Jacobian scratch of the solver's Newton fallback) plus 8 bytes per
+ * 256 tokens and row; when max_k exceeds GR_MAX_SUPPORT, also 128 bytes per token of max_V and row (supports
+ * that large are ordered, scanned and kept in HBM; max_V must then stay below 2^24, otherwise
+ * GR_EUNSUPPORTED).  GR_ENOMEM if it cannot be allocated. */
+int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int max_n, const gr_config* cfg);
 int gr_destroy(gr_handle h);
 
 /*
  * p, q        [B, V] float32 row-major, each row a distribution (q before top-k).
- * n           number of i.i.d. drafts per row, 1..GR_MAX_N.
+ * n           number of i.i.d. drafts per row, 1..max_n of the handle.
  * k           top-k applied to q (ties: lower token id); k <= 0 or k >= V means none.
- *             A support above GR_MAX_SUPPORT (no top-k on a larger V, or a larger top-k) lives in a
- *             device workspace that this call allocates or grows (128 bytes per token of V and
- *             row); V must then stay below 2^24, otherwise GR_EUNSUPPORTED.
+ *             A support above GR_MAX_SUPPORT (no top-k on a larger V, or a larger top-k) needs a handle
+ *             created with max_k at least that large (GR_EINVAL otherwise): it lives in the handle's
+ *             HBM workspace.
  * tol         the paper's error threshold tau (Alg. 1), >= 0: truncation sets are the fewest
  *             tokens by decreasing q with gamma_T <= tol (inner) / epsilon_T <= tol (outer).
  * accept_prob [B] float32 out: alpha* (Thm 3.1).       status [B] int32 out: GR_ROW_*.
@@ -120,20 +130,24 @@ int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
 
 /* Test / inspection entry points --------------------------------------------------- */
 
-/* Dense slice: pi [B, V] float32 out = pi(.|drafts);  accept_given_drafts [B] float32 out =
- * sum of pi over the row's distinct drafts. */
+/* Dense slice of the transport for the drafted tuple, normalised by pdraft(drafts) (Eq. "cases" with
+ * the residual lift of Eq. (3); Eq. "approx-c" when truncated; Alg. 1 "return normalized C"):
+ * pi [B, V] float32 out = pi(.|drafts);  accept_given_drafts [B] float32 out = sum of pi over the row's
+ * distinct drafts.  drafts [B, n] int32 with B, n of the last gr_solve. */
 int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_given_drafts,
                     void* hip_stream);
 
 /* Per-row policy object, each array [B, GR_MAX_SUPPORT] (entries beyond support[b] are
- * unspecified): order = token ids by decreasing q/p; block = 0 for H*, b >= 1 for the
- * b-th outer block; weight = e^{alpha_i} (float64); rho = p(i) - p_i (float64).
+ * unspecified): order = token ids by decreasing q/p (Sec. 5.1); block = 0 for H* (Thm 3.1), b >= 1 for the
+ * b-th outer block (ranks between two consecutive suffix-minimum records of psi, Lemma 6.3);
+ * weight = e^{alpha_i}, the softmax parameters of Thm 6.5 (inside H*) / Thm 6.4 (outside), float64;
+ * rho = p(i) - p_i, the outer residuals of Thm 6.2, float64.
  * support, h_size, iterations: [B] int32.  Any pointer may be NULL. */
 int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
                      int* support, int* h_size, int* iterations, void* hip_stream);
 
-/* One row of the policy object, the first `count` ranks (count <= the row's support): the same
- * arrays as gr_policy_export.  This is the only export of a policy over a support above
+/* One row of the policy object (Thm 6.2 residuals, Thm 6.4 / 6.5 weights, as above), the first `count`
+ * ranks (count <= the row's support): the same arrays as gr_policy_export.  This is the only export of a policy over a support above
  * GR_MAX_SUPPORT, whose rows hold up to V entries.  Device pointers, any may be NULL. */
 int gr_policy_export_row(gr_handle h, int row, int count, int* order, int* block, double* weight,
                          double* rho, void* hip_stream);

@@ -13,6 +13,7 @@ Steps (paper citations in each function):
   5. truncated convex programs               Thm 6.4 (outer), Thm 6.5 (inner), Alg. 1
   6. transport slice pi(.|omega)             Eq. (cases), Eq. (approx-c), Lemma 6.6
   7. single-step multi-draft sampling        App. A, multi-draft procedure
+  8. rows given as logits and a temperature  App. A, first paragraph
 
 Where the paper leaves a choice open the reading taken is stated at the function.
 Parity status: every function below is pinned by tests/test_oracle_*.py against brute
@@ -494,6 +495,25 @@ def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
         blocks.append(blk)
     return RowSolution(V, n, np.array(order, int), {int(t): i for i, t in enumerate(order)}, p_s, q_s, P, Q, F, G, h,
                        alpha_star, rho, target, block_of, blocks, w, status, fragile)
+
+
+# ----------------------------------------------------------------- rows given as logits
+def softmax_from_logits(logits, temperature=1.0):
+    """App. A (review of single-step speculative sampling, first paragraph): temperature sampling only changes
+    how p and q are computed from the models' logits -- softmax(logits / T), here in float64."""
+    z = np.asarray(logits, np.float64) / float(temperature)
+    z = z - z.max()
+    e = np.exp(z)
+    return e / e.sum()
+
+
+def solve_row_from_logits(target_logits, draft_logits, temperature, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
+    """Alg. 1 for a decode position given by its target and draft logits and one sampling temperature: p and q are
+    the float64 softmaxes (top-k is then applied to q as in solve_row; the k largest logits are the k largest q).
+    Returns (RowSolution, p, q)."""
+    p = softmax_from_logits(target_logits, temperature)
+    q = softmax_from_logits(draft_logits, temperature)
+    return solve_row(p, q, n, k, tol=tol, max_T=max_T, max_iter=max_iter, rtol=rtol), p, q
 
 
 # ----------------------------------------------------------------- slice and sampling

@@ -35,6 +35,7 @@ class GrError(RuntimeError):
 
 
 _lib = None
+_solved_shape: dict = {}      # handle -> (B, n, V) of its last gr_solve (argument checking only)
 
 
 def load_library(path: str | None = None) -> ctypes.CDLL:
@@ -47,7 +48,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
         raise FileNotFoundError(f"{path} is missing: run `python __graft_entry__.py` (or paper_2511_15898_amd/build.py) first")
     lib = ctypes.CDLL(path)
     vp, ci = ctypes.c_void_p, ctypes.c_int
-    lib.gr_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.POINTER(GrConfig)]
+    lib.gr_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ctypes.POINTER(GrConfig)]
     lib.gr_destroy.argtypes = [vp]
     lib.gr_solve.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
@@ -82,16 +83,20 @@ def _stream(stream) -> int:
     return (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
 
 
-def gr_create(max_B: int, max_V: int, max_iter: int = 0, max_T: int = 0, rel_tol: float = 0.0, flags: int = 0) -> int:
+def gr_create(max_B: int, max_V: int, max_k: int = GR_MAX_SUPPORT, max_n: int = GR_MAX_N, max_iter: int = 0, max_T: int = 0,
+              rel_tol: float = 0.0, flags: int = 0) -> int:
+    """max_k: largest top-k support the handle will serve (<= 0: whole rows; above GR_MAX_SUPPORT the handle
+    holds an HBM workspace of 128 bytes per token and row)."""
     cfg = GrConfig(max_iter, max_T, rel_tol, flags)
     h = ctypes.c_void_p()
-    rc = load_library().gr_create(ctypes.byref(h), max_B, max_V, ctypes.byref(cfg))
+    rc = load_library().gr_create(ctypes.byref(h), max_B, max_V, max_k, max_n, ctypes.byref(cfg))
     if rc != GR_OK:
         raise GrError(rc, "gr_create")
     return h.value
 
 
 def gr_destroy(handle: int) -> None:
+    _solved_shape.pop(handle, None)
     rc = load_library().gr_destroy(handle)
     if rc != GR_OK:
         raise GrError(rc, "gr_destroy")
@@ -111,7 +116,9 @@ def gr_solve(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: int, tol:
                                  _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
                                  _stream(stream))
     if rc != GR_OK:
+        _solved_shape.pop(handle, None)
         raise GrError(rc, "gr_solve")
+    _solved_shape[handle] = (B, n, V)
     return accept_prob, status
 
 
@@ -138,10 +145,24 @@ def gr_accept_sweep(handle: int, p: torch.Tensor, q: torch.Tensor, ks, ns,
     return accept_prob, status
 
 
+def _check_drafts(handle: int, drafts: torch.Tensor, what: str, V: int | None = None) -> None:
+    """The library trusts the sizes of the last solve: refuse buffers of another shape here."""
+    shape = _solved_shape.get(handle)
+    if shape is None:
+        return                              # no solve yet: the library answers GR_ESTATE
+    if drafts.dim() != 2 or tuple(drafts.shape) != shape[:2]:
+        raise TypeError(f"{what}: drafts must be [B, n] = {shape[:2]} of the last gr_solve, got {tuple(drafts.shape)}")
+    if V is not None and V != shape[2]:
+        raise TypeError(f"{what}: V = {V} differs from the last gr_solve's {shape[2]}")
+
+
 def gr_verify(handle: int, drafts: torch.Tensor, uniforms: torch.Tensor, token: torch.Tensor | None = None,
               accepted: torch.Tensor | None = None, stream=None):
     """drafts [B, n] int32, uniforms [B] float32.  Returns (token [B] int32, accepted [B] uint8)."""
+    _check_drafts(handle, drafts, "gr_verify")
     B = drafts.shape[0]
+    if uniforms.dim() != 1 or uniforms.shape[0] != B:
+        raise TypeError("gr_verify: uniforms must be [B]")
     if token is None:
         token = torch.empty(B, dtype=torch.int32, device=drafts.device)
     if accepted is None:
@@ -155,6 +176,7 @@ def gr_verify(handle: int, drafts: torch.Tensor, uniforms: torch.Tensor, token: 
 
 def gr_policy_slice(handle: int, drafts: torch.Tensor, V: int, stream=None):
     """Dense pi(.|drafts) [B, V] float32 and the conditional acceptance [B] float32."""
+    _check_drafts(handle, drafts, "gr_policy_slice", V)
     B = drafts.shape[0]
     pi = torch.empty((B, V), dtype=torch.float32, device=drafts.device)
     acc = torch.empty(B, dtype=torch.float32, device=drafts.device)

@@ -9,6 +9,8 @@ namespace { constexpr int kProfSlots = 512; }
 
 struct gr_handle_s {
     int max_B = 0, max_V = 0;
+    int k_cap = 0;                 // largest support (top-k, or max_V for whole rows) the handle was created for
+    int max_n = GR_MAX_N;
     int max_iter = 1000, max_T = GR_MAX_T;
     double rel_tol = 1e-8;
     int device = 0;
@@ -25,7 +27,7 @@ struct gr_handle_s {
     bool profile = false;
     hipEvent_t ev[kProfSlots][5] = {};
     int prof_count = 0;
-    // full-vocabulary path: workspace (grown on demand by gr_solve) and the arguments of the last such solve
+    // full-vocabulary path: workspace (allocated by gr_create when k_cap exceeds GR_MAX_SUPPORT) and the arguments of the last such solve
     void* full_ws = nullptr; size_t full_ws_bytes = 0;
     FullParams full = {};
     bool full_mode = false;
@@ -82,17 +84,14 @@ PolicyView policy_view(gr_handle h) {
     return pv;
 }
 
-// Carve the workspace of the full-vocabulary path out of one allocation (grown, never shrunk).
+constexpr size_t kFullPad = 256;
+size_t full_ws_bytes(size_t rows, size_t vs) { return rows * vs * kFullBytesPerToken + 40 * kFullPad + rows * 3 * sizeof(int); }
+
+// Carve the workspace of the full-vocabulary path (allocated once by gr_create) for a batch of B rows of V tokens.
 int prepare_full(gr_handle h, int B, int V) {
     const size_t vs = static_cast<size_t>(V) + 2, rows = static_cast<size_t>(B);
-    const size_t per_array_pad = 256;
-    const size_t need = rows * vs * kFullBytesPerToken + 40 * per_array_pad + rows * 3 * sizeof(int);
-    if (need > h->full_ws_bytes) {
-        (void)hipFree(h->full_ws);
-        h->full_ws = nullptr; h->full_ws_bytes = 0;
-        if (hipMalloc(&h->full_ws, need) != hipSuccess) { (void)hipGetLastError(); return GR_ENOMEM; }
-        h->full_ws_bytes = need;
-    }
+    const size_t per_array_pad = kFullPad;
+    if (full_ws_bytes(rows, vs) > h->full_ws_bytes) return GR_EINVAL;      // cannot happen for B <= max_B, V <= max_V
     unsigned char* cur = static_cast<unsigned char*>(h->full_ws);
     auto take = [&](size_t bytes) { void* r = cur; cur += (bytes + per_array_pad - 1) / per_array_pad * per_array_pad; return r; };
     FullParams& f = h->full;
@@ -110,12 +109,39 @@ int prepare_full(gr_handle h, int B, int V) {
 
 }  // namespace
 
-extern "C" int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* cfg) {
+namespace {
+
+// Argument checks and grid of a sweep, shared by both entry points.
+int fill_sweep(SweepParams& sw, const int* ks, int nk, const int* ns, int nn, int V) {
+    if (nk < 1 || nk > kSweepMaxK || nn < 1 || nn > kSweepMaxN) return GR_EINVAL;
+    sw.kmax = 0;
+    for (int i = 0; i < nk; ++i) {
+        if (ks[i] < 1 || ks[i] > kMaxSupport) return GR_EINVAL;
+        sw.ks[i] = ks[i];
+        if (ks[i] > sw.kmax) sw.kmax = ks[i];
+    }
+    for (int i = 0; i < nn; ++i) {
+        if (ns[i] < 1 || ns[i] > kSweepMaxDrafts) return GR_EINVAL;
+        sw.ns[i] = ns[i];
+    }
+    if (sw.kmax > V) sw.kmax = V;                        // a top-k of V or more keeps every positive entry
+    for (int i = nk; i < kSweepMaxK; ++i) sw.ks[i] = 0;
+    for (int i = nn; i < kSweepMaxN; ++i) sw.ns[i] = 1;
+    sw.nk = nk; sw.nn = nn; sw.V = V;
+    return GR_OK;
+}
+
+}  // namespace
+
+extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int max_n, const gr_config* cfg) {
     if (!out || max_B <= 0 || max_V <= 0) return GR_EINVAL;
+    if (max_n < 1 || max_n > GR_MAX_N) return GR_EINVAL;
+    const int k_cap = (max_k <= 0 || max_k >= max_V) ? max_V : max_k;
+    if (k_cap > kMaxSupport && max_V >= (1 << 24)) return GR_EUNSUPPORTED;
     if (cfg && (cfg->flags & ~GR_FLAG_PROFILE) != 0) return GR_EINVAL;
     gr_handle h = new (std::nothrow) gr_handle_s();
     if (!h) return GR_ENOMEM;
-    h->max_B = max_B; h->max_V = max_V;
+    h->max_B = max_B; h->max_V = max_V; h->k_cap = k_cap; h->max_n = max_n;
     if (cfg) {
         if (cfg->max_iter > 0) h->max_iter = cfg->max_iter;
         if (cfg->max_T > 0 && cfg->max_T <= GR_MAX_T) h->max_T = cfg->max_T;
@@ -133,6 +159,12 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, const gr_config* 
     h->piece_stride = (max_V + kSelTile - 1) / kSelTile * (kSelTile / 256) + kMaxSplits * (kSelTile / 256);
     ok = ok && dev_alloc(&h->piece_psum, rows * h->piece_stride);
     ok = ok && dev_alloc(&h->newton_ws, rows * kMaxT * (kMaxT + 1));
+    if (ok && k_cap > kMaxSupport) {
+        // supports above GR_MAX_SUPPORT live in HBM: 128 bytes per token of max_V and row, held until gr_destroy
+        const size_t need = full_ws_bytes(rows, static_cast<size_t>(max_V) + 2);
+        ok = hipMalloc(&h->full_ws, need) == hipSuccess;
+        if (ok) h->full_ws_bytes = need;
+    }
     if (!ok) { free_all(h); delete h; (void)hipGetLastError(); return GR_ENOMEM; }
     if (cfg && (cfg->flags & GR_FLAG_PROFILE)) {
         h->profile = true;
@@ -155,9 +187,10 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
                         int B, int V, float* accept_prob, int* status, void* hip_stream) {
     if (!h || !p || !q || !accept_prob || !status) return GR_EINVAL;
     if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
-    if (n < 1 || n > GR_MAX_N) return GR_EINVAL;
+    if (n < 1 || n > h->max_n) return GR_EINVAL;
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
+    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (k_eff > kMaxSupport) {
         // a support above GR_MAX_SUPPORT (no top-k, or a large one): the HBM-resident path
@@ -205,21 +238,9 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
                                int B, int V, float* accept_prob, int* status, void* hip_stream) {
     if (!h || !p || !q || !ks || !ns || !accept_prob || !status) return GR_EINVAL;
     if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
-    if (nk < 1 || nk > kSweepMaxK || nn < 1 || nn > kSweepMaxN) return GR_EINVAL;
     SweepParams sw;
-    sw.kmax = 0;
-    for (int i = 0; i < nk; ++i) {
-        if (ks[i] < 1 || ks[i] > kMaxSupport) return GR_EINVAL;
-        sw.ks[i] = ks[i];
-        if (ks[i] > sw.kmax) sw.kmax = ks[i];
-    }
-    for (int i = 0; i < nn; ++i) {
-        if (ns[i] < 1 || ns[i] > kSweepMaxDrafts) return GR_EINVAL;
-        sw.ns[i] = ns[i];
-    }
-    if (sw.kmax > V) sw.kmax = V;                        // a top-k of V or more keeps every positive entry
-    for (int i = nk; i < kSweepMaxK; ++i) sw.ks[i] = 0;
-    for (int i = nn; i < kSweepMaxN; ++i) sw.ns[i] = 1;
+    const int rcf = fill_sweep(sw, ks, nk, ns, nn, V);
+    if (rcf != GR_OK) return rcf;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int splits = choose_splits(B, V);
     int slice_len = (V + splits - 1) / splits;
@@ -228,9 +249,9 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
     launch_select(p, q, B, V, sw.kmax, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
                   h->part_bad, h->piece_psum, h->piece_stride, stream);
     if (hipGetLastError() != hipSuccess) return GR_EHIP;
-    sw.p = p; sw.V = V; sw.splits = splits;
+    sw.p = p; sw.splits = splits;
     sw.cand = h->cand; sw.cand_count = h->cand_count; sw.part_psum = h->part_psum; sw.part_qsum = h->part_qsum;
-    sw.part_bad = h->part_bad; sw.nk = nk; sw.nn = nn; sw.accept_prob = accept_prob; sw.status = status;
+    sw.part_bad = h->part_bad; sw.accept_prob = accept_prob; sw.status = status;
     if (launch_sweep(sw, B, stream) != hipSuccess) return GR_EHIP;
     return GR_OK;
 }
@@ -352,10 +373,11 @@ namespace {
 __global__ void clocks_kernel(const RowInfo* info, int B, long long* out) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    for (int i = 0; i < 16; ++i) out[b * 16 + i] = info[b].clk[i];
+    for (int i = 0; i < 24; ++i) out[b * 48 + i] = info[b].clk[i];
+    for (int i = 0; i < 24; ++i) out[b * 48 + 24 + i] = __double_as_longlong(info[b].errlog[i]);
 }
 }  // namespace
-// Profiling builds only: cycles of thread 0 per phase of the last solve, [B, 16] int64 device array.
+// Profiling builds only: cycles of thread 0 per phase of the last solve, [B, 48] int64 (24 cycle counts, then 24 doubles) device array.
 extern "C" int gr_debug_clocks(gr_handle h, long long* out, void* hip_stream) {
     if (!h || !out || !h->solved) return GR_EINVAL;
     hipLaunchKernelGGL(clocks_kernel, dim3((h->B + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream), h->info, h->B, out);

@@ -28,7 +28,8 @@ struct RowInfo {
     double q_total;     // float64 row sum of q (before top-k)
     double node_tokens; // sum over evaluator calls of (quadrature nodes x active tokens)
 #ifdef GR_PHASE_CLOCKS
-    long long clk[16];  // shader-clock cycles of thread 0 per phase of the solve kernel (profiling builds only)
+    long long clk[24];  // shader-clock cycles of thread 0 per phase of the solve kernel (profiling builds only)
+    double errlog[24];  // stopping measure after each of the first evaluations
 #endif
 };
 

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
             const double p4 = (static_cast<double>(pv[0]) + static_cast<double>(pv[1])) +
                               (static_cast<double>(pv[2]) + static_cast<double>(pv[3]));
             const double pw = wave_sum(p4);
-            if ((tid & 63) == 0) piece_psum[static_cast<size_t>(b) * piece_stride + (base >> 8) + (tid >> 6)] = pw;
+            if (piece_psum && (tid & 63) == 0) piece_psum[static_cast<size_t>(b) * piece_stride + (base >> 8) + (tid >> 6)] = pw;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

@@ -14,16 +14,22 @@
 // over draft tuples; here it is evaluated in polynomial time from
 //     1/x = int_0^inf e^{-xt} dt,
 //     E[ prod_{i in set(tuple)} x_i ] = n! [z^n] e^{z ctx} prod_i (1 + x_i (e^{z q_i} - 1)),  x_i = e^{-t w_i},
-// with truncated power series in z (degree n) and the trapezoid rule in log t: lanes are quadrature
-// nodes, waves split the tokens, the series live in registers.
+// with power series in z truncated at degree n and the trapezoid rule in log t.  The product is taken
+// through its logarithm: log(1 + x (e^u - 1)) = sum_k kappa_k(x) u^k / k! with the cumulants of a
+// Bernoulli(x) variable, and only k <= n can reach the z^n coefficient, so n cumulant sums per
+// quadrature node describe all tokens exactly; the series exponential is taken once per node.
 #include "gr_internal.h"
 
 namespace gr {
 
+// The workgroup's LDS (dynamic: its size is that of Lds<D>), named at file scope so that functions that are not
+// inlined address it as LDS and not through generic pointers.
+extern __shared__ __align__(16) unsigned char gr_lds_raw[];
+
 namespace {
 
 // Optional cycle accounting (builds with -DGR_PHASE_CLOCKS only): thread 0 adds the shader-clock cycles since
-// its previous mark to one of 16 slots; the totals per row are written to RowInfo::clk.
+// its previous mark to one of 24 slots; the totals per row are written to RowInfo::clk.
 #ifdef GR_PHASE_CLOCKS
 #define GR_CLK(L, slot) do { if (threadIdx.x == 0) { const long long now_ = clock64(); (L).clk[slot] += now_ - (L).clk_last; (L).clk_last = now_; } } while (0)
 #else
@@ -31,134 +37,246 @@ namespace {
 #endif
 
 constexpr int KS = kMaxSupport;
-constexpr int kST = 256;             // threads of the solve workgroup (one wave per SIMD: each may use all 512 registers)
-constexpr int kSW = kST / 64;
+// Threads of the solve workgroup: eight waves (two per SIMD, 256 registers each) up to 8 drafts, so that one
+// wave's dependent float64 chains and LDS waits are filled by the other; four waves (one per SIMD, all 512
+// registers) for the longer series of 9 to 16 drafts.
+#ifndef GR_THREADS_UP_TO_8
+#define GR_THREADS_UP_TO_8 512
+#endif
+template <int D> constexpr int kThreadsOf = D > 8 ? 256 : GR_THREADS_UP_TO_8;
 constexpr double kQuadStep = 0.45;   // trapezoid step in log t (discretisation error ~1e-9 relative)
 constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t_lo is added in closed form
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
-constexpr double kStretch = 4.0;      // first cap on the per-coordinate stretch of the fixed-point step
+constexpr double kStretch = 4.0;     // first cap on the per-coordinate stretch of the fixed-point step
 constexpr int kStall = 3;            // iterations without a better point before the cap is halved
 constexpr int kMixBudget = 60;       // the mixed fixed-point iteration gets kMixBudget + m evaluations before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
-constexpr int kGram = kCols * (kCols + 1) / 2 + kCols; // upper triangle of the Gram matrix + right-hand side
+constexpr int kMaxHeavy = 3;         // tokens that keep their exact factor (only with more than 8 drafts)
+constexpr double kHeavyShare = 0.3;  // ... those above this share of the program's draw mass
 
-// Operands of the light-token arithmetic, packed so that one token (phase 1) or one quadrature node
-// (phase 3) is three 16-byte LDS reads at constant offsets.
-struct alignas(16) NodeRec { double t, qw, T[4]; };          // abscissa, weight, total series at degrees n-1 .. n-4
-struct alignas(16) TokRec { double aw, e[4], pad; };         // weight, q^k / k! for k = 1..4
+// Operands of one token / one quadrature node, packed so that they are a few 16-byte LDS reads.
+template <int D> struct alignas(16) TokRec { double aw; double e[D]; double pad; };     // weight; e[k-1] = q^k / k! (0 for k > n)
+template <int D> struct alignas(16) NodeRec { double t, qw; double Tr[D]; };            // abscissa, quadrature weight; Tr[k-1] = T_{n-k}
 
-// D: the series degree of the kernel (>= n): the per-token and per-node series hold D + 1 terms, so the
-// kernels of small D leave LDS for a streaming workgroup of the next batch beside a live row.
+// The quadrature grid of one evaluation: nodes t_lo e^{step j}, j = 0..N-1, and the closed-form sums over the
+// nodes below t_lo (x = 1 there) of the integral of 1 (tail) and of t (tail2).
+struct Grid { double t_lo, step, tail, tail2; int N; };
+
+// D: the series degree of the kernel (>= n).
 template <int D>
 struct Lds {
-    static constexpr int kS = D + 1;  // stride of a series
+    static constexpr int kST = kThreadsOf<D>;
+    static constexpr int kSW = kST / 64;
+    static constexpr int kNPW = 64 / kSW;   // quadrature nodes a wave owns within a chunk of 64
     // support, in ratio order
     int tok[KS]; int blk[KS]; int inT[KS]; int ordq[KS]; int apos[kMaxT];
     int flag[KS + 2]; int blo[KS + 2];
     double qn[KS]; double pn[KS]; double rho[KS]; double tgt[KS]; double wgt[KS];
     double Q[KS + 1]; double F[KS + 2];
-    // one convex program
-    double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aw[kMaxT]; double aR[kMaxT]; double af[kMaxT];
+    // one convex program (tokens by decreasing q)
+    double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aR[kMaxT];
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
-    double etab[kMaxT * kS];        // q^a / a!, a = 0..D
-    int adeg[kMaxT];                // degree at which the token's exponential series may be cut
+    double aw[kMaxT]; double af[kMaxT]; int adeg[kMaxT];   // staging of the HBM-path programs kernel
     // Newton fallback (its Jacobian lives in a per-row HBM scratch)
     double nR[kMaxT]; double nstep[kMaxT]; double nsave[kMaxT]; int nused[kMaxT]; int ncolof[kMaxT];
-    double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
-    double gram[kGram]; double gamma[kCols];
-    // evaluator: node abscissae and weights, total series per node, per-wave partial routed mass
-    double tnode[64]; double qwnode[64]; double Tl[64 * kS];
-    double aS[kMaxT];               // routed mass weighted by the node abscissa t; aS_i = R_i - dR_i/d(log w_i)
     // scans and counters of the prologue (dead once the first program starts) share their bytes with the
-    // evaluator's per-wave partial sums
+    // evaluator's records and per-wave partial sums
     union {
         struct {
-            int cnt0[KS + 2]; int cnt1[KS + 2];
+            int cnt0[KS + 2]; int cnt1[KS + 2]; int ids[KS]; int byq[KS];
             double qd[KS]; double accb[KS];
             double P[KS + 1]; double S[KS + 1]; double G0[KS + 2]; double G1[KS + 2];
         };
         struct {
-            double rpart[kSW][kMaxT];
-            double spart[kSW][kMaxT];   // the same sums weighted by t
-            double cum[kSW * 4 * 64];   // per-wave cumulant sums of the light tokens, per node
+            double rpart[kSW][kMaxT];   // per wave: sum over its nodes of the integrand of each token
+            double spart[kSW][kMaxT];   // the same weighted by t
+            NodeRec<D> nrec[kSW][kNPW];
+            TokRec<D> trec[kMaxT + 4];  // active tokens; the 4 beyond the last have aw = 1e300 (x = 0)
         };
     };
-    NodeRec nrec[64 + 16];          // nodes of the current chunk; the 16 beyond are zero (weight 0)
-    TokRec trec[kMaxT + 16];        // active tokens; the 16 beyond the last have aw = 1e300 (x = 0)
+    double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
+    double pm[kHist][kHist];        // inner products of the stored residual vectors of the mixing, by history slot
+    Grid ctl_grid; int ctl_go, ctl_result, ctl_bestok;   // handed from the mixing wave to all waves
     double e2tab[32];               // 2^(-j/32)
-    int nbig;                       // number of heavy tokens of the current program
+    int nheavy;                     // leading tokens that keep their exact factor
+    int nfull;                      // leading tokens (the heavy ones included) that need all D cumulants; the rest need four
     double work;                    // sum over evaluator calls of nodes x active tokens (thread 0 only)
 #ifdef GR_PHASE_CLOCKS
-    long long clk[16]; long long clk_last;
+    long long clk[24]; long long clk_last; double errlog[24];
 #endif
-    double red[kSW]; double R0acc; int ok; int pick[4]; int count; int hist[256];
-    // unsorted candidates (select merge), later the per-wave partial products of the evaluator
-    union {
-        unsigned long long keys[kSelCap];
-        double part[kSW * kS * 64];
-    } u;
+    double red[2][kSW][8]; double redn[kSW]; double r0part[kSW]; int pick[4]; int count; int hist[256];
+    unsigned long long keys[kSelCap];   // unsorted candidates (select merge)
 };
 
+// ---- workgroup reductions with one barrier: the waves' partial results alternate between two LDS
+// strips (`par`), so the strip of the reduction before the previous one is free again.
+enum { kOpSum = 0, kOpMax = 1, kOpMin = 2 };
+__device__ __forceinline__ double combine(double a, double b, int op) {
+    return op == kOpSum ? a + b : (op == kOpMax ? fmax(a, b) : fmin(a, b));
+}
+// Several reductions over the lanes of one wave at once (their butterfly steps interleave): every lane ends with
+// the results.  All 64 lanes must be active.
+template <int NV>
+__device__ __forceinline__ void wave_reduce_many(double (&v)[NV], const int (&op)[NV]) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = combine(v[j], dpp_move<kDppXor1>(v[j]), op[j]);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = combine(v[j], dpp_move<kDppXor2>(v[j]), op[j]);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = combine(v[j], dpp_move<kDppHalfMirror>(v[j]), op[j]);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) v[j] = combine(v[j], dpp_move<kDppMirror>(v[j]), op[j]);
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+        v[j] = combine(combine(read_lane(v[j], 0), read_lane(v[j], 16), op[j]), combine(read_lane(v[j], 32), read_lane(v[j], 48), op[j]), op[j]);
+}
 
-// e^{-y} for y >= 0: Cody-Waite reduction by ln 2 and a degree-12 Taylor polynomial on
-// |r| <= ln(2)/2 (relative error below 1e-15; underflows to 0 beyond y = 708).
-__device__ __forceinline__ double exp_neg(double y) {
-    if (y > 708.0) return 0.0;
-    const double k = rint(y * 1.4426950408889634);
-    double r = fma(k, -6.93147180369123816490e-01, y);
-    r = fma(k, -1.90821492927058770002e-10, r);
-    r = -r;
-    double p = 2.08767569878680989792e-09;              // 1/12!
-    p = fma(p, r, 2.50521083854417187751e-08);           // 1/11!
-    p = fma(p, r, 2.75573192239858906526e-07);           // 1/10!
-    p = fma(p, r, 2.75573192239858906526e-06);           // 1/9!
-    p = fma(p, r, 2.48015873015873015873e-05);           // 1/8!
-    p = fma(p, r, 1.98412698412698412698e-04);           // 1/7!
-    p = fma(p, r, 1.38888888888888888889e-03);           // 1/6!
-    p = fma(p, r, 8.33333333333333333333e-03);           // 1/5!
-    p = fma(p, r, 4.16666666666666666667e-02);           // 1/4!
-    p = fma(p, r, 1.66666666666666666667e-01);           // 1/3!
+// v[j] holds this wave's partial result of operation op[j]; on return it holds the workgroup's.  After the
+// barrier lane l reads the partial of wave l mod NW (one LDS instruction per value and wave, not NW), and a
+// butterfly over NW neighbouring lanes combines them: every lane ends with the same bits.
+template <int NV, class LdsT>
+__device__ __forceinline__ void wg_reduce(LdsT& L, int& par, double (&v)[NV], const int (&op)[NV]) {
+    constexpr int NW = LdsT::kSW;
+    static_assert(NW == 4 || NW == 8, "the butterfly below covers four or eight waves");
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) L.red[par][wv][j] = v[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        double r = L.red[par][lane & (NW - 1)][j];
+        r = combine(r, dpp_move<kDppXor1>(r), op[j]);
+        r = combine(r, dpp_move<kDppXor2>(r), op[j]);
+        if (NW == 8) r = combine(r, dpp_move<kDppHalfMirror>(r), op[j]);
+        v[j] = r;
+    }
+    par ^= 1;
+}
+template <class LdsT> __device__ __forceinline__ double wg_sum(LdsT& L, int& par, double v) {
+    double a[1] = {wave_sum(v)};
+    wg_reduce<1>(L, par, a, {kOpSum});
+    return a[0];
+}
+template <class LdsT> __device__ __forceinline__ double wg_max(LdsT& L, int& par, double v) {
+    double a[1] = {wave_max(v)};
+    wg_reduce<1>(L, par, a, {kOpMax});
+    return a[0];
+}
+
+// e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
+// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
+__device__ __forceinline__ double exp_neg(double y, const double* tab) {
+    const double yc = fmin(y, 1000.0);
+    const double kf = rint(yc * 46.166241308446828);
+    const int ki = static_cast<int>(kf);
+    const double tv = tab[ki & 31];
+    double r = fma(kf, -(6.93147180369123816490e-01 / 32.0), yc);
+    r = -fma(kf, -(1.90821492927058770002e-10 / 32.0), r);
+    double p = 8.33333333333333333333e-03;
+    p = fma(p, r, 4.16666666666666666667e-02);
+    p = fma(p, r, 1.66666666666666666667e-01);
     p = fma(p, r, 0.5);
     p = fma(p, r, 1.0);
     p = fma(p, r, 1.0);
-    return ldexp(p, -static_cast<int>(k));
+    return ldexp(p * tv, -(ki >> 5));                          // 2^-1442 flushes to 0
 }
 
-// A(z) <- A(z) * (1 + x (e^{zq} - 1)), the exponential series cut at degree C <= D.
-// e[a] = q^a / a!.
-template <int D, int C>
-__device__ __forceinline__ void mul_factor(double (&A)[D + 1], double x, const double* e) {
-    double ee[C + 1];
+// 1/x from the hardware estimate and two Newton steps (about 1e-16 relative; x = 0, infinite or NaN gives NaN or 0).
+__device__ __forceinline__ double fast_rcp(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = r * fma(-x, r, 2.0);
+    r = r * fma(-x, r, 2.0);
+    return r;
+}
+
+// e^x for |x| <= 1000 (clamped beyond) with the table of exp_neg: x = -(k ln2/32 + r), k of either sign.
+__device__ __forceinline__ double exp_signed(double x, const double* tab) {
+    const double y = fmax(fmin(-x, 1000.0), -1000.0);
+    const double kf = rint(y * 46.166241308446828);
+    const int ki = static_cast<int>(kf);
+    const double tv = tab[ki & 31];                            // k = 32 (k >> 5) + (k & 31), also for negative k
+    double r = fma(kf, -(6.93147180369123816490e-01 / 32.0), y);
+    r = -fma(kf, -(1.90821492927058770002e-10 / 32.0), r);
+    double p = 8.33333333333333333333e-03;
+    p = fma(p, r, 4.16666666666666666667e-02);
+    p = fma(p, r, 1.66666666666666666667e-01);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p * tv, -(ki >> 5));
+}
+
+// log(x) to about 1e-16 relative for positive normal x: x = 2^e m with m in [sqrt(1/2), sqrt(2)),
+// log m = 2 atanh(s) = 2 s (1 + s^2/3 + s^4/5 + ...), s = (m - 1) / (m + 1), |s| <= 0.172 (eleven terms).
+// Anything else (zero, negative, denormal, infinite, NaN) goes to the library routine.
+__device__ __forceinline__ double fast_log(double x) {
+    if (!(x >= 2.3e-308 && x <= 1.7e308)) return log(x);
+    int e;
+    double m = frexp(x, &e);                                   // m in [1/2, 1)
+    if (m < 0.70710678118654752) { m *= 2.0; e -= 1; }
+    const double s = (m - 1.0) * fast_rcp(m + 1.0), z = s * s;
+    double p = 1.0 / 21.0;
+    p = fma(p, z, 1.0 / 19.0); p = fma(p, z, 1.0 / 17.0); p = fma(p, z, 1.0 / 15.0); p = fma(p, z, 1.0 / 13.0);
+    p = fma(p, z, 1.0 / 11.0); p = fma(p, z, 1.0 / 9.0); p = fma(p, z, 1.0 / 7.0); p = fma(p, z, 1.0 / 5.0);
+    p = fma(p, z, 1.0 / 3.0); p = fma(p, z, 1.0);
+    const double ed = static_cast<double>(e);
+    return fma(ed, 6.93147180369123816490e-01, fma(2.0 * s, p, ed * 1.90821492927058770002e-10));
+}
+
+// Cumulants of a Bernoulli(x) variable: kappa_1 = x, kappa_{k+1} = v g_k with v = x (1 - x),
+// g_k = d kappa_k / dx = a_k(v) for odd k, s a_k(v) for even k, s = 1 - 2x (from kappa_{k+1} = x (1 - x) kappa_k').
+// Row k: the coefficients of a_k in rising powers of v.
+__device__ constexpr double kCumA[17][8] = {
+    {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -6.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -12.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -30.0, 120.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -60.0, 360.0, 0.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -126.0, 1680.0, -5040.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -252.0, 5040.0, -20160.0, 0.0, 0.0, 0.0, 0.0},
+    {1.0, -510.0, 17640.0, -151200.0, 362880.0, 0.0, 0.0, 0.0},
+    {1.0, -1020.0, 52920.0, -604800.0, 1814400.0, 0.0, 0.0, 0.0},
+    {1.0, -2046.0, 168960.0, -3160080.0, 19958400.0, -39916800.0, 0.0, 0.0},
+    {1.0, -4092.0, 506880.0, -12640320.0, 99792000.0, -239500800.0, 0.0, 0.0},
+    {1.0, -8190.0, 1561560.0, -57657600.0, 726485760.0, -3632428800.0, 6227020800.0, 0.0},
+    {1.0, -16380.0, 4684680.0, -230630400.0, 3632428800.0, -21794572800.0, 43589145600.0, 0.0},
+    {1.0, -32766.0, 14217840.0, -988107120.0, 22313491200.0, -210680870400.0, 871782912000.0, -1307674368000.0},
+    {1.0, -65532.0, 42653520.0, -3952428480.0, 111567456000.0, -1264085222400.0, 6102480384000.0, -10461394944000.0},
+};
+
+// g[k-1] = g_k(x) for k = 1..C.
+template <int K, int C>
+__device__ __forceinline__ void cum_g_from(double v, double s, double (&g)[C]) {
+    if constexpr (K <= C) {
+        constexpr int deg = (K - 1) / 2;
+        double r = kCumA[K][deg];
 #pragma unroll
-    for (int a = 1; a <= C; ++a) ee[a] = e[a];
+        for (int j = deg - 1; j >= 0; --j) r = fma(r, v, kCumA[K][j]);
+        g[K - 1] = (K % 2 == 0) ? r * s : r;
+        cum_g_from<K + 1, C>(v, s, g);
+    }
+}
+
+// A(z) <- A(z) * (1 + x (e^{zq} - 1)), e[a-1] = q^a / a!.
+template <int D>
+__device__ __forceinline__ void mul_factor(double (&A)[D + 1], double x, const double (&e)[D]) {
 #pragma unroll
     for (int d = D; d >= 1; --d) {
         double acc = 0.0;
 #pragma unroll
-        for (int a = 1; a <= (d < C ? d : C); ++a) acc = fma(ee[a], A[d - a], acc);
+        for (int a = 1; a <= d; ++a) acc = fma(e[a - 1], A[d - a], acc);
         A[d] = fma(x, acc, A[d]);
     }
 }
 
-// A(z) <- A(z) * B(z), truncated at degree D.
+// [z^n] of  (e^{zq} - 1) * T(z) / (1 + x (e^{zq} - 1)): the leave-one-out coefficient of a token that
+// keeps its exact factor, by series division (the quotient is only needed below degree n).
 template <int D>
-__device__ __forceinline__ void mul_series(double (&A)[D + 1], const double (&B)[D + 1]) {
-#pragma unroll
-    for (int d = D; d >= 0; --d) {
-        double acc = 0.0;
-#pragma unroll
-        for (int a = 0; a <= d; ++a) acc = fma(A[a], B[d - a], acc);
-        A[d] = acc;
-    }
-}
-
-// [z^n] of  (e^{zq} - 1) * T(z) / (1 + x (e^{zq} - 1)): the leave-one-out coefficient of a token,
-// by series division (the quotient is only needed below degree n).
-template <int D, int C>
-__device__ __forceinline__ double loo_coeff(const double (&T)[D + 1], double x, const double* e, int n) {
-    double ee[C + 1];
-#pragma unroll
-    for (int a = 1; a <= C; ++a) ee[a] = e[a];
+__device__ __forceinline__ double loo_coeff(const double (&T)[D + 1], double x, const double (&e)[D], int n) {
     double Bq[D + 1];
     Bq[0] = T[0];
     double cn = 0.0;
@@ -166,411 +284,321 @@ __device__ __forceinline__ double loo_coeff(const double (&T)[D + 1], double x, 
     for (int d = 1; d <= D; ++d) {
         double conv = 0.0;
 #pragma unroll
-        for (int a = 1; a <= (d < C ? d : C); ++a) conv = fma(ee[a], Bq[d - a], conv);
+        for (int a = 1; a <= d; ++a) conv = fma(e[a - 1], Bq[d - a], conv);
         Bq[d] = fma(-x, conv, T[d]);
         if (d == n) cn = conv;
     }
     return cn;
 }
 
-// Four independent copies of the primitives, interleaved instruction by instruction so that the
-// dependent fp64 chains of one copy fill the latency of the others.
-//
-// e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
-// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
-__device__ __forceinline__ void exp_neg4(const double (&y)[4], double (&out)[4], const double* tab) {
-    double kf[4], r[4], p[4], tv[4];
-    int ki[4];
+// rec.Tr[k-1] = T_{NN-k} (0 below degree 0); returns T_NN.
+template <int D, int NN>
+__device__ __forceinline__ double pick_series(NodeRec<D>& rec, const double (&T)[D + 1], int n) {
+    if constexpr (NN >= 1) {
+        if (n == NN) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) kf[j] = rint(fmin(y[j], 1000.0) * 46.166241308446828);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) { ki[j] = static_cast<int>(kf[j]); tv[j] = tab[ki[j] & 31]; }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = fma(kf[j], -(6.93147180369123816490e-01 / 32.0), fmin(y[j], 1000.0));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = -fma(kf[j], -(1.90821492927058770002e-10 / 32.0), r[j]);
-    const double c[5] = {4.16666666666666666667e-02, 1.66666666666666666667e-01, 0.5, 1.0, 1.0};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) p[j] = 8.33333333333333333333e-03;
-#pragma unroll
-    for (int i = 0; i < 5; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) p[j] = fma(p[j], r[j], c[i]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) out[j] = ldexp(p[j] * tv[j], -(ki[j] >> 5));      // 2^-1442 flushes to 0
+            for (int k = 1; k <= D; ++k) rec.Tr[k - 1] = (NN - k >= 0) ? T[(NN - k >= 0) ? NN - k : 0] : 0.0;
+            return T[NN];
+        }
+        return pick_series<D, NN - 1>(rec, T, n);
+    } else {
+        return 0.0;
+    }
 }
 
+// Phase 1, one token at one node: its cumulant terms into the node's sums, K[k-1] += kappa_k(x) q^k / k!
+// for k <= C (C = D: exact; C = 4 for a token so small that its higher terms cannot reach the z^n
+// coefficient within 1e-11).
 template <int D, int C>
-__device__ __forceinline__ void mul_factor4(double (&A)[4][D + 1], const double (&x)[4], const double (&e)[4][C + 1]) {
+__device__ __forceinline__ void phase1_token(double (&K)[D], const TokRec<D>& r, double t, const double* tab) {
+    const double x = exp_neg(t * r.aw, tab);
+    const double v = fma(-x, x, x), s = fma(-2.0, x, 1.0);
+    K[0] = fma(x, r.e[0], K[0]);
+    if constexpr (C >= 2) {
+        double g[C - 1];
+        cum_g_from<1, C - 1>(v, s, g);
 #pragma unroll
-    for (int d = D; d >= 1; --d) {
-        double acc[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = e[j][1] * A[j][d - 1];
-#pragma unroll
-        for (int a = 2; a <= (d < C ? d : C); ++a)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = fma(e[j][a], A[j][d - a], acc[j]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) A[j][d] = fma(x[j], acc[j], A[j][d]);
+        for (int k = 2; k <= C; ++k) K[k - 1] = fma(v * g[k - 2], r.e[k - 1], K[k - 1]);
     }
 }
 
-// four quotients T_j / (1 + x_j (e^{zq} - 1)) of the same token (series e) at four nodes
+// Tokens first + tsub, first + tsub + NS, ... below `last` at this lane's node, two records in flight.
+template <int D, int C, int NS>
+__device__ __forceinline__ void phase1_range(double (&K)[D], const TokRec<D>* trec, int first, int last, int pad, int tsub,
+                                             double t, const double* tab) {
+    if (first >= last) return;
+    const int i0 = first + tsub;
+    TokRec<D> cur = trec[i0 < last ? i0 : pad];
+    for (int b = first; b < last; b += 2 * NS) {           // uniform trip count; the pad record has x = 0
+        const int i1 = b + tsub + NS, i2 = b + tsub + 2 * NS;
+        const TokRec<D> nxt = trec[i1 < last ? i1 : pad];
+        phase1_token<D, C>(K, cur, t, tab);
+        cur = trec[i2 < last ? i2 : pad];
+        phase1_token<D, C>(K, nxt, t, tab);
+    }
+}
+
+// Phase 3, one token at one node: (e^u - 1) / (1 + x (e^u - 1)) = sum_k g_k(x) u^k / k!, so the
+// leave-one-out coefficient is sum_{k <= C} g_k(x) (q^k / k!) T_{n-k}.
 template <int D, int C>
-__device__ __forceinline__ void loo_coeff4(const double (&T)[4][D + 1], const double (&x)[4], const double (&e)[D + 1],
-                                           int n, double (&cn)[4]) {
-    double Bq[4][D + 1];
+__device__ __forceinline__ void phase3_pair(const NodeRec<D>& c, const double (&e)[D], double wt, const double* tab,
+                                            double& acc, double& at) {
+    const double x = exp_neg(c.t * wt, tab);
+    const double v = fma(-x, x, x), s = fma(-2.0, x, 1.0);
+    double g[C];
+    cum_g_from<1, C>(v, s, g);
+    double cn = e[0] * c.Tr[0];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { Bq[j][0] = T[j][0]; cn[j] = 0.0; }
+    for (int k = 2; k <= C; ++k) cn = fma(e[k - 1] * g[k - 1], c.Tr[k - 1], cn);
+    const double term = c.qw * x * cn;
+    acc += term;
+    at = fma(term, c.t, at);
+}
+
+// Tokens [first, last) against the npw nodes of this wave: lane = (token slot, node subset), the split that
+// needs the fewest rounds; the sums go to this wave's rpart / spart.
+template <int D, int C, class LdsT>
+__device__ __forceinline__ void phase3_range(LdsT& L, int first, int last, int pad, int npw, int wv, int lane) {
+    constexpr int NPW = LdsT::kNPW;
+    const int cnt = last - first;
+    if (cnt <= 0 || npw <= 0) return;
+    // cost of a split in units of one (token, node) pair: per group of tokens the rounds over the node
+    // subsets, one unit for loading the token and storing its sums, one per level of the butterfly
+    int ts_log = 6, best = ((cnt + 63) >> 6) * (npw + 1);
 #pragma unroll
-    for (int d = 1; d <= D; ++d) {
-        double conv[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) conv[j] = e[1] * Bq[j][d - 1];
-#pragma unroll
-        for (int a = 2; a <= (d < C ? d : C); ++a)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) conv[j] = fma(e[a], Bq[j][d - a], conv[j]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { Bq[j][d] = fma(-x[j], conv[j], T[j][d]); if (d == n) cn[j] = conv[j]; }
+    for (int tl = 5; tl >= 3; --tl) {
+        const int nsub_ = 64 >> tl;
+        if (nsub_ > NPW) break;
+        const int c = ((cnt + (1 << tl) - 1) >> tl) * ((npw + nsub_ - 1) / nsub_ + 1 + (6 - tl));
+        if (c < best) { best = c; ts_log = tl; }
+    }
+    const int TS = 1 << ts_log, nsub = 64 >> ts_log;
+    const int tslot = lane & (TS - 1), ns = lane >> ts_log;
+    const int rounds = (npw + nsub - 1) / nsub;
+    for (int g0 = first; g0 < last; g0 += TS) {
+        const int tok = g0 + tslot;
+        const TokRec<D> tr = L.trec[tok < last ? tok : pad];
+        double acc = 0.0, at = 0.0;
+        NodeRec<D> cur = L.nrec[wv][ns];
+        for (int r = 0; r < rounds; r += 2) {
+            const int j1 = ns + (r + 1) * nsub, j2 = ns + (r + 2) * nsub;
+            const NodeRec<D> nxt = L.nrec[wv][j1 < NPW ? j1 : ns];
+            phase3_pair<D, C>(cur, tr.e, tr.aw, L.e2tab, acc, at);
+            cur = L.nrec[wv][j2 < NPW ? j2 : ns];
+            if (r + 1 < rounds) phase3_pair<D, C>(nxt, tr.e, tr.aw, L.e2tab, acc, at);
+        }
+        if (ts_log <= 5) { acc += __shfl_xor(acc, 32); at += __shfl_xor(at, 32); }
+        if (ts_log <= 4) { acc += __shfl_xor(acc, 16); at += __shfl_xor(at, 16); }
+        if (ts_log <= 3) { acc += __shfl_xor(acc, 8); at += __shfl_xor(at, 8); }
+        if (ns == 0 && tok < last) { L.rpart[wv][tok] += acc; L.spart[wv][tok] += at; }
     }
 }
 
-// Phase 1, tokens that keep their full factor: tokens i0, i0+4, i0+8, i0+12 (below `bound`) into the
-// four running products.
-template <int D>
-__device__ __forceinline__ void phase1_big(double (&A)[4][D + 1], const Lds<D>& L, int i0, int bound, double t) {
-    double y[4], x[4], e[4][D + 1];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int i = i0 + j * kSW;
-        const int ii = i < bound ? i : i0;
-        y[j] = i < bound ? t * L.aw[ii] : 1000.0;             // a missing token gets x = 0: its factor is 1
-#pragma unroll
-        for (int a = 1; a <= D; ++a) e[j][a] = L.etab[ii * (D + 1) + a];
-    }
-    exp_neg4(y, x, L.e2tab);
-    mul_factor4<D, D>(A, x, e);
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
-// Phase 1, light tokens: log(1 + x (e^u - 1)) = sum_k kappa_k(x) u^k / k!  with the cumulants of a
-// Bernoulli(x) variable, so the product of their factors is the exponential of four sums.
-// Tokens first, first + kSW, ... below m, four at a time (records beyond m contribute nothing); two
-// register sets alternate so that the LDS operands of the next four are requested before the
-// arithmetic of the current four.
-template <class LdsT>
-__device__ __forceinline__ void phase1_small_load(const LdsT& L, int i0, TokRec (&r)[4]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = L.trec[i0 + j * kSW];
-}
-__device__ __forceinline__ void phase1_small_quad(double (&K)[4][4], const TokRec (&r)[4], double t, const double* tab) {
-    double y[4], x[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) y[j] = t * r[j].aw;
-    exp_neg4(y, x, tab);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const double v = x[j] * (1.0 - x[j]);                  // kappa_2
-        const double k3 = v * fma(-2.0, x[j], 1.0);            // kappa_3 = v (1 - 2x)
-        const double k4 = v * fma(-6.0, v, 1.0);               // kappa_4 = v (1 - 6 v)
-        K[j][0] = fma(x[j], r[j].e[0], K[j][0]);
-        K[j][1] = fma(v, r[j].e[1], K[j][1]);
-        K[j][2] = fma(k3, r[j].e[2], K[j][2]);
-        K[j][3] = fma(k4, r[j].e[3], K[j][3]);
-    }
-}
-template <class LdsT>
-__device__ __forceinline__ void phase1_small(double (&K)[4][4], const LdsT& L, int first, int m, double t) {
-    if (first >= m) return;
-    TokRec a[4], b[4];
-    phase1_small_load(L, first, a);
-    for (int i0 = first; i0 < m; i0 += 8 * kSW) {
-        const bool more = i0 + 4 * kSW < m;
-        if (more) phase1_small_load(L, i0 + 4 * kSW, b);
-        phase1_small_quad(K, a, t, L.e2tab);
-        if (!more) break;
-        if (i0 + 8 * kSW < m) phase1_small_load(L, i0 + 8 * kSW, a);
-        phase1_small_quad(K, b, t, L.e2tab);
-    }
-}
-
-// Phase 3, a token with its full factor at the four nodes nu0 + j*stride (j = 0..3).
-template <int D>
-__device__ __forceinline__ double phase3_big(const Lds<D>& L, const double (&e)[D + 1], double wt, int n, int nu0,
-                                             int stride, int nn, double& acc_t) {
-    double T[4][D + 1], y[4], x[4], qq[4], cn[4], tt[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int nu = nu0 + j * stride;
-        const int nv = nu < nn ? nu : 0;
-        tt[j] = L.tnode[nv];
-        y[j] = tt[j] * wt;
-        qq[j] = nu < nn ? L.qwnode[nv] : 0.0;
-#pragma unroll
-        for (int d = 0; d <= D; ++d) T[j][d] = L.Tl[nv * (D + 1) + d];
-    }
-    exp_neg4(y, x, L.e2tab);
-    loo_coeff4<D, D>(T, x, e, n, cn);
-    double acc = 0.0, at = 0.0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const double term = qq[j] * x[j] * cn[j];
-        acc += term;
-        at = fma(term, tt[j], at);
-    }
-    acc_t = at;
-    return acc;
-}
-
-// Phase 3, a light token: (e^u - 1) / (1 + x (e^u - 1)) = u + (1/2 - x) u^2 + (1/6 - x + x^2) u^3 +
-// (1/24 - 7x/12 + 3x^2/2 - x^3) u^4 + ..., so the leave-one-out coefficient is a four-term sum over
-// T[n-1..n-4].  e[k] = q^k / k! (zero for k > n), so the brackets are multiplied by k!.
-// This wave's nodes wv, wv + kSW, ..., four at a time from the node records (uniform over the wave;
-// records at or beyond nn carry weight 0); two register sets alternate as in phase 1.
-template <class LdsT>
-__device__ __forceinline__ void phase3_small_load(const LdsT& L, int nu0, NodeRec (&r)[4]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r[j] = L.nrec[nu0 + j * kSW];
-}
-__device__ __forceinline__ void phase3_small_quad(const NodeRec (&c)[4], const double (&e)[5], double wt, const double* tab,
-                                                  double& acc, double& at) {
-    double y[4], x[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) y[j] = c[j].t * wt;
-    exp_neg4(y, x, tab);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const double xx = x[j];
-        const double g2 = fma(-2.0, xx, 1.0);
-        const double g3 = fma(6.0 * xx, xx - 1.0, 1.0);
-        const double g4 = fma(xx, fma(xx, fma(-24.0, xx, 36.0), -14.0), 1.0);
-        double cn = e[1] * c[j].T[0];
-        cn = fma(e[2] * g2, c[j].T[1], cn);
-        cn = fma(e[3] * g3, c[j].T[2], cn);
-        cn = fma(e[4] * g4, c[j].T[3], cn);
-        const double term = c[j].qw * xx * cn;
-        acc += term;
-        at = fma(term, c[j].t, at);
-    }
-}
-template <class LdsT>
-__device__ __forceinline__ double phase3_small(const LdsT& L, const double (&e)[5], double wt, int wv, int nn, double& acc_t) {
-    double acc = 0.0, at = 0.0;
-    acc_t = 0.0;
-    if (wv >= nn) return acc;
-    NodeRec a[4], b[4];
-    phase3_small_load(L, wv, a);
-    for (int nu0 = wv; nu0 < nn; nu0 += 8 * kSW) {
-        const bool more = nu0 + 4 * kSW < nn;
-        if (more) phase3_small_load(L, nu0 + 4 * kSW, b);
-        phase3_small_quad(a, e, wt, L.e2tab, acc, at);
-        if (!more) break;
-        if (nu0 + 8 * kSW < nn) phase3_small_load(L, nu0 + 8 * kSW, a);
-        phase3_small_quad(b, e, wt, L.e2tab, acc, at);
-    }
-    acc_t = at;
-    return acc;
+__device__ __forceinline__ Grid make_grid(int slack, double ctx, double wsum, double wmin, double step0) {
+    Grid g;
+    g.t_lo = kQuadLo * fast_rcp(slack + wsum);
+    const double lowest = slack + ((slack == 0 || ctx == 0.0) ? wmin : 0.0);
+    const double range = fast_log((kQuadHi / kQuadLo) * (slack + wsum) * fast_rcp(lowest));
+    g.step = step0;
+    int N = static_cast<int>(ceil(range / g.step)) + 1;
+    if (step0 == kQuadStep && N > 64 && range <= 0.5 * 63.0) { g.step = range / 63.0; N = 64; }
+    if (N < 1) N = 1;
+    if (N > 4096) N = 4096;
+    g.N = N;
+    const double estep = g.step == kQuadStep ? 1.5683121854901688 : exp(g.step);      // e^0.45
+    g.tail = g.step * g.t_lo * fast_rcp(estep - 1.0);
+    g.tail2 = g.step * g.t_lo * g.t_lo * fast_rcp(estep * estep - 1.0);
+    return g;
 }
 
 // Routed mass of every active token, and the mass left to the slack term.
 //
-// Tokens are held in decreasing q.  The first L.nbig of them ("heavy") keep their full factor
-// 1 + x (e^{zq} - 1); the others ("light": q so small that terms beyond u^4 cannot change the z^n
-// coefficient, or n <= 4 where four terms are exact) enter through four cumulant sums.
-// Per chunk of 64 quadrature nodes:
-//   phase 1  lanes = nodes; wave w takes tokens w, w+4, ...: heavy ones into four interleaved running
-//            products, light ones into the cumulant sums;
-//   phase 2  wave 0 forms T(node) = exp(z ctx + cumulant series) * product of the heavy products -> LDS;
-//   phase 3  lanes = tokens, wave w walks nodes w, w+4, ...: each lane takes the leave-one-out
-//            coefficient of its token (series division for heavy tokens, the four-term expansion for
-//            light ones) and accumulates; no cross-lane reduction for the light tokens, two shuffles
-//            for the heavy ones (16 tokens x 4 node groups per wave).
-// In: L.aq, L.aal, L.etab / L.nbig / L.apd (set up by solve_program), m, n, ctx, slack, qsum = sum aq.
-// Out: L.aR[0..m), L.R0acc (slack mass; meaningful when slack = 1).  All threads call it.
+// Tokens are held in decreasing q: first the (at most three, only with more than 8 drafts) heavy ones that keep
+// their exact factor, then up to L.nfull tokens with all D cumulants, then the tokens that need four.  A chunk
+// of up to 64 quadrature nodes is dealt to the waves (wave w owns nodes w, w + NW, ...), and a wave takes
+// its nodes through all three phases without a workgroup barrier:
+//   phase 1  lane = (node, token subset): the cumulant sums of its tokens at its node, then a butterfly over
+//            the subsets;
+//   phase 2  per node: T = exp(z ctx + cumulant series) (times the exact factors of the heavy tokens), the
+//            slack integrand, and the node record {t, weight, T_{n-1..n-D}} -> LDS;
+//   phase 3  lane = (token, node subset): the leave-one-out coefficient of its token at each of the wave's
+//            nodes; the waves' partial sums meet in LDS at the end.
+// In: L.trec[] (weights and series terms), L.apd / L.nheavy / L.nfull (set up by solve_program), the grid.
+// Out: every wave's partial sums in L.rpart / L.spart / L.r0part.  All waves call it behind a barrier that made
+// the weights visible; it contains no workgroup barrier itself.
 template <int D>
-__device__ __forceinline__ void routed_eval(Lds<D>& L, int m, int n, double ctx, int slack, double qsum) {
+__device__ __forceinline__ void eval_core(Lds<D>& L, const Grid& gr, int m, int n, double ctx, int slack) {
+    constexpr int kSW = Lds<D>::kSW, NPW = Lds<D>::kNPW, NS = 64 / NPW;
+    constexpr int CL = D < 4 ? D : 4;                          // cumulants of a light token
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int nbig = L.nbig;
-    GR_CLK(L, 12);
-    double w = 0.0;
-    if (tid < m) { w = exp(L.aal[tid]); L.aw[tid] = w; L.trec[tid].aw = w; }
-    if (tid < 16) { NodeRec z; z.t = 0.0; z.qw = 0.0; z.T[0] = z.T[1] = z.T[2] = z.T[3] = 0.0; L.nrec[64 + tid] = z; }
-    const double wsum = block_sum<kSW>(tid < m ? w : 0.0, L.red);
-    const double wmin = block_min<kSW>(tid < m ? w : 1e300, L.red);
-    const double t_lo = kQuadLo / (slack + wsum);
-    const double t_hi = kQuadHi / (slack + ((slack == 0 || ctx == 0.0) ? wmin : 0.0));
-    const double range = log(t_hi / t_lo);
-    double step = kQuadStep;
-    int N = static_cast<int>(ceil(range / step)) + 1;
-    if (N > 64 && range <= 0.5 * 63.0) { step = range / 63.0; N = 64; }
-    if (N < 1) N = 1;
-    if (N > 4096) N = 4096;
-    const double atot = ctx + qsum;
-    const double estep = exp(step);
-    const double tail = step * t_lo / (estep - 1.0);       // trapezoid sum of the nodes below t_lo, x = 1 there
-    const double tail2 = step * t_lo * t_lo / (estep * estep - 1.0);   // the same for the integrand times t
-    double fact = 1.0;
-    for (int i = 2; i <= n; ++i) fact *= i;
-    double r0 = 0.0;                                       // slack mass, accumulated by lane 0 of wave 0
-    double racc[2] = {0.0, 0.0};                           // phase 3 accumulators of light tokens lane, lane + 64
-    double sacc[2] = {0.0, 0.0};                           // the same, weighted by the node abscissa t
-    if (tid < m) { for (int w2 = 0; w2 < kSW; ++w2) { L.rpart[w2][tid] = 0.0; L.spart[w2][tid] = 0.0; } }
-    const int first_small = nbig + ((wv - nbig) % kSW + kSW) % kSW;   // first light token of this wave
-    // this lane's light tokens in phase 3: series terms q^k / k!, k <= min(n, 4)
-    double es[2][5]; double ws[2];
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int tok = pass * 64 + lane;
-        const int tk = tok < m ? tok : 0;
-        ws[pass] = m > 0 ? L.aw[tk] : 0.0;
-#pragma unroll
-        for (int a = 1; a <= 4; ++a) es[pass][a] = (a <= n && a <= D && m > 0) ? L.etab[tk * (D + 1) + (a <= D ? a : 0)] : 0.0;
-        es[pass][0] = 0.0;
-    }
-    __syncthreads();
+    const int nheavy = (D > 8) ? L.nheavy : 0;
+    const int nfull = (D > 4) ? L.nfull : nheavy;              // up to four drafts four cumulants are all there are
+    const double t_lo = gr.t_lo, step = gr.step;
+    const int N = gr.N;
+    for (int i = lane; i < m; i += 64) { L.rpart[wv][i] = 0.0; L.spart[wv][i] = 0.0; }
+    double r0 = 0.0;                                       // slack integrand, lanes of token subset 0
+    double hacc[kMaxHeavy] = {0.0, 0.0, 0.0}, hacct[kMaxHeavy] = {0.0, 0.0, 0.0};
+    const int j = lane & (NPW - 1), tsub = lane / NPW;
     GR_CLK(L, 6);
 
     for (int c0 = 0; c0 < N; c0 += 64) {
-        const int node = c0 + lane;
-        const double t = t_lo * exp(step * node);
-        const double qw = node < N ? step * t * exp_neg(slack * t) : 0.0;
-        if (wv == 0) { L.tnode[lane] = t; L.qwnode[lane] = qw; }
-        // ---- phase 1
-        if (nbig > 0) {
-            double A[4][D + 1];
+        const int nn = min(64, N - c0);
+        const int npw = (nn - wv + kSW - 1) / kSW;          // nodes of this wave in the chunk: c0 + wv + kSW j
+        const double t = t_lo * exp(step * static_cast<double>(c0 + wv + kSW * j));
+        const double qw = j < npw ? step * t * exp_neg(slack * t, L.e2tab) : 0.0;
+        // ---- phase 1: cumulant sums at node j of the tokens of subset tsub
+        double K[D];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int d = 0; d <= D; ++d) A[j][d] = d == 0;
-            for (int i0 = wv; i0 < nbig; i0 += 4 * kSW) phase1_big<D>(A, L, i0, nbig, t);
-            mul_series<D>(A[0], A[1]); mul_series<D>(A[2], A[3]); mul_series<D>(A[0], A[2]);
-#pragma unroll
-            for (int d = 0; d <= D; ++d) L.u.part[(wv * (D + 1) + d) * 64 + lane] = A[0][d];
+        for (int k = 0; k < D; ++k) K[k] = 0.0;
+        if (npw > 0) {
+            if constexpr (D > 4) phase1_range<D, D, NS>(K, L.trec, nheavy, nfull, m, tsub, t, L.e2tab);
+            phase1_range<D, CL, NS>(K, L.trec, nfull, m, m, tsub, t, L.e2tab);
         }
-        {
-            double K[4][4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) K[j][k] = 0.0;
-            phase1_small(K, L, first_small, m, t);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) L.cum[(wv * 4 + k) * 64 + lane] = (K[0][k] + K[1][k]) + (K[2][k] + K[3][k]);
+        for (int k = 0; k < D; ++k) {
+            if (NS >= 8) K[k] += __shfl_xor(K[k], 8);
+            K[k] += __shfl_xor(K[k], 16);
+            K[k] += __shfl_xor(K[k], 32);
         }
-        __syncthreads();
         GR_CLK(L, 7);
-        // ---- phase 2 (wave 0)
-        if (wv == 0) {
-            double Kt[4];
+        // ---- phase 2: the node's series T = exp(z ctx + sum_k K_k z^k), every lane of the node alike
+        K[0] += ctx;
+        double T[D + 1];
+        T[0] = 1.0;
+        {
+            double kK[D];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                Kt[k] = 0.0;
-                for (int w2 = 0; w2 < kSW; ++w2) Kt[k] += L.cum[(w2 * 4 + k) * 64 + lane];
-            }
-            Kt[0] += ctx;                                  // e^{z ctx}
-            // T = exp(Kt_1 z + ... + Kt_4 z^4):  d T_d = sum_k k Kt_k T_{d-k}
-            double T[D + 1];
-            T[0] = 1.0;
+            for (int k = 1; k <= D; ++k) kK[k - 1] = static_cast<double>(k) * K[k - 1];
 #pragma unroll
             for (int d = 1; d <= D; ++d) {
-                double acc = Kt[0] * T[d - 1];
+                double acc = kK[0] * T[d - 1];
 #pragma unroll
-                for (int k = 2; k <= (d < 4 ? d : 4); ++k) acc = fma(static_cast<double>(k) * Kt[k - 1], T[d - k], acc);
+                for (int k = 2; k <= d; ++k) acc = fma(kK[k - 1], T[d - k], acc);
                 T[d] = acc * (1.0 / d);
             }
-            if (nbig > 0) {
-                for (int w2 = 0; w2 < kSW; ++w2) {
-                    double Bc[D + 1];
-#pragma unroll
-                    for (int d = 0; d <= D; ++d) Bc[d] = L.u.part[(w2 * (D + 1) + d) * 64 + lane];
-                    mul_series<D>(T, Bc);
-                }
-            }
-            double tn = 0.0;
-            NodeRec rec; rec.t = t; rec.qw = qw; rec.T[0] = rec.T[1] = rec.T[2] = rec.T[3] = 0.0;
-#pragma unroll
-            for (int d = 0; d <= D; ++d) {
-                L.Tl[lane * (D + 1) + d] = T[d];
-                if (d == n) tn = T[d];
-                if (d == n - 1) rec.T[0] = T[d];
-                if (d == n - 2) rec.T[1] = T[d];
-                if (d == n - 3) rec.T[2] = T[d];
-                if (d == n - 4) rec.T[3] = T[d];
-            }
-            L.nrec[lane] = rec;
-            r0 += wave_sum(qw * tn);
         }
-        __syncthreads();
+        if constexpr (D > 8) {
+            // the heavy tokens' exact factors, then each one's leave-one-out coefficient by series division
+            double xh[kMaxHeavy];
+            for (int hv = 0; hv < nheavy; ++hv) {
+                double e[D];
+#pragma unroll
+                for (int a = 0; a < D; ++a) e[a] = L.trec[hv].e[a];
+                xh[hv] = exp_neg(t * L.trec[hv].aw, L.e2tab);
+                mul_factor<D>(T, xh[hv], e);
+            }
+            for (int hv = 0; hv < nheavy; ++hv) {
+                double e[D];
+#pragma unroll
+                for (int a = 0; a < D; ++a) e[a] = L.trec[hv].e[a];
+                const double term = (tsub == 0 ? qw : 0.0) * xh[hv] * loo_coeff<D>(T, xh[hv], e, n);
+                hacc[hv] += term;
+                hacct[hv] = fma(term, t, hacct[hv]);
+            }
+        }
+        {
+            NodeRec<D> rec;
+            rec.t = t; rec.qw = qw;
+            const double tn = pick_series<D, D>(rec, T, n);
+            if (tsub == 0) { r0 = fma(qw, tn, r0); L.nrec[wv][j] = rec; }
+        }
+        wave_lds_sync();
         GR_CLK(L, 8);
         // ---- phase 3
-        const int nn = min(64, N - c0);
-        // heavy tokens: 16 per round, lane = (token, node group); this wave's nodes are wv, wv+4, ...,
-        // node group g takes every fourth of them
-        for (int b0 = 0; b0 < nbig; b0 += 16) {
-            const int tok = b0 + (lane & 15);
-            const int tk = tok < nbig ? tok : 0;
-            double e[D + 1];
-#pragma unroll
-            for (int a = 0; a <= D; ++a) e[a] = L.etab[tk * (D + 1) + a];
-            double acct;
-            double acc = phase3_big<D>(L, e, L.aw[tk], n, wv + kSW * (lane >> 4), 4 * kSW, nn, acct);
-            acc += __shfl_xor(acc, 16); acct += __shfl_xor(acct, 16);
-            acc += __shfl_xor(acc, 32); acct += __shfl_xor(acct, 32);
-            if (lane < 16 && tok < nbig) { L.rpart[wv][tok] += acc; L.spart[wv][tok] += acct; }
-        }
-        // light tokens
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            if (pass * 64 < m && (pass + 1) * 64 > nbig) {
-                double at;
-                racc[pass] += phase3_small(L, es[pass], ws[pass], wv, nn, at);
-                sacc[pass] += at;
-            }
-        }
-        __syncthreads();                                   // part / cum / Tl / tnode are rewritten by the next chunk
+        if constexpr (D > 4) phase3_range<D, D>(L, nheavy, nfull, m, npw, wv, lane);
+        phase3_range<D, CL>(L, nfull, m, m, npw, wv, lane);
+        wave_lds_sync();                                   // this wave's node records are rewritten by its next chunk
         GR_CLK(L, 9);
     }
-    if (lane < m && lane >= nbig) { L.rpart[wv][lane] = racc[0]; L.spart[wv][lane] = sacc[0]; }
-    if (64 + lane < m && 64 + lane >= nbig) { L.rpart[wv][64 + lane] = racc[1]; L.spart[wv][64 + lane] = sacc[1]; }
-    if (tid == 0) { L.R0acc = (r0 + ipow(atot, n) * tail / fact) * fact * slack; L.work += static_cast<double>(N) * m; }
-    __syncthreads();
-    if (tid < m) {
-        double r = L.apd[tid] * tail / fact;
-        // the nodes below t_lo (x = 1 there) add tail to the integral of 1 and tail2 to that of t
-        double sq = L.apd[tid] * tail2 / fact;
-        for (int w2 = 0; w2 < kSW; ++w2) { r += L.rpart[w2][tid]; sq += L.spart[w2][tid]; }
-        L.aR[tid] = r * L.aw[tid] * fact;
-        L.aS[tid] = sq * L.aw[tid] * L.aw[tid] * fact;
+    if constexpr (D > 8) {
+        for (int hv = 0; hv < nheavy; ++hv) {
+            const double a = wave_sum(hacc[hv]), b = wave_sum(hacct[hv]);
+            if (lane == 0) { L.rpart[wv][hv] = a; L.spart[wv][hv] = b; }
+        }
     }
+    {
+        const double r0w = wave_sum(r0);
+        if (lane == 0) L.r0part[wv] = r0w;
+    }
+    if (tid == 0) L.work += static_cast<double>(N) * m;
+}
+
+// The routed mass R and its t-weighted companion S of token `tok` from the waves' partial sums (behind the
+// barrier that follows eval_core), and the slack mass.
+template <int D>
+__device__ __forceinline__ void token_sums(const Lds<D>& L, const Grid& gr, int tok, double fact, double& R, double& S) {
+    constexpr int kSW = Lds<D>::kSW;
+    const double rfact = fast_rcp(fact);
+    double r = L.apd[tok] * gr.tail * rfact, sq = L.apd[tok] * gr.tail2 * rfact;
+#pragma unroll
+    for (int w2 = 0; w2 < kSW; ++w2) { r += L.rpart[w2][tok]; sq += L.spart[w2][tok]; }
+    const double w = L.trec[tok].aw;
+    R = r * w * fact;
+    S = sq * w * w * fact;
+}
+template <int D>
+__device__ __forceinline__ double slack_mass(const Lds<D>& L, const Grid& gr, int n, double atot, double fact, int slack) {
+    constexpr int kSW = Lds<D>::kSW;
+    double r0all = 0.0;
+#pragma unroll
+    for (int w2 = 0; w2 < kSW; ++w2) r0all += L.r0part[w2];
+    return (r0all * fact + ipow(atot, n) * gr.tail) * slack;
+}
+
+// Workgroup-wide evaluation (the Newton fallback's): every thread passes the log weight of its own token and gets
+// that token's routed mass back (also left in L.aR); returns the slack mass.  All threads call it.
+struct Routed { double R0, R, S; };
+template <int D>
+__device__ __forceinline__ Routed routed_eval(Lds<D>& L, int& par, int m, int n, double ctx, int slack, double qsum, double fact, double alpha) {
+    const int tid = threadIdx.x;
+    double w = 0.0;
+    if (tid < m) { w = exp(alpha); L.trec[tid].aw = w; }
+    double a[2] = {wave_sum(tid < m ? w : 0.0), wave_min(tid < m ? w : 1e300)};
+    wg_reduce<2>(L, par, a, {kOpSum, kOpMin});              // its barrier also publishes the weights
+    const Grid gr = make_grid(slack, ctx, a[0], a[1], kQuadStep);
+    eval_core<D>(L, gr, m, n, ctx, slack);
     __syncthreads();
+    Routed out;
+    out.R = 0.0; out.S = 0.0;
+    if (tid < m) { token_sums<D>(L, gr, tid, fact, out.R, out.S); L.aR[tid] = out.R; }
+    out.R0 = slack_mass<D>(L, gr, n, ctx + qsum, fact, slack);
     GR_CLK(L, 10);
-#ifdef GR_PHASE_CLOCKS
-    if (tid == 0) L.clk[15] += 1;
-#endif
+    return out;
 }
 
 // One evaluation and the stopping measure: max_i | log(target_i / routed_i) - common term |, where the
 // common term is log(slack_target / slack mass) with slack, log(sum target / sum routed) without
-// (the latter is zero in exact arithmetic and removes the common quadrature error).  f -> L.af;
-// L.aR and L.aS stay valid until the next evaluation.
+// (the latter is zero in exact arithmetic and removes the common quadrature error).  Per-token quantities are
+// those of the calling thread's token: alpha and target in, f = log(target / routed) - common term, R and S out.
+struct Defect { double err, f, R, S, rsum, R0; };
 template <int D>
-__device__ double defect_eval(Lds<D>& L, int m, int n, double ctx, int slack, double slack_target, double qsum,
-                              double tsum, double* rsum_out) {
+__device__ __forceinline__ Defect defect_eval(Lds<D>& L, int& par, int m, int n, double ctx, int slack, double slack_target, double qsum,
+                                              double tsum, double fact, double alpha, double target) {
     const int tid = threadIdx.x;
-    routed_eval<D>(L, m, n, ctx, slack, qsum);
-    // the sum of the routed masses is needed without slack (common term) and by the Newton iteration
-    const double rsum = (!slack || rsum_out) ? block_sum<kSW>(tid < m ? L.aR[tid] : 0.0, L.red) : 0.0;
-    double f = 0.0;
-    if (tid < m) {
-        const double common = slack ? L.R0acc / slack_target : rsum / tsum;
-        f = log(L.at[tid] / L.aR[tid] * common);
-        L.af[tid] = f;
+    Defect d;
+    {
+        const Routed r = routed_eval<D>(L, par, m, n, ctx, slack, qsum, fact, alpha);
+        d.R0 = r.R0; d.R = r.R; d.S = r.S;
     }
-    if (rsum_out) *rsum_out = rsum;
-    const double worst = block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
+    double g = 0.0;
+    if (tid < m) { g = fast_log(target / d.R); if (!(g == g)) g = 1e301; }
+    double a[3] = {wave_sum(tid < m ? d.R : 0.0), wave_max(tid < m ? g : -1e300), wave_min(tid < m ? g : 1e300)};
+    wg_reduce<3>(L, par, a, {kOpSum, kOpMax, kOpMin});
+    d.rsum = a[0];
+    const double gmax = a[1], gmin = a[2];
+    const double lc = fast_log(slack ? d.R0 / slack_target : d.rsum / tsum);
+    d.f = tid < m ? g + lc : 0.0;
+    double worst = fmax(fabs(gmax + lc), fabs(gmin + lc));
+    if (!(worst == worst)) worst = 1e301;                  // NaN: treated as "no finite point"
+    if (!(gmax < 1e300) || !(gmin > -1e300)) worst = 1e301;
+    d.err = worst;
     GR_CLK(L, 11);
-    return worst;
+    return d;
 }
 
 // Damped Newton iteration on routed(alpha) = target with a finite-difference Jacobian (the Hessian of
@@ -579,27 +607,30 @@ __device__ double defect_eval(Lds<D>& L, int m, int n, double ctx, int slack, do
 // it only takes over when the mixed iteration has used up its budget.  Without slack the last weight
 // is pinned (the system is singular along the common shift).  Starts from L.aal.
 // J: this row's scratch in HBM, kMaxT rows of kMaxT + 1 doubles (the last column is the right-hand side).
+// The cap counts the evaluations of this program only (`evals0` = the row's count when the program began).
 template <int D>
-__device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, int slack, double slack_target, double qsum,
-                              double tsum, double rel_tol, int max_evals, int* evals) {
-    const int tid = threadIdx.x, lane = tid & 63;
+__device__ int newton_program(Lds<D>& L, int& par, double* J, int m, int n, double ctx, int slack, double slack_target, double qsum,
+                              double tsum, double fact, double rel_tol, int max_evals, int* evals, int evals0) {
+    constexpr int kSW = Lds<D>::kSW;
+    const int tid = threadIdx.x;
     const int nfree = slack ? m : m - 1;
     constexpr int LD = kMaxT + 1;
     constexpr double kFd = 1e-6;
-    double rsum;
-    double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+    const double target = tid < m ? L.at[tid] : 0.0;
+    Defect dd = defect_eval<D>(L, par, m, n, ctx, slack, slack_target, qsum, tsum, fact, tid < m ? L.aal[tid] : 0.0, target);
+    double err = dd.err, rsum = dd.rsum, R0 = dd.R0, f = dd.f;
     *evals += 1;
-    while (err > rel_tol && *evals < max_evals && err < 1e300) {
-        if (tid < m) L.nR[tid] = L.aR[tid];
+    while (err > rel_tol && *evals - evals0 < max_evals && err < 1e300) {
+        if (tid < m) { L.nR[tid] = L.aR[tid]; L.af[tid] = f; }
         // common ratio routed/target over all vertices, the slack vertex included: Newton aims at
         // routed_j = ratio * target_j, which is what the stopping measure asks for
-        const double ratio = slack ? (rsum + L.R0acc) / (tsum + slack_target) : rsum / tsum;
+        const double ratio = slack ? (rsum + R0) / (tsum + slack_target) : rsum / tsum;
         __syncthreads();
         for (int k = 0; k < nfree; ++k) {
             if (tid == k) L.aal[k] += kFd;
             __syncthreads();
-            routed_eval<D>(L, m, n, ctx, slack, qsum);
-            if (tid < nfree) J[tid * LD + k] = (L.aR[tid] - L.nR[tid]) / kFd;
+            const Routed rk = routed_eval<D>(L, par, m, n, ctx, slack, qsum, fact, tid < m ? L.aal[tid] : 0.0);
+            if (tid < nfree) J[tid * LD + k] = (rk.R - L.nR[tid]) / kFd;
             if (tid == k) L.aal[k] -= kFd;
             __syncthreads();
         }
@@ -609,13 +640,13 @@ __device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, in
         // Gauss-Jordan with partial pivoting: thread r owns row r
         for (int c = 0; c < nfree; ++c) {
             const double mag = (tid < nfree && !L.nused[tid]) ? fabs(J[tid * LD + c]) : -1.0;
-            const double best = block_max<kSW>(mag, L.red);
+            const double best = block_max<kSW>(mag, L.redn);
             if (!(best > 0.0)) continue;                   // no pivot left in this column: its step stays 0
-            const int who = static_cast<int>(block_min<kSW>(mag == best ? static_cast<double>(tid) : 1e9, L.red));
+            const int who = static_cast<int>(block_min<kSW>(mag == best ? static_cast<double>(tid) : 1e9, L.redn));
             const double piv = J[who * LD + c];
             if (tid < nfree && tid != who) {
                 const double fct = J[tid * LD + c] / piv;
-                for (int j = c; j < nfree; ++j) J[tid * LD + j] -= fct * J[who * LD + j];
+                for (int jc = c; jc < nfree; ++jc) J[tid * LD + jc] -= fct * J[who * LD + jc];
                 J[tid * LD + kMaxT] -= fct * J[who * LD + kMaxT];
             }
             if (tid == who) { L.nused[tid] = 1; L.ncolof[tid] = c; }
@@ -627,17 +658,17 @@ __device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, in
             L.nstep[my_col] = dg != 0.0 ? J[tid * LD + kMaxT] / dg : 0.0;
         }
         __syncthreads();
-        const double smax = block_max<kSW>(tid < nfree ? fabs(L.nstep[tid]) : 0.0, L.red);
+        const double smax = block_max<kSW>(tid < nfree ? fabs(L.nstep[tid]) : 0.0, L.redn);
         if (!(smax < 1e300)) break;
         const double clip = smax > 2.0 ? 2.0 / smax : 1.0;
         // slope of the objective along the step: grad . d with grad_j = routed_j - ratio * target_j
-        double slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * clip * L.nstep[tid] : 0.0, L.red);
+        double slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * clip * L.nstep[tid] : 0.0, L.redn);
         if (!(slope0 < 0.0)) {
             // not a descent direction (noise in the difference quotients): take the plain
             // fixed-point step instead, which always is one
             if (tid < nfree) L.nstep[tid] = L.af[tid] / clip;
             __syncthreads();
-            slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * L.af[tid] : 0.0, L.red);
+            slope0 = block_sum<kSW>(tid < nfree ? (L.nR[tid] - L.at[tid] * ratio) * L.af[tid] : 0.0, L.redn);
         }
         if (tid < m) L.nsave[tid] = L.aal[tid];
         __syncthreads();
@@ -648,10 +679,11 @@ __device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, in
         for (int ls = 0; ls < 20 && !ok; ++ls) {
             if (tid < nfree) L.aal[tid] = L.nsave[tid] + lam * clip * L.nstep[tid];
             __syncthreads();
-            err2 = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, &rsum);
+            dd = defect_eval<D>(L, par, m, n, ctx, slack, slack_target, qsum, tsum, fact, tid < m ? L.aal[tid] : 0.0, target);
+            err2 = dd.err; rsum = dd.rsum; R0 = dd.R0; f = dd.f;
             *evals += 1;
-            const double ratio2 = slack ? (rsum + L.R0acc) / (tsum + slack_target) : rsum / tsum;
-            const double slope = block_sum<kSW>(tid < nfree ? (L.aR[tid] - L.at[tid] * ratio2) * clip * L.nstep[tid] : 0.0, L.red);
+            const double ratio2 = slack ? (rsum + R0) / (tsum + slack_target) : rsum / tsum;
+            const double slope = block_sum<kSW>(tid < nfree ? (L.aR[tid] - L.at[tid] * ratio2) * clip * L.nstep[tid] : 0.0, L.redn);
             ok = (err2 < 1e300) && (slope <= 0.5 * fabs(slope0) || err2 < err);
             if (!ok) lam *= 0.5;
         }
@@ -666,13 +698,214 @@ __device__ int newton_program(Lds<D>& L, double* J, int m, int n, double ctx, in
     return err <= rel_tol ? 0 : 1;
 }
 
-// Solve one program by iterative scaling with Anderson mixing.  Returns 0 when converged.
-// In: L.aq, L.at (targets, already scaled to the tuple mass), L.aal (start log weights).
-// Out: L.aal.  `evals` counts evaluator calls.
+// The mixing step of one iteration, by wave 0 alone behind the barrier that follows the evaluation.  Compiled as a
+// function of its own (not inlined) so that its values do not compete for registers with the evaluator's series.
+// The uniform solver state travels in MixState; per-token values live in LDS (see solve_program).
+struct MixState { int hcount, plain, since; double best_err, cap; };
 template <int D>
-__device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m, int n, double ctx, int slack, double slack_target,
-                             double rel_tol, int max_iter, int* evals) {
+__device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int it, int m, int n, int slack, double ctx, double slack_target,
+                                                      double tsum, double atot, double fact, double rel_tol, int evals) {
+    Lds<D>& L = *reinterpret_cast<Lds<D>*>(gr_lds_raw);
+    const int tid = threadIdx.x, lane = tid & 63;
+    int hcount = st.hcount, plain = st.plain, since = st.since;
+    double best_err = st.best_err, cap = st.cap;
+    const int tk[2] = {lane, lane + 64};
+    const bool on[2] = {tk[0] < m, tk[1] < m};
+    double R[2] = {0.0, 0.0}, S[2] = {0.0, 0.0}, g[2] = {0.0, 0.0}, al[2] = {0.0, 0.0};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) if (on[u]) {
+        token_sums<D>(L, gr, tk[u], fact, R[u], S[u]);
+        g[u] = fast_log(L.at[tk[u]] * fast_rcp(R[u]));
+        if (!(g[u] == g[u])) g[u] = 1e301;
+        al[u] = L.aal[tk[u]];
+    }
+    const double R0 = slack_mass<D>(L, gr, n, atot, fact, slack);
+    // stopping measure: max_i | log(target_i / routed_i) - common term |, the common term log(slack_target / slack
+    // mass) with slack, log(sum target / sum routed) without (zero in exact arithmetic: it removes the common
+    // quadrature error)
+    double rd[3] = {(on[0] ? R[0] : 0.0) + (on[1] ? R[1] : 0.0), fmax(on[0] ? g[0] : -1e300, on[1] ? g[1] : -1e300),
+                    fmin(on[0] ? g[0] : 1e300, on[1] ? g[1] : 1e300)};
+    wave_reduce_many<3>(rd, {kOpSum, kOpMax, kOpMin});
+    const double lc = fast_log(slack ? R0 * fast_rcp(slack_target) : rd[0] * fast_rcp(tsum));
+    double err = fmax(fabs(rd[1] + lc), fabs(rd[2] + lc));
+    if (!(err == err) || !(rd[1] < 1e300) || !(rd[2] > -1e300)) err = 1e301;      // NaN or infinite: "no finite point"
+#ifdef GR_PHASE_CLOCKS
+    if (tid == 0 && evals <= 24) L.errlog[evals - 1] = err;
+#endif
+    GR_CLK(L, 11);
+    // The fixed-point step log(target / routed) treats the routed mass as proportional to the
+    // weight; its true logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a
+    // token loses to itself), so the step of each coordinate is stretched by R / (R - S), at most
+    // `cap`.  The stretched iteration is no longer monotone: when kStall iterations bring no
+    // better point it returns to the best one with half the cap; at cap 1 (the plain step, whose
+    // stopping measure need not fall at every step) it is left alone.
+    double f[2], ratio[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        f[u] = on[u] ? g[u] + lc : 0.0;
+        const double d = R[u] - S[u];
+        ratio[u] = (on[u] && d > 0.0) ? fmin(R[u] * fast_rcp(d), 1e30) : (on[u] ? 1e30 : 1.0);
+    }
+    bool stop = false;
+    if (err <= rel_tol) {
+        if (lane == 0) L.ctl_result = 0;
+        stop = true;
+    } else if (!(err < 1e300) || err > 100.0 * best_err) {
+        // a mixed step went astray: back to the best point, unmixed steps for a while
+        if (!(best_err < 1e300)) stop = true;          // no finite point seen: give up on this program
+#pragma unroll
+        for (int u = 0; u < 2; ++u) if (on[u]) { al[u] = L.aBest[tk[u]]; f[u] = L.fBest[tk[u]]; ratio[u] = L.rBest[tk[u]]; }
+        hcount = 0; plain = 20; since = 0;
+    } else if (err < best_err) {
+        best_err = err; since = 0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) if (on[u]) { L.aBest[tk[u]] = al[u]; L.fBest[tk[u]] = f[u]; L.rBest[tk[u]] = ratio[u]; }
+    } else if (cap > 1.0 && ++since >= kStall) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) if (on[u]) { al[u] = L.aBest[tk[u]]; f[u] = L.fBest[tk[u]]; ratio[u] = L.rBest[tk[u]]; }
+        hcount = 0; since = 0;
+        cap = fmax(1.0, 0.5 * cap);
+    }
+    if (stop) {
+        if (lane == 0) { L.ctl_go = 0; L.ctl_bestok = best_err < 1e300 ? 1 : 0; }
+        return st;
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) f[u] *= fmin(ratio[u], cap);
+    GR_CLK(L, 16);
+    const int cur = it % kHist;
+    const int navail = min(hcount, kCols);             // stored vectors since the history was last dropped
+    const int ncol = plain > 0 ? 0 : navail;
+    if (plain > 0) --plain;
+    // inner products of the new residual vector with itself and the stored ones, and the longest plain step
+    double hf[kCols][2], ha[kCols][2];
+    double ex[kHist + 1];
+    ex[0] = f[0] * f[0] + f[1] * f[1];
+    ex[kHist] = fmax(fabs(f[0]), fabs(f[1]));
+#pragma unroll
+    for (int c = 0; c < kCols; ++c) {
+        const int slot = (cur - 1 - c + 2 * kHist) % kHist;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            hf[c][u] = (on[u] && c < navail) ? L.Hf[slot][tk[u]] : 0.0;
+            ha[c][u] = (on[u] && c < navail) ? L.Ha[slot][tk[u]] : 0.0;
+        }
+        ex[1 + c] = f[0] * hf[c][0] + f[1] * hf[c][1];
+    }
+    wave_reduce_many<kHist + 1>(ex, {kOpSum, kOpSum, kOpSum, kOpSum, kOpSum, kOpMax});
+    GR_CLK(L, 17);
+    double stepv[2] = {f[0], f[1]};
+    if (ncol >= 1) {
+        // normal equations of  min || f - dF gamma ||  with dF_c = f - f_c:  <dF_a, dF_b> and <dF_a, f> from the
+        // inner products (the new vector's are in ex, the older ones in L.pm: lane 4a + b fetches entry (a, b));
+        // Gaussian elimination without pivoting (symmetric positive definite after the ridge), in registers
+        double old;
+        {
+            const int la = (lane >> 2) & 3, lb = lane & 3;
+            old = L.pm[(cur - 1 - la + 2 * kHist) % kHist][(cur - 1 - lb + 2 * kHist) % kHist];
+        }
+        double Gm[kCols][kCols + 1];
+#pragma unroll
+        for (int a2 = 0; a2 < kCols; ++a2) {
+#pragma unroll
+            for (int b2 = 0; b2 < kCols; ++b2) Gm[a2][b2] = (ex[0] - ex[1 + a2]) - (ex[1 + b2] - read_lane(old, 4 * a2 + b2));
+            Gm[a2][kCols] = ex[0] - ex[1 + a2];
+        }
+        bool good = true;
+        double pivinv[kCols];
+#pragma unroll
+        for (int c = 0; c < kCols; ++c) pivinv[c] = 0.0;
+#pragma unroll
+        for (int c = 0; c < kCols; ++c) {
+            if (c < ncol) {
+                // a ridge relative to the column itself: recent columns are far shorter than old ones
+                Gm[c][c] = Gm[c][c] * (1.0 + 1e-10) + 1e-300;
+                good = good && (Gm[c][c] > 0.0);
+                double inv = __builtin_amdgcn_rcp(Gm[c][c]);          // reciprocal: two Newton steps from the hardware estimate
+                inv = inv * fma(-Gm[c][c], inv, 2.0);
+                inv = inv * fma(-Gm[c][c], inv, 2.0);
+                pivinv[c] = inv;
+#pragma unroll
+                for (int r = c + 1; r < kCols; ++r) {
+                    if (r < ncol) {
+                        const double fct = Gm[r][c] * inv;
+#pragma unroll
+                        for (int jc = c + 1; jc <= kCols; ++jc) Gm[r][jc] = fma(-fct, Gm[c][jc], Gm[r][jc]);
+                    }
+                }
+            }
+        }
+        double gam[kCols];
+#pragma unroll
+        for (int c = kCols - 1; c >= 0; --c) {
+            double sacc = Gm[c][kCols];
+#pragma unroll
+            for (int jc = c + 1; jc < kCols; ++jc) if (jc < ncol) sacc = fma(-Gm[c][jc], gam[jc], sacc);
+            gam[c] = (c < ncol) ? sacc * pivinv[c] : 0.0;
+        }
+        double gnorm = 0.0;
+#pragma unroll
+        for (int c = 0; c < kCols; ++c) gnorm += fabs(gam[c]);
+        const bool solved = good && gnorm < 1e300;
+        double cand[2] = {f[0], f[1]};
+#pragma unroll
+        for (int c = 0; c < kCols; ++c)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) if (c < ncol) cand[u] -= ((al[u] - ha[c][u]) + (f[u] - hf[c][u])) * gam[c];
+        const double cmax = wave_max(fmax(on[0] ? fabs(cand[0]) : 0.0, on[1] ? fabs(cand[1]) : 0.0));
+        // a mixed step longer than 3 in log weight is cut to that length (the same cap as the
+        // Newton fallback); a failed solve drops the history
+        if (solved && cmax < 1e300) {
+            const double cut = cmax > 3.0 ? 3.0 * fast_rcp(cmax) : 1.0;
+            stepv[0] = cand[0] * cut; stepv[1] = cand[1] * cut;
+        } else hcount = 0;
+    } else {                                           // a plain step: the same cap on its length
+        const double fmx = ex[kHist];
+        if (fmx > 3.0) { const double cut = 3.0 * fast_rcp(fmx); stepv[0] = f[0] * cut; stepv[1] = f[1] * cut; }
+    }
+    GR_CLK(L, 20);
+    // the new vector takes slot `cur` of the history (its inner products are read again next iteration)
+    if (lane <= kCols) {
+        const int slot = lane == 0 ? cur : (cur - lane + 2 * kHist) % kHist;
+        double val = ex[0];                             // ex[lane] without indexing registers by a variable
+#pragma unroll
+        for (int c = 1; c <= kCols; ++c) if (lane == c) val = c - 1 < navail ? ex[c] : 0.0;
+        L.pm[cur][slot] = val; L.pm[slot][cur] = val;
+    }
+    double ws = 0.0, wm = 1e300, amax = -1e300;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) if (on[u]) {
+        L.Ha[cur][tk[u]] = al[u]; L.Hf[cur][tk[u]] = f[u];
+        al[u] += stepv[u];
+        amax = fmax(amax, al[u]);
+    }
+    if (!slack) amax = wave_max(amax); else amax = 0.0;   // without slack only differences of log weights matter
+#pragma unroll
+    for (int u = 0; u < 2; ++u) if (on[u]) {
+        al[u] -= amax;
+        const double w = exp_signed(al[u], L.e2tab);
+        L.aal[tk[u]] = al[u]; L.trec[tk[u]].aw = w; ws += w; wm = fmin(wm, w);
+    }
+    ws = wave_sum(ws); wm = wave_min(wm);
+    if (lane == 0) {
+        L.ctl_grid = make_grid(slack, ctx, ws, wm, kQuadStep); L.ctl_bestok = best_err < 1e300 ? 1 : 0;
+    }
+    ++hcount;
+    st.hcount = hcount; st.plain = plain; st.since = since; st.best_err = best_err; st.cap = cap;
+    GR_CLK(L, 12);
+    return st;
+}
+
+// Solve one program by iterative scaling with Anderson mixing.  Returns 0 when converged.
+// In: L.aq, L.at (targets, already scaled to the tuple mass), L.aal (start log weights), each written by the
+// thread of its token; qsum = sum aq, tsum = sum at.
+// Out: L.aal.  `evals` counts evaluator calls (summed over the row's programs; max_iter caps this program's).
+template <int D>
+__device__ __forceinline__ int solve_program(Lds<D>& L, int& par, double* newton_ws, int m, int n, double ctx, int slack, double slack_target,
+                             double qsum, double tsum, double rel_tol, int max_iter, int* evals) {
+    constexpr int kSW = Lds<D>::kSW;
     const int tid = threadIdx.x;
+    const int evals0 = *evals;
     if (n == 1) {
         // One draft: a tuple is a single token, so the routed mass of token i is q_i w_i / (1 + w_i)
         // with the slack term (the single-draft rule, w_i = t_i / (q_i - t_i) in closed form) and q_i
@@ -685,198 +918,96 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m
             stuck = !(d > 0.0);
             L.aal[tid] = stuck ? 690.0 : log(L.at[tid] / d);
         }
-        return block_sum_i<kSW>(stuck, L.red) ? 1 : 0;
+        return wg_sum(L, par, static_cast<double>(stuck)) > 0.0 ? 1 : 0;
     }
-    const double qsum = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
-    const double tsum = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+    const double atot = ctx + qsum;
+    int heavy = 0, full = 0;
     if (tid < m) {
-        // per-token series of e^{zq}, and the degree beyond which its terms change the z^n
-        // coefficient by less than 1e-11 relative: C(n-1, c) (q/atot)^c / (c+1) < 1e-11
-        const double q = L.aq[tid], atot = ctx + qsum;
+        // per-token series of e^{zq}: q^k / k! for k <= n (terms beyond z^n never reach the z^n coefficient)
+        const double q = L.aq[tid];
         double e = 1.0;
-        L.etab[tid * (D + 1)] = 1.0;
-        for (int a = 1; a <= (D > 4 ? D : 4); ++a) {
-            e = e * q / a;
-            if (a <= D) L.etab[tid * (D + 1) + a] = e;
-            if (a <= 4) L.trec[tid].e[a - 1] = e;
+#pragma unroll
+        for (int a = 1; a <= D; ++a) {
+            e = e * q * (1.0 / a);
+            L.trec[tid].e[a - 1] = a <= n ? e : 0.0;
         }
-        // light if the u^5 and later terms of its factor cannot change the z^n coefficient by more
-        // than 1e-11 relative: C(n-1, 4) (q/atot)^4 / 5 < 1e-11; exact for n <= 4
+        L.trec[tid].pad = 0.0;
+        L.apd[tid] = pow_diff(atot, q, n);
+        // With more than 8 drafts the cumulant series of a token that dominates the draw mass loses digits to
+        // cancellation: the (at most three) tokens above kHeavyShare keep their exact factor instead.
+        heavy = (D > 8 && q > kHeavyShare * atot) ? 1 : 0;
+        // A token needs only four cumulants when the u^5 and later terms of its factor cannot change the z^n
+        // coefficient by more than 1e-11 relative: C(n-1, 4) (q/atot)^4 / 5 < 1e-11 (always, up to four drafts).
         const double r = q / atot;
         double binom = 1.0;
         for (int c = 1; c <= 4; ++c) binom = binom * (n - c) / c;         // C(n-1, 4)
-        L.adeg[tid] = (n <= 4 || binom * r * r * r * r / 5.0 < 1e-11) ? 0 : D;
-        L.apd[tid] = pow_diff(atot, q, n);
+        full = (D > 4 && !(binom * r * r * r * r / 5.0 < 1e-11)) ? 1 : 0;
     }
     if (tid < 32) L.e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
-    if (tid < 16) { TokRec z; z.aw = 1e300; z.e[0] = z.e[1] = z.e[2] = z.e[3] = 0.0; z.pad = 0.0; L.trec[m + tid] = z; }
-    const int nheavy = block_sum_i<kSW>((tid < m && L.adeg[tid] != 0) ? 1 : 0, L.red);
-    if (tid == 0) L.nbig = nheavy;
-    __syncthreads();
-    GR_CLK(L, 5);
-    int hcount = 0, plain = 0, since = 0;
-    double best_err = 1e300, cap = kStretch;
-    int result = 1;
-    const int mix_iters = (max_iter > kMixBudget + m) ? kMixBudget + m : max_iter;
-    for (int it = 1; it <= mix_iters; ++it) {
-        if (!slack) {
-            const double amax = block_max<kSW>(tid < m ? L.aal[tid] : -1e300, L.red);
-            if (tid < m) L.aal[tid] -= amax;
-            __syncthreads();
-        }
-        const double err = defect_eval<D>(L, m, n, ctx, slack, slack_target, qsum, tsum, nullptr);
-        *evals += 1;
-        // The fixed-point step log(target / routed) treats the routed mass as proportional to the
-        // weight; its true logarithmic derivative is (R - S) / R with S = w^2 int t ... (the share a
-        // token loses to itself), so the step of each coordinate is stretched by R / (R - S), at most
-        // `cap`.  The stretched iteration is no longer monotone: when kStall iterations bring no
-        // better point it returns to the best one with half the cap; at cap 1 (the plain step, whose
-        // stopping measure need not fall at every step) it is left alone.
-        double f = 0.0, ratio = 1.0;
-        if (tid < m) {
-            f = L.af[tid];
-            const double R = L.aR[tid], d = R - L.aS[tid];
-            ratio = (d > 0.0) ? fmin(R / d, 1e30) : 1e30;
-        }
-        if (err <= rel_tol) { result = 0; break; }
-        if (!(err < 1e300) || err > 100.0 * best_err) {
-            // a mixed step went astray: back to the best point, unmixed steps for a while
-            if (!(best_err < 1e300)) break;        // no finite point seen: give up on this program
-            if (tid < m) { L.aal[tid] = L.aBest[tid]; f = L.fBest[tid]; ratio = L.rBest[tid]; }
-            hcount = 0; plain = 20; since = 0;
-        } else if (err < best_err) {
-            best_err = err; since = 0;
-            if (tid < m) { L.aBest[tid] = L.aal[tid]; L.fBest[tid] = f; L.rBest[tid] = ratio; }
-        } else if (cap > 1.0 && ++since >= kStall) {
-            if (tid < m) { L.aal[tid] = L.aBest[tid]; f = L.fBest[tid]; ratio = L.rBest[tid]; }
-            hcount = 0; since = 0;
-            cap = fmax(1.0, 0.5 * cap);
-        }
-        f *= fmin(ratio, cap);
-        const int cur = it % kHist;
-        if (tid < m) { L.Ha[cur][tid] = L.aal[tid]; L.Hf[cur][tid] = f; }
-        const int ncol = plain > 0 ? 0 : min(hcount, kHist - 1);
-        if (plain > 0) --plain;
-        double stepv = f;
-        if (ncol >= 1) {
-            // normal equations of  min || f - dF gamma ||  with dF_c = f - f_c
-            double dF[kHist - 1], dA[kHist - 1];
+    if (tid < 4) {
+        TokRec<D>& z = L.trec[m + tid];
+        z.aw = 1e300; z.pad = 0.0;
 #pragma unroll
-            for (int c = 0; c < kHist - 1; ++c) {
-                const int slot = (cur - 1 - c + 2 * kHist) % kHist;
-                const bool on = c < ncol && tid < m;
-                dF[c] = on ? f - L.Hf[slot][tid] : 0.0;
-                dA[c] = on ? L.aal[tid] - L.Ha[slot][tid] : 0.0;
-            }
-            // Gram matrix and right-hand side
-            __syncthreads();                               // Hf[cur] is complete
-            {
-                // entry e of (upper triangle of the Gram matrix, then dF_a . f) goes to wave e mod 4;
-                // lanes cover the tokens.  The loop is unrolled, so the columns of an entry are constants.
-                const int wv = tid >> 6, lane = tid & 63;
-#pragma unroll
-                for (int e = 0; e < kGram; ++e) {
-                    constexpr int kTri = kCols * (kCols + 1) / 2;
-                    int ca = 0, cb = 0, idx = 0;
-#pragma unroll
-                    for (int a2 = 0; a2 < kCols; ++a2)
-#pragma unroll
-                        for (int b2 = a2; b2 < kCols; ++b2) { if (idx == e) { ca = a2; cb = b2; } ++idx; }
-                    const bool rhs = e >= kTri;
-                    if (rhs) { ca = e - kTri; cb = 0; }
-                    if ((e % kSW) != wv) continue;
-                    double acc = 0.0;
-                    if (ca < ncol && (rhs || cb < ncol)) {
-                        const int sa = (cur - 1 - ca + 2 * kHist) % kHist, sb = (cur - 1 - cb + 2 * kHist) % kHist;
-                        for (int i = lane; i < m; i += 64) {
-                            const double fi = L.Hf[cur][i];
-                            const double da = fi - L.Hf[sa][i];
-                            acc = fma(da, rhs ? fi : fi - L.Hf[sb][i], acc);
-                        }
-                        acc = wave_sum(acc);
-                    }
-                    if (lane == 0) L.gram[e] = acc;
-                }
-            }
-            __syncthreads();
-            if (tid == 0) {
-                // normal equations by Gaussian elimination without pivoting (the matrix is symmetric
-                // positive definite after the ridge); fully unrolled so that it stays in registers
-                double Gm[kCols][kCols + 1];
-                {
-                    int idx = 0;
-#pragma unroll
-                    for (int a = 0; a < kCols; ++a)
-#pragma unroll
-                        for (int b = a; b < kCols; ++b) {
-                            const double g = L.gram[idx];
-                            Gm[a][b] = g; Gm[b][a] = g; ++idx;
-                        }
-#pragma unroll
-                    for (int a = 0; a < kCols; ++a) {
-                        Gm[a][kCols] = L.gram[idx]; ++idx;
-                    }
-                }
-                bool good = true;
-                double pivinv[kCols];
-#pragma unroll
-                for (int c = 0; c < kCols; ++c) pivinv[c] = 0.0;
-#pragma unroll
-                for (int c = 0; c < kCols; ++c) {
-                    if (c < ncol) {
-                        // a ridge relative to the column itself: recent columns are far shorter than old ones
-                        Gm[c][c] = Gm[c][c] * (1.0 + 1e-10) + 1e-300;
-                        good = good && (Gm[c][c] > 0.0);
-                        const double inv = 1.0 / Gm[c][c];
-                        pivinv[c] = inv;
-#pragma unroll
-                        for (int r = c + 1; r < kCols; ++r) {
-                            if (r < ncol) {
-                                const double fct = Gm[r][c] * inv;
-#pragma unroll
-                                for (int j = c + 1; j <= kCols; ++j) Gm[r][j] = fma(-fct, Gm[c][j], Gm[r][j]);
-                            }
-                        }
-                    }
-                }
-                double gam[kCols];
-#pragma unroll
-                for (int c = kCols - 1; c >= 0; --c) {
-                    double sacc = Gm[c][kCols];
-#pragma unroll
-                    for (int j = c + 1; j < kCols; ++j) if (j < ncol) sacc = fma(-Gm[c][j], gam[j], sacc);
-                    gam[c] = (c < ncol) ? sacc * pivinv[c] : 0.0;
-                }
-                double gnorm = 0.0;
-#pragma unroll
-                for (int c = 0; c < kCols; ++c) { L.gamma[c] = gam[c]; gnorm += fabs(gam[c]); }
-                L.ok = (good && gnorm < 1e300) ? 1 : 0;
-            }
-            __syncthreads();
-            double cand = f;
-#pragma unroll
-            for (int c = 0; c < kCols; ++c) cand -= (dA[c] + dF[c]) * L.gamma[c];
-            const int solved = L.ok;
-            const double cmax = block_max<kSW>(tid < m ? fabs(cand) : 0.0, L.red);
-            // a mixed step longer than 3 in log weight is cut to that length (the same cap as the
-            // Newton fallback); a failed solve drops the history
-            if (solved && cmax < 1e300) stepv = cmax > 3.0 ? cand * (3.0 / cmax) : cand;
-            else hcount = 0;
-        }
-        if (ncol < 1) {                                    // a plain step: the same cap on its length
-            const double fmx = block_max<kSW>(tid < m ? fabs(f) : 0.0, L.red);
-            if (fmx > 3.0) stepv = f * (3.0 / fmx);
-        }
-        if (tid < m) L.aal[tid] += stepv;
-        ++hcount;
-        __syncthreads();
+        for (int a = 0; a < D; ++a) z.e[a] = 0.0;
+    }
+    if (D > 4) {
+        // tokens are in decreasing q: the heavy ones are the first nh, those with all cumulants the first nf
+        double a[2] = {wave_sum(static_cast<double>(heavy)), wave_sum(static_cast<double>(full))};
+        wg_reduce<2>(L, par, a, {kOpSum, kOpSum});
+        const int nh = static_cast<int>(a[0]), nf = static_cast<int>(a[1]);
+        if (tid == 0) { L.nheavy = nh < kMaxHeavy ? nh : kMaxHeavy; L.nfull = nf > L.nheavy ? nf : L.nheavy; }
     }
     __syncthreads();
+    GR_CLK(L, 5);
+    double fact = 1.0;
+    for (int i = 2; i <= n; ++i) fact *= i;
+    const int mix_iters = (max_iter > kMixBudget + m) ? kMixBudget + m : max_iter;
+    const int wvi = tid >> 6, lane = tid & 63;
+    // The iteration is steered by wave 0 alone (lane l holds tokens l and l + 64, so every reduction over the
+    // tokens is a wave reduction and the mixing needs no workgroup exchange); all waves evaluate.  Per
+    // iteration: barrier, evaluation by all waves, barrier, mixing step by wave 0 (the others wait at the next
+    // barrier).  Wave 0 hands over through L.ctl_*: whether to go on, and the quadrature grid of the new weights.
+    // Wave-0 state: uniform scalars in registers, per-token values in LDS (L.aal, L.at, the best point, the last
+    // kHist iterates and stretched residuals by slot, L.pm = inner products of the stored residual vectors).
+    MixState st;
+    st.hcount = 0; st.plain = 0; st.since = 0; st.best_err = 1e300; st.cap = kStretch;
+    const int tk[2] = {lane, lane + 64};
+    const bool on[2] = {wvi == 0 && tk[0] < m, wvi == 0 && tk[1] < m};
+    if (wvi == 0) {
+        double ws = 0.0, wm = 1e300, amax = -1e300;
+        if (!slack) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) if (on[u]) amax = fmax(amax, L.aal[tk[u]]);
+            amax = wave_max(amax);
+        } else amax = 0.0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) if (on[u]) {
+            const double al = L.aal[tk[u]] - amax;
+            const double w = exp_signed(al, L.e2tab);
+            L.aal[tk[u]] = al; L.trec[tk[u]].aw = w; ws += w; wm = fmin(wm, w);
+        }
+        ws = wave_sum(ws); wm = wave_min(wm);
+        if (lane == 0) { L.ctl_go = 1; L.ctl_result = 1; L.ctl_bestok = 0; L.ctl_grid = make_grid(slack, ctx, ws, wm, kQuadStep); }
+    }
+    for (int it = 1; it <= mix_iters; ++it) {
+        __syncthreads();                                   // the weights and L.ctl of this iteration are in place
+        if (!L.ctl_go) break;
+        const Grid gr = L.ctl_grid;
+        eval_core<D>(L, gr, m, n, ctx, slack);
+        *evals += 1;
+        __syncthreads();                                   // every wave's partial sums are in place
+        GR_CLK(L, 10);
+        if (wvi != 0) continue;
+        st = mix_step<D>(st, gr, it, m, n, slack, ctx, slack_target, tsum, atot, fact, rel_tol, *evals);
+    }
+    __syncthreads();
+    int result = L.ctl_result;
+    const bool bestok = L.ctl_bestok != 0;
     GR_CLK(L, 12);
-    if (result != 0 && mix_iters < max_iter && best_err < 1e300) {
+    if (result != 0 && mix_iters < max_iter && bestok) {
         if (tid < m) L.aal[tid] = L.aBest[tid];
         __syncthreads();
-        result = newton_program<D>(L, newton_ws, m, n, ctx, slack, slack_target, qsum, tsum, rel_tol, max_iter, evals);
+        result = newton_program<D>(L, par, newton_ws, m, n, ctx, slack, slack_target, qsum, tsum, fact, rel_tol, max_iter, evals, evals0);
         GR_CLK(L, 13);
     }
     return result;
@@ -887,13 +1018,14 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, double* newton_ws, int m
 // order).  Returns m (possibly > kMaxT, in which case nothing was written beyond kMaxT).
 template <class LdsT>
 __device__ int compact_active(LdsT& L, int lo, int hi, int kk) {
+    constexpr int kSW = LdsT::kSW;
     const int tid = threadIdx.x;
     const int j = tid < kk ? L.ordq[tid] : -1;           // kk <= KS <= kST
     const int on = (j >= lo && j < hi && L.inT[j] && L.tgt[j] > 0.0) ? 1 : 0;
     // inclusive scan of `on` over the workgroup
     int incl = on;
     for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if ((tid & 63) >= o) incl += up; }
-    int* wtot = reinterpret_cast<int*>(L.red);
+    int* wtot = reinterpret_cast<int*>(L.redn);
     if ((tid & 63) == 63) wtot[tid >> 6] = incl;
     __syncthreads();
     int base = 0, total = 0;
@@ -907,9 +1039,9 @@ __device__ int compact_active(LdsT& L, int lo, int hi, int kk) {
 }  // namespace
 
 template <int D>
-__global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds<D>& L = *reinterpret_cast<Lds<D>*>(lds_raw);
+__global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
+    constexpr int kST = Lds<D>::kST, kSW = Lds<D>::kSW;
+    Lds<D>& L = *reinterpret_cast<Lds<D>*>(gr_lds_raw);
     const int tid = threadIdx.x;
     const int row = blockIdx.x;
     const int n = sp.n, V = sp.V;
@@ -942,55 +1074,59 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         for (int s = 0; s < sp.splits; ++s) {
             const int c = sp.cand_count[row * sp.splits + s];
             const unsigned long long* src = sp.cand + (static_cast<size_t>(row) * sp.splits + s) * kMaxSupport;
-            for (int i = tid; i < c; i += kST) L.u.keys[off + i] = src[i];
+            for (int i = tid; i < c; i += kST) L.keys[off + i] = src[i];
             off += c;
         }
     }
     if (tid == 0) { L.count = 0; L.work = 0.0; }
 #ifdef GR_PHASE_CLOCKS
-    if (tid == 0) { for (int i = 0; i < 16; ++i) L.clk[i] = 0; L.clk_last = clock64(); }
+    if (tid == 0) { for (int i = 0; i < 24; ++i) L.clk[i] = 0; L.clk_last = clock64(); }
 #endif
     __syncthreads();
     unsigned long long theta = 0ull;
-    if (total > sp.k) theta = block_kth_largest<kST>(L.u.keys, total, sp.k, L.hist, L.pick);
+    if (total > sp.k) theta = block_kth_largest<kST>(L.keys, total, sp.k, L.hist, L.pick);
     const int kk = min(total, sp.k);
     for (int i = tid; i < total; i += kST) {
-        const unsigned long long key = L.u.keys[i];
+        const unsigned long long key = L.keys[i];
         if (key >= theta) {
             const int slot = atomicAdd(&L.count, 1);
-            if (slot < KS) { L.ordq[slot] = key_id(key); L.accb[slot] = static_cast<double>(key_q(key)); }
+            if (slot < KS) { L.ids[slot] = key_id(key); L.accb[slot] = static_cast<double>(key_q(key)); }
         }
     }
     __syncthreads();
-    // unsorted: token ids in ordq, q in accb (exact float values), p gathered into G0
-    if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ordq[tid]]);
+    // unsorted: token ids in ids, q in accb (exact float values), p gathered into G0
+    if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
+    if (tid < kk) { L.cnt0[tid] = 0; L.cnt1[tid] = 0; }
     __syncthreads();
     GR_CLK(L, 0);
-    // ---- order by decreasing q/p: exact cross products (float x float fits a double), ties by id.
-    // Rank counting; `parts` threads share a token (each counts over a stretch of the others).
+    // ---- two orders from one pass of rank counting (`parts` threads share a token, each counts over a stretch
+    // of the others): by decreasing q/p -- exact cross products (float x float fits a double), ties by id --
+    // and by decreasing q, ties by id (the order in which truncation sets grow).
     {
         const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
         const int per = kST / parts;                       // tokens a part can hold
         const int me = tid % per, part = tid / per;
-        if (tid < kk) L.cnt0[tid] = 0;
-        __syncthreads();
         if (me < kk) {
             const double qa = L.accb[me], pa = L.G0[me];
-            const int ta = L.ordq[me];
+            const int ta = L.ids[me];
             const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
-            int rank = 0;
-#pragma unroll 8
+            int rank = 0, qrank = 0;
+#pragma unroll 4
             for (int j = j0; j < j1; ++j) {
-                const double lhs = L.accb[j] * pa, rhs = qa * L.G0[j];   // j before me?
-                rank += static_cast<int>(lhs > rhs) | (static_cast<int>(lhs == rhs) & static_cast<int>(L.ordq[j] < ta));
+                const double qj = L.accb[j];
+                const double lhs = qj * pa, rhs = qa * L.G0[j];   // j before me?
+                const int lower = static_cast<int>(L.ids[j] < ta);
+                rank += static_cast<int>(lhs > rhs) | (static_cast<int>(lhs == rhs) & lower);
+                qrank += static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & lower);
             }
-            if (parts > 1) atomicAdd(&L.cnt0[me], rank); else L.cnt0[me] = rank;
+            if (parts > 1) { atomicAdd(&L.cnt0[me], rank); atomicAdd(&L.cnt1[me], qrank); }
+            else { L.cnt0[me] = rank; L.cnt1[me] = qrank; }
         }
         __syncthreads();
         if (tid < kk) {
             const int rank = L.cnt0[tid];
-            const double pa = L.G0[tid];
-            L.tok[rank] = L.ordq[tid]; L.qd[rank] = L.accb[tid]; L.pn[rank] = pa / ptot;
+            L.tok[rank] = L.ids[tid]; L.qd[rank] = L.accb[tid]; L.pn[rank] = L.G0[tid] / ptot;
+            L.byq[L.cnt1[tid]] = rank;                    // the token of q rank j sits at ratio rank byq[j]
         }
         __syncthreads();
     }
@@ -1010,81 +1146,92 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         }
         __syncthreads();
     }
-    // ---- H*: the smallest minimising prefix
-    double fmin_local = 1e300;
-    for (int m = tid; m <= kk; m += kST) fmin_local = fmin(fmin_local, L.F[m]);
-    const double Fmin = block_min<kSW>(fmin_local, L.red);
-    double hcand = 1e9;
-    for (int m = tid; m <= kk; m += kST) if (L.F[m] == Fmin) hcand = fmin(hcand, static_cast<double>(m));
-    const int h = static_cast<int>(block_min<kSW>(hcand, L.red));
-    // ---- G = suffix minima of F (Hillis-Steele over kk+1 entries)
-    for (int m = tid; m <= kk; m += kST) L.G0[m] = L.F[m];
-    __syncthreads();
-    {
-        double* src = L.G0; double* dst = L.G1;
-        for (int o = 1; o <= kk; o <<= 1) {
-            for (int m = tid; m <= kk; m += kST) dst[m] = (m + o <= kk) ? fmin(src[m], src[m + o]) : src[m];
-            __syncthreads();
-            double* t = src; src = dst; dst = t;
+    // ---- one wave, no barriers: H* (the smallest minimising prefix), the suffix minima G of F, residuals,
+    // targets and records (F(m) <= G(m+1) for m >= h; m = kk always), the block of every token, and the
+    // order by decreasing q split into H* and the rest.  Lane l holds ranks 5l .. 5l+4 (kk + 1 <= 257).
+    if ((tid >> 6) == 0) {
+        constexpr int E = (KS + 1 + 63) / 64;
+        const int lane = tid, m0 = lane * E;
+        double Fv[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) Fv[e] = (m0 + e <= kk) ? L.F[m0 + e] : 1e300;
+        double lmin = Fv[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) lmin = fmin(lmin, Fv[e]);
+        const double Fmin = wave_min(lmin);
+        int lidx = 1 << 20;
+#pragma unroll
+        for (int e = E - 1; e >= 0; --e) if (Fv[e] == Fmin) lidx = m0 + e;
+        const int hh = static_cast<int>(wave_min(static_cast<double>(lidx)));
+        double sfx[E];
+        sfx[E - 1] = Fv[E - 1];
+#pragma unroll
+        for (int e = E - 2; e >= 0; --e) sfx[e] = fmin(Fv[e], sfx[e + 1]);
+        double later = sfx[0];                             // min of F over this lane's ranks and all later ones
+        for (int o = 1; o < 64; o <<= 1) { const double x = __shfl_down(later, o); if (lane + o < 64) later = fmin(later, x); }
+        double after = __shfl_down(later, 1);              // ... over the later lanes only
+        if (lane == 63) after = 1e300;
+        int fl[E], run = 0, cl[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int m = m0 + e;
+            fl[e] = 0;
+            if (m <= kk) {
+                const double g = fmin(sfx[e], after);                                   // G(m)
+                const double gn = (e < E - 1) ? fmin(sfx[e + 1], after) : after;         // G(m + 1), unused at m = kk
+                fl[e] = (m >= hh && (m == kk || Fv[e] <= gn)) ? 1 : 0;
+                L.flag[m] = fl[e];
+                if (m < kk) {
+                    const double r = (m >= hh) ? gn - g : 0.0;
+                    L.rho[m] = r; L.tgt[m] = L.pn[m] - r;
+                }
+            }
+            run += fl[e]; cl[e] = run;
         }
-        if (src != L.G0) { for (int m = tid; m <= kk; m += kST) L.G0[m] = src[m]; }
-        __syncthreads();
-    }
-    // residuals, targets, records (F(m) <= G(m+1) for m >= h; m = kk always)
-    for (int m = tid; m <= kk; m += kST) {
-        L.flag[m] = (m >= h && (m == kk || L.F[m] <= L.G0[m + 1])) ? 1 : 0;
-        if (m < kk) {
-            const double r = (m >= h) ? L.G0[m + 1] - L.G0[m] : 0.0;
-            L.rho[m] = r; L.tgt[m] = L.pn[m] - r;
+        int incl = run;
+        for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+        const int base = incl - run;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int m = m0 + e;
+            if (m <= kk) {
+                const int c = base + cl[e];
+                if (fl[e]) L.blo[c] = m;                     // record number c (1-based) sits at rank m
+                if (m < kk) L.blk[m] = (m >= hh) ? c : 0;    // token m (rank m+1) lies after record c
+            }
         }
+        const int nrec_ = __shfl(incl, 63);
+        // ordq: ratio ranks listed by decreasing q, the tokens of H* first (a stable split of the q order)
+        constexpr int E4 = KS / 64;
+        const int j0 = lane * E4;
+        int rk[E4], in[E4], cin = 0, ci[E4];
+#pragma unroll
+        for (int e = 0; e < E4; ++e) {
+            const int j = j0 + e;
+            rk[e] = j < kk ? L.byq[j] : 0;
+            in[e] = (j < kk && rk[e] < hh) ? 1 : 0;
+            ci[e] = cin;                                   // members of H* among this lane's earlier entries
+            cin += in[e];
+        }
+        int incl_in = cin;
+        for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl_in, o); if (lane >= o) incl_in += up; }
+        const int base_in = incl_in - cin;
+#pragma unroll
+        for (int e = 0; e < E4; ++e) {
+            const int j = j0 + e;
+            if (j < kk) {
+                const int before_in = base_in + ci[e];
+                L.ordq[in[e] ? before_in : hh + (j - before_in)] = rk[e];
+            }
+        }
+        if (lane == 0) { L.pick[0] = hh; L.pick[1] = nrec_; }
     }
     __syncthreads();
-    // inclusive count of records -> block id of each token outside H*, and block bounds
-    for (int m = tid; m <= kk; m += kST) L.cnt0[m] = L.flag[m];
-    __syncthreads();
-    {
-        int* src = L.cnt0; int* dst = L.cnt1;
-        for (int o = 1; o <= kk; o <<= 1) {
-            for (int m = tid; m <= kk; m += kST) dst[m] = (m >= o) ? src[m] + src[m - o] : src[m];
-            __syncthreads();
-            int* t = src; src = dst; dst = t;
-        }
-        if (src != L.cnt0) { for (int m = tid; m <= kk; m += kST) L.cnt0[m] = src[m]; }
-        __syncthreads();
-    }
-    const int nrec = L.cnt0[kk];
+    const int h = L.pick[0];
+    const int nrec = L.pick[1];
     const int nblk = nrec - 1;
-    for (int m = tid; m <= kk; m += kST) {
-        if (L.flag[m]) L.blo[L.cnt0[m]] = m;             // record number c (1-based) sits at rank m
-        if (m < kk) L.blk[m] = (m >= h) ? L.cnt0[m] : 0; // token m (rank m+1) lies after record cnt0[m]
-    }
-    __syncthreads();
     GR_CLK(L, 2);
     // ---- truncation sets: fewest tokens by decreasing q with gamma_T <= tau / epsilon_T <= tau
-    {
-        const int parts = kk <= kST / 4 ? 4 : (kk <= kST / 2 ? 2 : 1);
-        const int per = kST / parts;
-        const int me = tid % per, part = tid / per;
-        if (tid < kk) L.cnt1[tid] = 0;
-        __syncthreads();
-        if (me < kk) {
-            const int mine_in = me < h;
-            const float qa = static_cast<float>(L.qd[me]);
-            const int ta = L.tok[me];
-            const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
-            int rank = 0;
-#pragma unroll 8
-            for (int j = j0; j < j1; ++j) {
-                const int same = (j < h) == mine_in;
-                const float qj = static_cast<float>(L.qd[j]);
-                rank += same & (static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & static_cast<int>(L.tok[j] < ta)));
-            }
-            if (parts > 1) atomicAdd(&L.cnt1[me], rank); else L.cnt1[me] = rank;
-        }
-        __syncthreads();
-        if (tid < kk) L.ordq[(tid < h ? 0 : h) + L.cnt1[tid]] = tid;
-    }
-    __syncthreads();
     const double Qh = L.Q[h];
     {
 #pragma clang fp contract(off)
@@ -1094,12 +1241,12 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         if ((tid >> 6) == 0) wave_sequential_scan(L.G0, L.G1, h, 0.0);
         if ((tid >> 6) == 1) wave_sequential_scan(L.G0 + h, L.G1 + h + 1, kk - h, Qh);
         __syncthreads();
-        if (tid < kk) L.accb[L.ordq[tid]] = L.G1[tid < h ? tid : tid + 1];
-        __syncthreads();
+        // the token at position t of that order has the mass G1[...] before it
         if (tid < kk) {
-            const double a = L.accb[tid];
+            const int j = L.ordq[tid];
+            const double a = L.G1[tid < h ? tid : tid + 1];
             const double an = (a > 0.0) ? ipow(a, n) : 0.0;
-            L.inT[tid] = (tid < h) ? ((ipow(Qh, n) - an) > sp.tau) : ((1.0 - an) > sp.tau);
+            L.inT[j] = (j < h) ? ((ipow(Qh, n) - an) > sp.tau) : ((1.0 - an) > sp.tau);
         }
     }
     // ---- start weights: target / Pr[token drawn within its system], inner ones in the slack's gauge
@@ -1114,7 +1261,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 
     GR_CLK(L, 3);
     // ---- the convex programs: program 0 = inner system, then every outer block of two or more tokens
-    int status = GR_ROW_OK, evals = 0;
+    int status = GR_ROW_OK, evals = 0, par = 0;
     for (int b = (h > 0 ? 0 : 1); b <= nblk && status != GR_ROW_TRUNC_CAP; ++b) {
         const int lo = (b == 0) ? 0 : L.blo[b];
         const int hi = (b == 0) ? h : L.blo[b + 1];
@@ -1122,18 +1269,21 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         const int m = compact_active(L, lo, hi, kk);
         if (m > sp.max_T) { status = GR_ROW_TRUNC_CAP; break; }
         if (m == 0 || (b > 0 && m < 2)) continue;
+        double w0 = 0.0, q0 = 0.0, t0 = 0.0;
         if (tid < m) {
             const int j = L.apos[tid];
-            L.aq[tid] = L.qn[j]; L.at[tid] = L.tgt[j]; L.aal[tid] = log(L.wgt[j]);
+            w0 = L.wgt[j]; q0 = L.qn[j]; t0 = L.tgt[j];
+            L.aq[tid] = q0; L.aal[tid] = fast_log(w0);
         }
-        __syncthreads();
-        const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
-        const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+        // one exchange: the draw mass and the targets of the active tokens, their start weights, and (inner
+        // system) the context = tokens of T with target 0 (weight 0): they fill tuples but take no mass
+        double ex[4] = {wave_sum(q0), wave_sum(t0), wave_sum(w0),
+                        wave_sum((b == 0 && tid < h && L.inT[tid] && !(L.tgt[tid] > 0.0)) ? L.qn[tid] : 0.0)};
+        wg_reduce<4>(L, par, ex, {kOpSum, kOpSum, kOpSum, kOpSum});
+        const double qa = ex[0], ta = ex[1], w0sum = ex[2];
         double ctx, scale, slack_target = 0.0;
         if (b == 0) {
-            // context = tokens of T with target 0 (weight 0): they fill tuples but take no mass
-            const int j = tid;
-            ctx = block_sum<kSW>((j < h && L.inT[j] && !(L.tgt[j] > 0.0)) ? L.qn[j] : 0.0, L.red);
+            ctx = ex[3];
             const double mass = ipow(ctx + qa, n);
             scale = mass / (ta - L.F[h]);
             slack_target = -L.F[h] * scale;
@@ -1141,14 +1291,13 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
             ctx = L.Q[lo];
             scale = pow_diff(ctx + qa, qa, n) / ta;
         }
-        const double w0sum = block_sum<kSW>(tid < m ? L.wgt[L.apos[tid]] : 0.0, L.red);
-        if (tid < m) L.at[tid] *= scale;
-        __syncthreads();
+        if (tid < m) L.at[tid] = t0 * scale;
         GR_CLK(L, 4);
-        const int rc = solve_program<D>(L, sp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, b == 0, slack_target, sp.rel_tol, sp.max_iter, &evals);
+        const int rc = solve_program<D>(L, par, sp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, b == 0, slack_target,
+                                        qa, ta * scale, sp.rel_tol, sp.max_iter, &evals);
         if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
         const double wv = (tid < m) ? exp(L.aal[tid]) : 0.0;
-        const double wsum = block_sum<kSW>(wv, L.red);
+        const double wsum = (b == 0) ? 1.0 : wg_sum(L, par, wv);
         if (tid < m) L.wgt[L.apos[tid]] = (b == 0) ? wv : wv * (w0sum / wsum);
         __syncthreads();
     }
@@ -1169,7 +1318,7 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
         info.res_total = -L.F[h];
         info.node_tokens = L.work;
 #ifdef GR_PHASE_CLOCKS
-        { const long long now_ = clock64(); L.clk[14] += now_ - L.clk_last; for (int i = 0; i < 16; ++i) info.clk[i] = L.clk[i]; }
+        { const long long now_ = clock64(); L.clk[14] += now_ - L.clk_last; for (int i = 0; i < 24; ++i) { info.clk[i] = L.clk[i]; info.errlog[i] = i < evals ? L.errlog[i] : 0.0; } }
 #endif
         sp.info[row] = info;
         sp.accept_prob[row] = static_cast<float>(1.0 + L.F[h]);
@@ -1182,9 +1331,9 @@ __global__ __launch_bounds__(kST) void solve_kernel(SolveParams sp) {
 // inner program over T inside H* and one outer program per block that holds two or more active
 // tokens of T -- the same programs, in the same arithmetic, as the LDS-resident path.
 template <int D>
-__global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    Lds<D>& L = *reinterpret_cast<Lds<D>*>(lds_raw);
+__global__ __launch_bounds__(kThreadsOf<D>) void full_programs_kernel(FullParams fp) {
+    constexpr int kST = Lds<D>::kST, kSW = Lds<D>::kSW;
+    Lds<D>& L = *reinterpret_cast<Lds<D>*>(gr_lds_raw);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
     const int n = fp.n, V = fp.V;
     const size_t vs = static_cast<size_t>(V) + 2;
@@ -1230,7 +1379,7 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
     if (tid == 0) L.work = 0.0;
     __syncthreads();
 
-    int status = GR_ROW_OK, evals = 0;
+    int status = GR_ROW_OK, evals = 0, par = 0;
     // ---- inner program: T inside H* is the first tcount[0] entries of byq, already by decreasing q
     if (h > 0) {
         const int c_in = fp.tcount[2 * row];
@@ -1252,33 +1401,34 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
             m += tile_total;
             __syncthreads();
         }
-        const double ctx = block_sum<kSW>(ctx_part, L.red);
+        const double ctx = block_sum<kSW>(ctx_part, L.redn);
         if (m > 0 && m <= kMaxT) {
-            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
-            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.redn);
+            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.redn);
             const double mass = ipow(ctx + qa, n);
             const double scale = mass / (ta - Fh);
             const double slack_target = -Fh * scale;
             if (tid < m) L.at[tid] *= scale;
             __syncthreads();
-            const int rc = solve_program<D>(L, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 1, slack_target, fp.rel_tol, fp.max_iter, &evals);
+            const int rc = solve_program<D>(L, par, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 1, slack_target,
+                                            qa, ta * scale, fp.rel_tol, fp.max_iter, &evals);
             if (rc != 0) status = GR_ROW_ITER_CAP;
             if (tid < m) weight[L.apos[tid]] = exp(L.aal[tid]);
             __syncthreads();
         }
     }
-    // ---- outer programs: windows of kST blocks, those with two or more active tokens of T
+    // ---- outer programs: those blocks with two or more active tokens of T
     const int nblk = fp.nblk[row];
-    for (int b0 = 1; b0 <= nblk; b0 += kST) {
+    for (int b0 = 1; b0 <= nblk; b0 += KS) {               // windows of KS blocks: L.flag lists the window's programs
         const int bme = b0 + tid;
-        const bool need = bme <= nblk && bcount[bme] >= 2;
+        const bool need = tid < KS && bme <= nblk && bcount[bme] >= 2;
         const unsigned long long nmask = __ballot(need);
         if (lane == 0) L.hist[wv] = __popcll(nmask);
         __syncthreads();
         int pslot = __popcll(nmask & ((1ull << lane) - 1ull));
         int nprog = 0;
         for (int w = 0; w < kSW; ++w) { if (w < wv) pslot += L.hist[w]; nprog += L.hist[w]; }
-        if (need) L.flag[pslot] = bme;                      // nprog <= kST <= KS + 2
+        if (need) L.flag[pslot] = bme;                      // nprog <= KS
         __syncthreads();
         for (int pi = 0; pi < nprog; ++pi) {
             const int b = L.flag[pi];
@@ -1307,17 +1457,18 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
                 L.apos[pos] = L.adeg[tid]; L.aq[pos] = qa; L.at[pos] = L.aR[tid]; L.aal[pos] = L.aw[tid];
             }
             __syncthreads();
-            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.red);
-            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.red);
+            const double qa = block_sum<kSW>(tid < m ? L.aq[tid] : 0.0, L.redn);
+            const double ta = block_sum<kSW>(tid < m ? L.at[tid] : 0.0, L.redn);
             const double ctx = Q[lo];
             const double scale = pow_diff(ctx + qa, qa, n) / ta;
-            const double w0sum = block_sum<kSW>(tid < m ? exp(L.aal[tid]) : 0.0, L.red);
+            const double w0sum = block_sum<kSW>(tid < m ? exp(L.aal[tid]) : 0.0, L.redn);
             if (tid < m) L.at[tid] *= scale;
             __syncthreads();
-            const int rc = solve_program<D>(L, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 0, 0.0, fp.rel_tol, fp.max_iter, &evals);
+            const int rc = solve_program<D>(L, par, fp.newton_ws + static_cast<size_t>(row) * kMaxT * (kMaxT + 1), m, n, ctx, 0, 0.0,
+                                            qa, ta * scale, fp.rel_tol, fp.max_iter, &evals);
             if (rc != 0 && status == GR_ROW_OK) status = GR_ROW_ITER_CAP;
             const double wvv = (tid < m) ? exp(L.aal[tid]) : 0.0;
-            const double wsum = block_sum<kSW>(wvv, L.red);
+            const double wsum = block_sum<kSW>(wvv, L.redn);
             if (tid < m) weight[L.apos[tid]] = wvv * (w0sum / wsum);
             __syncthreads();
         }
@@ -1331,11 +1482,11 @@ __global__ __launch_bounds__(kST) void full_programs_kernel(FullParams fp) {
 }
 
 hipError_t launch_full_programs(const FullParams& fp, hipStream_t stream) {
-    const dim3 grid(fp.B), block(kST);
-    if (fp.n <= 2) hipLaunchKernelGGL(full_programs_kernel<2>, grid, block, sizeof(Lds<2>), stream, fp);
-    else if (fp.n <= 4) hipLaunchKernelGGL(full_programs_kernel<4>, grid, block, sizeof(Lds<4>), stream, fp);
-    else if (fp.n <= 8) hipLaunchKernelGGL(full_programs_kernel<8>, grid, block, sizeof(Lds<8>), stream, fp);
-    else hipLaunchKernelGGL(full_programs_kernel<16>, grid, block, sizeof(Lds<16>), stream, fp);
+    const dim3 grid(fp.B);
+    if (fp.n <= 2) hipLaunchKernelGGL(full_programs_kernel<2>, grid, dim3(kThreadsOf<2>), sizeof(Lds<2>), stream, fp);
+    else if (fp.n <= 4) hipLaunchKernelGGL(full_programs_kernel<4>, grid, dim3(kThreadsOf<4>), sizeof(Lds<4>), stream, fp);
+    else if (fp.n <= 8) hipLaunchKernelGGL(full_programs_kernel<8>, grid, dim3(kThreadsOf<8>), sizeof(Lds<8>), stream, fp);
+    else hipLaunchKernelGGL(full_programs_kernel<16>, grid, dim3(kThreadsOf<16>), sizeof(Lds<16>), stream, fp);
     return hipGetLastError();
 }
 
@@ -1358,11 +1509,11 @@ hipError_t solve_kernel_setup() {
 
 // One kernel per series degree D >= n (2, 4, 8, 16), so that each keeps its series in registers.
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream) {
-    const dim3 grid(sp.B), block(kST);
-    if (sp.n <= 2) hipLaunchKernelGGL(solve_kernel<2>, grid, block, sizeof(Lds<2>), stream, sp);
-    else if (sp.n <= 4) hipLaunchKernelGGL(solve_kernel<4>, grid, block, sizeof(Lds<4>), stream, sp);
-    else if (sp.n <= 8) hipLaunchKernelGGL(solve_kernel<8>, grid, block, sizeof(Lds<8>), stream, sp);
-    else hipLaunchKernelGGL(solve_kernel<16>, grid, block, sizeof(Lds<16>), stream, sp);
+    const dim3 grid(sp.B);
+    if (sp.n <= 2) hipLaunchKernelGGL(solve_kernel<2>, grid, dim3(kThreadsOf<2>), sizeof(Lds<2>), stream, sp);
+    else if (sp.n <= 4) hipLaunchKernelGGL(solve_kernel<4>, grid, dim3(kThreadsOf<4>), sizeof(Lds<4>), stream, sp);
+    else if (sp.n <= 8) hipLaunchKernelGGL(solve_kernel<8>, grid, dim3(kThreadsOf<8>), sizeof(Lds<8>), stream, sp);
+    else hipLaunchKernelGGL(solve_kernel<16>, grid, dim3(kThreadsOf<16>), sizeof(Lds<16>), stream, sp);
     return hipGetLastError();
 }
 

@@ -47,8 +47,11 @@ def topk_support(q_row: np.ndarray, k: int) -> np.ndarray:
     """Indices of the k largest positive entries (ties: lower index first), ascending."""
     pos = np.flatnonzero(q_row > 0)
     if 0 < k < q_row.shape[0] and pos.size > k:
-        order = np.lexsort((pos, -q_row[pos].astype(np.float64)))
-        pos = pos[order[:k]]
+        vals = q_row[pos]
+        kth = np.partition(vals, pos.size - k)[pos.size - k]      # the k-th largest value
+        above = pos[vals > kth]
+        ties = pos[vals == kth]                                   # ascending index
+        pos = np.concatenate([above, ties[: k - above.size]])
     return np.sort(pos)
 
 

@@ -131,7 +131,7 @@ def test_one_draft_with_a_large_support_uses_the_closed_form():
     compare_rows(wl, out, range(wl.B), 1e-7)
     # closed form of the acceptance at n = 1: sum_i min(p_i, q_i) over the renormalised top-k row
     for b in range(wl.B):
-        sup = W.topk_support(wl.q[b], wl.k)
+        sup = sorted(sorted(np.flatnonzero(wl.q[b] > 0), key=lambda i: (-float(wl.q[b, i]), i))[: wl.k])   # the k largest q, ties to the lower id
         qs = wl.q[b, sup].astype(np.float64); qs /= qs.sum()
         ps = wl.p[b, sup].astype(np.float64) / float(np.sum(wl.p[b], dtype=np.float64))
         assert abs(out["accept_prob"][b] - np.minimum(ps, qs).sum()) < 1e-5

@@ -101,7 +101,7 @@ def test_uniform_rows_at_full_size():
     from paper_2511_15898_amd import binding as gr
     dev = torch.device("cuda:0")
     V = 128256
-    h = gr.gr_create(2, V)
+    h = gr.gr_create(2, V, max_k=0)
     try:
         p = torch.full((2, V), 1.0 / V, device=dev)
         acc, st = gr.gr_solve(h, p, p, 4, V, 1e-6)

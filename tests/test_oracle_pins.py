@@ -425,3 +425,33 @@ def test_fragile_flag_covers_every_row_whose_discrete_structure_moves_under_roun
             if np.array_equal(p, q):
                 assert sol.fragile and abs(sol.alpha_star - 1.0) < 1e-12
     assert flagged >= 10 and moved_flagged >= 5, (flagged, moved_flagged)
+
+
+# ------------------------------------------------------------------ rows given as logits
+def test_logits_front_end_against_closed_forms_and_invariances():
+    """App. A: temperature only changes how p, q come from the logits.  Two tokens: p_1 = 1 / (1 + e^{(b - a)/T})
+    (the logistic function) and alpha* = 1 + min(0, p_1 - q_1^n, p_2 - q_2^n), the minimum of psi over the four
+    subsets written out (Thm 3.1).  Any V: a shift of the logits changes nothing, logits and temperature scaled
+    together change nothing, equal logits give alpha* = 1, and the result equals that of the softmaxed rows."""
+    rng = np.random.default_rng(81)
+    for _ in range(40):
+        a, b, c, d = rng.normal(0, 2, size=4)
+        T = float(rng.uniform(0.3, 2.0)); n = int(rng.integers(1, 6))
+        sol, p, q = G.solve_row_from_logits([a, b], [c, d], T, n, tol=0.0)
+        p1 = 1.0 / (1.0 + math.exp((b - a) / T)); q1 = 1.0 / (1.0 + math.exp((d - c) / T))
+        assert abs(p[0] - p1) < 1e-14 and abs(q[0] - q1) < 1e-14
+        expect = 1.0 + min(0.0, p1 - q1 ** n, (1.0 - p1) - (1.0 - q1) ** n)
+        assert abs(sol.alpha_star - expect) < 1e-12, (a, b, c, d, T, n)
+    for _ in range(10):
+        V = int(rng.integers(5, 40)); n = int(rng.integers(2, 5)); k = int(rng.integers(2, V))
+        tl = 3.0 * rng.standard_normal(V); dl = 0.8 * tl + rng.standard_normal(V); T = float(rng.uniform(0.5, 1.5))
+        base, p, q = G.solve_row_from_logits(tl, dl, T, n, k, tol=1e-9)
+        shifted, _, _ = G.solve_row_from_logits(tl + 7.25, dl - 3.5, T, n, k, tol=1e-9)
+        scaled, _, _ = G.solve_row_from_logits(2.0 * tl, 2.0 * dl, 2.0 * T, n, k, tol=1e-9)
+        direct = G.solve_row(p, q, n, k, tol=1e-9)
+        for other in (shifted, scaled, direct):
+            assert abs(other.alpha_star - base.alpha_star) < 1e-12 and np.array_equal(other.order, base.order)
+            assert np.abs(other.w - base.w).max() <= 1e-7 * max(1.0, np.abs(base.w).max())
+        same, _, _ = G.solve_row_from_logits(tl, tl, T, n, 0, tol=0.0)
+        assert abs(same.alpha_star - 1.0) < 1e-12
+        assert sorted(int(t) for t in base.order) == sorted(int(t) for t in np.argsort(-dl, kind="stable")[:k])   # top-k of q = top-k of the draft logits
