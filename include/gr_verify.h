@@ -46,6 +46,7 @@ typedef struct gr_handle_s* gr_handle;
 #define GR_ESTATE       (-3)   /* gr_verify / gr_policy_* before a successful gr_solve */
 #define GR_EHIP         (-4)   /* a HIP runtime call failed */
 #define GR_EUNSUPPORTED (-5)   /* V >= 2^24 with a support above GR_MAX_SUPPORT; dense export of such a policy */
+#define GR_ECAPACITY    (-6)   /* more rows than the fixed scratch of gr_accept_sweep_noalloc holds */
 
 /* per-row status written by gr_solve */
 #define GR_ROW_OK         0
@@ -114,6 +115,21 @@ int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float to
 #define GR_SWEEP_MAX_DRAFTS  64
 int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
                     int B, int V, float* accept_prob, int* status, void* hip_stream);
+
+/*
+ * gr_accept_sweep for callers that cannot allocate device memory or create a handle: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and arithmetic as
+ * gr_accept_sweep, without the handle; the selection scratch (candidate keys and partial sums, 16.2 KB per row)
+ * is a fixed array in the library's device image, so B is limited to GR_NOALLOC_MAX_B rows (GR_ECAPACITY
+ * beyond; 4.2 MB per GPU, held until the process ends).  The call allocates nothing, frees nothing and does
+ * not synchronise.  The array's address on the current device is looked up on the first call on that device
+ * (and by any gr_create on it): make that first call outside a graph capture.  Every call on a GPU uses
+ * that GPU's one array: calls that overlap in time on one GPU race, whatever their streams.  Nothing in the
+ * array needs clearing between calls (every entry a call reads was written by that call).
+ */
+#define GR_NOALLOC_MAX_B 256
+int gr_accept_sweep_noalloc(const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
+                            int B, int V, float* accept_prob, int* status, void* hip_stream);
 
 /*
  * drafts   [B, n] int32 token ids drawn from the top-k renormalised q rows.

@@ -16,9 +16,10 @@ GR_MAX_SUPPORT = 256
 GR_MAX_T = 128
 GR_MAX_N = 16
 GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
-GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED, GR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
+GR_NOALLOC_MAX_B = 256
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_accept_sweep", "gr_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -52,6 +53,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_destroy.argtypes = [vp]
     lib.gr_solve.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
+    lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
@@ -142,6 +144,24 @@ def gr_accept_sweep(handle: int, p: torch.Tensor, q: torch.Tensor, ks, ns,
                                         _stream(stream))
     if rc != GR_OK:
         raise GrError(rc, "gr_accept_sweep")
+    return accept_prob, status
+
+
+def gr_accept_sweep_noalloc(p: torch.Tensor, q: torch.Tensor, ks, ns, accept_prob: torch.Tensor, status: torch.Tensor, stream=None):
+    """gr_accept_sweep without a handle and without any allocation: the caller passes every buffer
+    (accept_prob [B, len(ks), len(ns)] float32, status [B] int32); at most GR_NOALLOC_MAX_B rows."""
+    if p.dim() != 2 or p.shape != q.shape:
+        raise TypeError("gr_accept_sweep_noalloc: p and q must both be [B, V]")
+    B, V = p.shape
+    ks = [int(k) for k in ks]; ns = [int(n) for n in ns]
+    if tuple(accept_prob.shape) != (B, len(ks), len(ns)) or tuple(status.shape) != (B,):
+        raise TypeError("gr_accept_sweep_noalloc: accept_prob must be [B, len(ks), len(ns)] and status [B]")
+    ka = (ctypes.c_int * len(ks))(*ks); na = (ctypes.c_int * len(ns))(*ns)
+    rc = load_library().gr_accept_sweep_noalloc(_ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), ka, len(ks), na, len(ns),
+                                                B, V, _ptr(accept_prob, torch.float32, "accept_prob"),
+                                                _ptr(status, torch.int32, "status"), _stream(stream))
+    if rc != GR_OK:
+        raise GrError(rc, "gr_accept_sweep_noalloc")
     return accept_prob, status
 
 

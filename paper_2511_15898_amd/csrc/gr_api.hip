@@ -109,7 +109,34 @@ int prepare_full(gr_handle h, int B, int V) {
 
 }  // namespace
 
+// ---- allocation-free sweep: the selection scratch lives in the device image.
 namespace {
+
+constexpr size_t kNoAllocRows = GR_NOALLOC_MAX_B;
+constexpr size_t kNaCand = 0;                                                                  // u64 [rows, kMaxSplits, kMaxSupport]
+constexpr size_t kNaPsum = kNaCand + kNoAllocRows * kMaxSplits * kMaxSupport * sizeof(unsigned long long);   // f64 [rows, kMaxSplits]
+constexpr size_t kNaQsum = kNaPsum + kNoAllocRows * kMaxSplits * sizeof(double);              // f64 [rows, kMaxSplits]
+constexpr size_t kNaCount = kNaQsum + kNoAllocRows * kMaxSplits * sizeof(double);             // i32 [rows, kMaxSplits]
+constexpr size_t kNaBad = kNaCount + kNoAllocRows * kMaxSplits * sizeof(int);                 // i32 [rows, kMaxSplits]
+constexpr size_t kNaBytes = kNaBad + kNoAllocRows * kMaxSplits * sizeof(int);
+
+static __device__ __align__(256) unsigned char scratch[kNaBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each GPU, looked up once per device
+
+// The address of this device's copy of `scratch` (host code must never pass the array's name to a kernel).
+int scratch_address(unsigned char** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GR_EHIP;
+    void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return GR_EHIP; }
+        __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);      // every thread finds the same address
+    }
+    *out = static_cast<unsigned char*>(ptr);
+    return GR_OK;
+}
 
 // Argument checks and grid of a sweep, shared by both entry points.
 int fill_sweep(SweepParams& sw, const int* ks, int nk, const int* ns, int nn, int V) {
@@ -149,6 +176,7 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int ma
     }
     if (hipGetDevice(&h->device) != hipSuccess) { delete h; return GR_EHIP; }
     if (solve_kernel_setup() != hipSuccess) { delete h; return GR_EHIP; }
+    { unsigned char* na = nullptr; (void)scratch_address(&na); }      // so that gr_accept_sweep_noalloc finds its array later
     const size_t rows = static_cast<size_t>(max_B);
     bool ok = dev_alloc(&h->cand, rows * kMaxSplits * kMaxSupport) && dev_alloc(&h->cand_count, rows * kMaxSplits) &&
               dev_alloc(&h->part_psum, rows * kMaxSplits) && dev_alloc(&h->part_qsum, rows * kMaxSplits) &&
@@ -252,6 +280,34 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
     sw.p = p; sw.splits = splits;
     sw.cand = h->cand; sw.cand_count = h->cand_count; sw.part_psum = h->part_psum; sw.part_qsum = h->part_qsum;
     sw.part_bad = h->part_bad; sw.accept_prob = accept_prob; sw.status = status;
+    if (launch_sweep(sw, B, stream) != hipSuccess) return GR_EHIP;
+    return GR_OK;
+}
+
+extern "C" int gr_accept_sweep_noalloc(const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
+                                       int B, int V, float* accept_prob, int* status, void* hip_stream) {
+    if (!p || !q || !ks || !ns || !accept_prob || !status || B <= 0 || V <= 0) return GR_EINVAL;
+    if (static_cast<size_t>(B) > kNoAllocRows) return GR_ECAPACITY;
+    SweepParams sw;
+    const int rc = fill_sweep(sw, ks, nk, ns, nn, V);
+    if (rc != GR_OK) return rc;
+    unsigned char* base = nullptr;
+    const int rs = scratch_address(&base);
+    if (rs != GR_OK) return rs;
+    unsigned long long* cand = reinterpret_cast<unsigned long long*>(base + kNaCand);
+    double* psum = reinterpret_cast<double*>(base + kNaPsum);
+    double* qsum = reinterpret_cast<double*>(base + kNaQsum);
+    int* count = reinterpret_cast<int*>(base + kNaCount);
+    int* bad = reinterpret_cast<int*>(base + kNaBad);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int splits = choose_splits(B, V);
+    int slice_len = (V + splits - 1) / splits;
+    slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;
+    launch_select(p, q, B, V, sw.kmax, splits, slice_len, cand, count, psum, qsum, bad, nullptr, 0, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    sw.p = p; sw.splits = splits;
+    sw.cand = cand; sw.cand_count = count; sw.part_psum = psum; sw.part_qsum = qsum; sw.part_bad = bad;
+    sw.accept_prob = accept_prob; sw.status = status;
     if (launch_sweep(sw, B, stream) != hipSuccess) return GR_EHIP;
     return GR_OK;
 }
@@ -393,6 +449,7 @@ extern "C" const char* gr_strerror(int code) {
         case GR_ESTATE: return "no solved policy in this handle";
         case GR_EHIP: return "HIP runtime error";
         case GR_EUNSUPPORTED: return "a vocabulary of 2^24 tokens or more with a support above GR_MAX_SUPPORT, or a dense export of such a policy";
+        case GR_ECAPACITY: return "more rows than GR_NOALLOC_MAX_B, the fixed capacity of the allocation-free entry point";
         default: return "unknown error";
     }
 }
