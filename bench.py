@@ -136,6 +136,8 @@ def main():
                     help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    ap.add_argument("--tail-mass", type=float, default=0.0,
+                    help="nucleus cut of the draft (gr_config.tail_mass) for workloads without a top-k; 0: none")
     ap.add_argument("--streams", type=int, default=3,
                     help="handles / HIP streams the steps of the second timed region are dealt to (1: skip that region); "
                          "three of them plus the default stream fill the four hardware queues of a process")
@@ -161,7 +163,7 @@ def main():
     d = torch.from_numpy(wl.drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)
     acc = torch.empty(wl.B, dtype=torch.float32, device=dev); st = torch.empty(wl.B, dtype=torch.int32, device=dev)
     tok = torch.empty(wl.B, dtype=torch.int32, device=dev); ok = torch.empty(wl.B, dtype=torch.uint8, device=dev)
-    h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, flags=0 if args.no_events else gr.GR_FLAG_PROFILE)
+    h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, flags=0 if args.no_events else gr.GR_FLAG_PROFILE, tail_mass=args.tail_mass)
 
     def step():
         gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
@@ -207,7 +209,7 @@ def main():
     ns = max(1, min(args.streams, 8))
     pipelined = None
     if ns > 1:
-        hs = [gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n) for _ in range(ns)]
+        hs = [gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, tail_mass=args.tail_mass) for _ in range(ns)]
         ss = [torch.cuda.Stream() for _ in range(ns)]
         outs = [(torch.empty_like(acc), torch.empty_like(st), torch.empty_like(tok), torch.empty_like(ok)) for _ in range(ns)]
         ins = [(p, q)] + [(p.clone(), q.clone()) for _ in range(ns - 1)]      # every stream reads its own copy of the batch
@@ -297,7 +299,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
-                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "streams": 1},
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "streams": 1},
         "step_events": step_events,
         "pipelined": pipelined,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],

@@ -35,14 +35,29 @@ STATUS_OK, STATUS_TRUNC_CAP, STATUS_ITER_CAP, STATUS_BAD_ROW = 0, 1, 2, 3
 
 
 # --------------------------------------------------------------------------- steps 1-4
-def topk_support(q, k):
+def topk_support(q, k, tail_mass=0.0):
     """Tokens V_0 that top-k draft sampling can emit (App. "Top-k Sampling ..."): the k
-    largest q (ties: lower token id), or every token with q > 0 when k <= 0 or k >= V."""
+    largest q (ties: lower token id), or every token with q > 0 when k <= 0 or k >= V.
+    With tail_mass > 0 the support is also cut to a nucleus (App. A, first paragraph: top-p
+    sampling, like top-k, only changes how q is computed): tokens are taken by decreasing q
+    (ties: lower token id) until their running sum -- float64, added one after the other in
+    that order -- reaches (1 - tail_mass) times the float64 row sum of q.  The tokens left
+    out carry at most tail_mass of the draw mass, so n draws avoid them with probability
+    at least 1 - n tail_mass: as an approximation of the uncut draft this moves alpha* and
+    the coupling by at most n tail_mass in total variation."""
     q = np.asarray(q)
     pos = [i for i in range(q.shape[0]) if q[i] > 0]
-    if 0 < k < q.shape[0] and len(pos) > k:
+    cut_k = 0 < k < q.shape[0] and len(pos) > k
+    if cut_k or tail_mass > 0:
         pos.sort(key=lambda i: (-float(q[i]), i))
+    if cut_k:
         pos = pos[:k]
+    if tail_mass > 0:
+        need = (1.0 - float(tail_mass)) * float(np.sum(q, dtype=np.float64))
+        run = np.cumsum(np.array([float(q[i]) for i in pos]))          # sequential float64 sums
+        reached = np.flatnonzero(run >= need)
+        if reached.size:
+            pos = pos[: int(reached[0]) + 1]
     return sorted(pos)
 
 
@@ -376,8 +391,9 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
 
 
 # ----------------------------------------------------------------------- the row solve
-def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
-    """Alg. 1 lines 1-2 and both convex programs, for one decode position.
+def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11, tail_mass=0.0):
+    """Alg. 1 lines 1-2 and both convex programs, for one decode position (tail_mass: the nucleus cut of
+    topk_support).
 
     Readings where the paper is silent:
       * "minimal T" (Alg. 1): the fewest tokens, taken by decreasing q (ties lower id),
@@ -407,7 +423,7 @@ def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
     if bad:
         return RowSolution(V, n, np.zeros(0, int), {}, *(np.zeros(0),) * 4, np.zeros(1), np.zeros(1), 0, float("nan"),
                            np.zeros(0), np.zeros(0), np.zeros(0, int), [], np.zeros(0), STATUS_BAD_ROW)
-    support = topk_support(q, k)
+    support = topk_support(q, k, tail_mass)
     order = ratio_order(p, q, support)
     kk = len(order)
     p_total = float(np.sum(p, dtype=np.float64))   # float32 rows sum to 1 only to rounding

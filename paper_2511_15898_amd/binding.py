@@ -26,7 +26,7 @@ GR_FLAG_PROFILE = 1
 
 class GrConfig(ctypes.Structure):
     _fields_ = [("max_iter", ctypes.c_int), ("max_T", ctypes.c_int), ("rel_tol", ctypes.c_double),
-                ("flags", ctypes.c_int)]
+                ("flags", ctypes.c_int), ("tail_mass", ctypes.c_double)]
 
 
 class GrError(RuntimeError):
@@ -86,10 +86,10 @@ def _stream(stream) -> int:
 
 
 def gr_create(max_B: int, max_V: int, max_k: int = GR_MAX_SUPPORT, max_n: int = GR_MAX_N, max_iter: int = 0, max_T: int = 0,
-              rel_tol: float = 0.0, flags: int = 0) -> int:
+              rel_tol: float = 0.0, flags: int = 0, tail_mass: float = 0.0) -> int:
     """max_k: largest top-k support the handle will serve (<= 0: whole rows; above GR_MAX_SUPPORT the handle
-    holds an HBM workspace of 128 bytes per token and row)."""
-    cfg = GrConfig(max_iter, max_T, rel_tol, flags)
+    holds an HBM workspace of 128 bytes per token and row).  tail_mass: nucleus cut of the draft on that path."""
+    cfg = GrConfig(max_iter, max_T, rel_tol, flags, tail_mass)
     h = ctypes.c_void_p()
     rc = load_library().gr_create(ctypes.byref(h), max_B, max_V, max_k, max_n, ctypes.byref(cfg))
     if rc != GR_OK:

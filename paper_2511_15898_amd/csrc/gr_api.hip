@@ -13,6 +13,7 @@ struct gr_handle_s {
     int max_n = GR_MAX_N;
     int max_iter = 1000, max_T = GR_MAX_T;
     double rel_tol = 1e-8;
+    double tail_mass = 0.0;        // nucleus cut of the draft on the HBM-resident path
     int device = 0;
     // scratch of the select kernel
     unsigned long long* cand = nullptr; int* cand_count = nullptr;
@@ -173,6 +174,8 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int ma
         if (cfg->max_iter > 0) h->max_iter = cfg->max_iter;
         if (cfg->max_T > 0 && cfg->max_T <= GR_MAX_T) h->max_T = cfg->max_T;
         if (cfg->rel_tol > 0.0) h->rel_tol = cfg->rel_tol;
+        if (!(cfg->tail_mass >= 0.0) || !(cfg->tail_mass < 1.0)) { delete h; return GR_EINVAL; }
+        h->tail_mass = cfg->tail_mass;
     }
     if (hipGetDevice(&h->device) != hipSuccess) { delete h; return GR_EHIP; }
     if (solve_kernel_setup() != hipSuccess) { delete h; return GR_EHIP; }
@@ -219,6 +222,7 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
     if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
+    if (k_eff <= kMaxSupport && h->tail_mass > 0.0) return GR_EUNSUPPORTED;   // the nucleus cut is for the HBM-resident path
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (k_eff > kMaxSupport) {
         // a support above GR_MAX_SUPPORT (no top-k, or a large one): the HBM-resident path
@@ -228,7 +232,7 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         if (rc != GR_OK) return rc;
         FullParams& f = h->full;
         f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.k = k_eff; f.max_T = h->max_T; f.max_iter = h->max_iter;
-        f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol;
+        f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol; f.tail_mass = h->tail_mass;
         f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
         mark(h, 0, stream);
         launch_full_prologue(f, stream);

@@ -215,6 +215,10 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     __shared__ SortLds S;
     __shared__ double red[kWaves];
     __shared__ int wtot[4 * kWaves];
+    __shared__ double dscan[kThreads];
+    __shared__ double xin[kThreads];
+    __shared__ double xout[kThreads + 1];
+    __shared__ int bsel;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
     const int V = fp.V;
     const size_t vs = static_cast<size_t>(V) + 2;
@@ -236,19 +240,62 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
         if (tid == 0) mark_bad(fp, row, ptot, qtot);
         return;
     }
-    // With a top-k below the number of positive entries: order the positive entries by decreasing q
-    // (ties by token id) and flag the first k of them; the support is then the flagged tokens.
+    // With a top-k below the number of positive entries, or a nucleus cut (tail_mass > 0; Sec. 5.1: top-p/k
+    // sampling of the draft restricts the domain): order the candidates by decreasing q (ties by token id)
+    // and flag the first k' of them; the support is then the flagged tokens.
     int* member = fp.flag + row * vs;                       // by token id here; reused by rank later
     bool by_flag = false;
-    if (fp.k < V) {
+    const bool cut = fp.tail_mass > 0.0;
+    if (fp.k < V || cut) {
+        // Nucleus cut: tokens are taken by decreasing q until their running sum reaches (1 - tail_mass) qtot.
+        // Candidates first, so that only they are sorted: half of the budget tail_mass qtot goes to the tokens
+        // below qmin = budget / (2 V) (fewer than V of them: below budget / 2 together), the other half to the
+        // lowest occupied magnitude classes (exponent and four mantissa bits of q: every member is below the
+        // class's upper edge, so count x edge bounds the class's mass).  Everything dropped here lies in the
+        // tail that the exact walk below would leave out anyway.
+        double qmin = 0.0; int bstar = 0;
+        if (cut) {
+            int* chist = reinterpret_cast<int*>(&S.wcnt[0][0][0]);          // 4096 classes = the sort's 16 KB of counters
+            static_assert(sizeof(S.wcnt) >= 4096 * sizeof(int), "the class histogram borrows the sort's counters");
+            for (int c = tid; c < 4096; c += kThreads) chist[c] = 0;
+            __syncthreads();
+            const double budget = fp.tail_mass * qtot;
+            qmin = 0.5 * budget / static_cast<double>(V);
+            for (int i = tid; i < V; i += kThreads) {
+                const float qv = qr[i];
+                if (static_cast<double>(qv) >= qmin && qv > 0.f) atomicAdd(&chist[__float_as_uint(qv) >> 19], 1);
+            }
+            __syncthreads();
+            // thread t owns classes 16 t .. 16 t + 15; prefix of the mass bounds over the threads, serially by thread 0
+            double local = 0.0;
+            for (int c = 16 * tid; c < 16 * tid + 16; ++c)
+                local += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
+            dscan[tid] = local;
+            if (tid == 0) bsel = 4096;
+            __syncthreads();
+            if (tid == 0) { double run = 0.0; for (int t = 0; t < kThreads; ++t) { const double v = dscan[t]; dscan[t] = run; run += v; } }
+            __syncthreads();
+            {
+                double run = dscan[tid];                             // bound on the mass of all classes below 16 tid
+                for (int c = 16 * tid; c < 16 * tid + 16; ++c) {
+                    run += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
+                    if (run > 0.5 * budget) { atomicMin(&bsel, c); break; }    // class c cannot be dropped whole
+                }
+            }
+            __syncthreads();
+            bstar = bsel;                                            // 4096: every class fits the budget (degenerate; keep all)
+            if (bstar == 4096) bstar = 0;
+            __syncthreads();
+        }
         int cnt = 0;
         for (int t0 = 0; t0 < V; t0 += 4 * kThreads) {           // 1024 tokens per round
-            float qv[4]; unsigned long long mask[4];
+            float qv[4]; unsigned long long mask[4]; bool take[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) { const int i = t0 + j * kThreads + tid; qv[j] = i < V ? qr[i] : 0.f; }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                mask[j] = __ballot(qv[j] > 0.f);
+                take[j] = qv[j] > 0.f && (!cut || (static_cast<double>(qv[j]) >= qmin && static_cast<int>(__float_as_uint(qv[j]) >> 19) >= bstar));
+                mask[j] = __ballot(take[j]);
                 if (lane == 0) wtot[j * kWaves + wv] = __popcll(mask[j]);
             }
             __syncthreads();
@@ -262,7 +309,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = t0 + j * kThreads + tid;
-                if (qv[j] > 0.f) {
+                if (take[j]) {
                     const int off = cnt + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
                     k0[off] = static_cast<unsigned long long>(~__float_as_uint(qv[j]));   // ties: the sort is stable and this is token order
                     v0[off] = i;
@@ -272,10 +319,33 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
             cnt += run;
             __syncthreads();
         }
-        if (cnt > fp.k) {
+        if (cnt > fp.k || (cut && cnt > 0)) {
             const int res = block_radix_sort(k0, v0, k1, v1, cnt, S);
             const int* sorted = res ? v1 : v0;
-            for (int r = tid; r < fp.k; r += kThreads) member[sorted[r]] = 1;
+            int keep = cnt;
+            if (cut) {
+                // the exact walk: running sums of q in the sorted order, added one after the other (wave 0), until
+                // they reach (1 - tail_mass) qtot; the first rank that does is the last token of the support
+                const double need = (1.0 - fp.tail_mass) * qtot;
+                double carry = 0.0;
+                if (tid == 0) bsel = cnt;                                // rank of the last kept token; cnt: never reached
+                __syncthreads();
+                for (int t0 = 0; t0 < cnt; t0 += kThreads) {
+                    const int r = t0 + tid;
+                    xin[tid] = r < cnt ? static_cast<double>(qr[sorted[r]]) : 0.0;
+                    __syncthreads();
+                    if (wv == 0) wave_sequential_scan_padded(xin, xout, kThreads, carry);
+                    __syncthreads();
+                    if (r < cnt && xout[tid + 1] >= need) atomicMin(&bsel, r);
+                    carry = xout[kThreads];
+                    __syncthreads();
+                    if (bsel < cnt) break;                               // uniform: read behind the barrier
+                }
+                keep = bsel < cnt ? bsel + 1 : cnt;
+                __syncthreads();
+            }
+            if (fp.k < keep) keep = fp.k;
+            for (int r = tid; r < keep; r += kThreads) member[sorted[r]] = 1;
             by_flag = true;
         }
         __syncthreads();

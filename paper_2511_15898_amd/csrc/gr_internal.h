@@ -59,6 +59,7 @@ struct FullParams {
     int B, V, n, max_T, max_iter;
     int k;             // top-k on q (V: none)
     double tau, rel_tol;
+    double tail_mass;  // nucleus cut of the draft: share of the draw mass that may be left out (0: none)
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p
     int* byq;          // ranks by (inside H* first, decreasing q, token id)

@@ -8,7 +8,7 @@ ABS_TOL = 1e-5          # spec tolerance on alpha* and on every policy ent
 EDGE_TOL = 1e-5         # a uniform this close to a CDF edge may fall either way
 
 
-def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=None, export_rows=None):
+def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=None, export_rows=None, tail_mass=0.0):
     """Run the HIP path.  A policy over more than GR_MAX_SUPPORT tokens (no top-k on a large V, or a large top-k) has no
     dense export: its rows listed in `export_rows` are fetched one by one into out["rows"]."""
     import torch
@@ -18,7 +18,7 @@ def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=N
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     d = torch.from_numpy(wl.drafts if drafts is None else drafts).to(dev)
     u = torch.from_numpy(wl.uniforms).to(dev)
-    h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, max_iter=max_iter, max_T=max_T, rel_tol=rel_tol)
+    h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, max_iter=max_iter, max_T=max_T, rel_tol=rel_tol, tail_mass=tail_mass)
     try:
         acc, st = gr.gr_solve(h, p, q, wl.n, wl.k, tol)
         tok, ok = gr.gr_verify(h, d, u)
@@ -94,7 +94,7 @@ def check_row_validity(wl, out, b, drafts, alpha_star):
             assert abs(acc - alpha_star) < ABS_TOL, (b, acc, alpha_star)
 
 
-def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None, max_edge_frac=0.05):
+def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None, max_edge_frac=0.05, tail_mass=0.0):
     """Element-by-element comparison with the CPU checker on `rows`.  Rows the checker flags as fragile
     (several optimal H* within rounding) are compared on alpha* and on everything that holds for any
     correct result (check_row_validity).  Returns statistics; at most max_edge_frac of the rows (and
@@ -106,7 +106,10 @@ def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None, max_ed
     stats = {"rows": 0, "fragile": 0, "edge": 0, "max_dacc": 0.0, "max_dpi": 0.0, "inner_programs": 0, "outer_programs": 0,
              "solved_rows": 0}
     for b in rows:
-        sol = G.solve_row(wl.p[b], wl.q[b], wl.n, wl.k, tol=tol, max_T=max_T, max_iter=max_iter)
+        sol = G.solve_row(wl.p[b], wl.q[b], wl.n, wl.k, tol=tol, max_T=max_T, max_iter=max_iter, tail_mass=tail_mass)
+        if tail_mass > 0 and sol.status != G.STATUS_BAD_ROW and not all(int(t) in sol.pos_of for t in drafts[b]):
+            stats["skipped"] = stats.get("skipped", 0) + 1      # a draft from the cut tail: not a draw of the cut draft
+            continue
         tok, accepted, pi, acc_given, edge = G.verify_row(sol, wl.p[b], drafts[b], wl.uniforms[b])
         stats["rows"] += 1
         assert abs(out["accept_prob"][b] - sol.alpha_star) < ABS_TOL, (b, out["accept_prob"][b], sol.alpha_star)
@@ -160,11 +163,11 @@ def rows_with_outer_programs(wl, candidates, tol, want=2):
     return found
 
 
-def check_alpha_all_rows(wl, out):
+def check_alpha_all_rows(wl, out, rows=None, tail_mass=0.0):
     """alpha* needs no convex solve (Sec. 6, step 1): cheap enough to check on every row."""
     from oracle import gr_oracle as G
-    for b in range(wl.B):
-        sup = G.topk_support(wl.q[b], wl.k)
+    for b in (range(wl.B) if rows is None else rows):
+        sup = G.topk_support(wl.q[b], wl.k, tail_mass)
         order = G.ratio_order(wl.p[b], wl.q[b], sup)
         pt = float(np.sum(wl.p[b], dtype=np.float64))
         _, _, F = G.prefix_psi(wl.p[b][order].astype(np.float64) / pt, wl.q[b][order], wl.n)

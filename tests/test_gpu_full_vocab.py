@@ -150,3 +150,46 @@ def test_top_k_above_the_lds_capacity(V, n, k, tol):
     check_alpha_all_rows(wl, out)
     stats = compare_rows(wl, out, range(wl.B), tol)
     assert stats["rows"] == wl.B
+
+
+@pytest.mark.parametrize("V,n,k,tail_mass,tol", [(5000, 4, 0, 1e-6, 1e-4), (5000, 2, 0, 1e-3, 1e-4), (3000, 8, 0, 1e-4, 1e-3),
+                                                 (5000, 4, 300, 1e-3, 1e-4), (777, 3, 0, 0.05, 1e-3)])
+def test_nucleus_cut_of_the_draft(V, n, k, tail_mass, tol):
+    """gr_config.tail_mass (Sec. 5.1 / App. A: top-p sampling of the draft restricts the domain): every row
+    against the checker with the same cut -- support size, order, blocks, programs, slice, token -- and
+    alpha* against the uncut run within n * tail_mass."""
+    from oracle import gr_oracle as G
+    wl = W.llm_shaped(B=24, V=V, n=n, k=k, seed_sub=60 + n)
+    out = run_gpu(wl, tol, export_rows=range(wl.B), tail_mass=tail_mass)
+    check_alpha_all_rows(wl, out, tail_mass=tail_mass)
+    for b in range(wl.B):
+        assert out["support"][b] == len(G.topk_support(wl.q[b], k, tail_mass)), b
+    stats = compare_rows(wl, out, range(wl.B), tol, tail_mass=tail_mass)
+    assert stats["rows"] + stats.get("skipped", 0) == wl.B and stats["rows"] >= wl.B // 2 and stats["fragile"] < wl.B
+    uncut = run_gpu(wl, tol, want_slice=False)
+    assert np.all(np.abs(out["accept_prob"] - uncut["accept_prob"]) <= n * tail_mass + 2e-6)
+    assert np.any(out["support"] < uncut["support"])            # the cut dropped tokens
+
+
+def test_nucleus_cut_on_the_stress_cell_at_full_batch():
+    """Config 5, 'top-k = full V', n = 8, B = 1024 at V = 128256 with tail_mass = 1e-8 (alpha* within 8e-8 of the
+    uncut value): the supports shrink to what the checker orders in milliseconds, so alpha* is checked on
+    every 4th row, 24 rows are compared in full (near-identical rows among them), rows with programs must
+    be there, and four rows are held against the uncut checker."""
+    from oracle import gr_oracle as G
+    tm = 1e-8
+    wl = W.stress(B=1024, n=8, k=0, seed_sub=908)
+    near = [int(x) for x in np.flatnonzero(wl.meta["near"])[:6]]
+    rows = sorted(set(range(5, wl.B, 57)) | set(near))
+    out = run_gpu(wl, 1e-4, want_slice=False, export_rows=rows, tail_mass=tm)
+    check_alpha_all_rows(wl, out, rows=range(0, wl.B, 4), tail_mass=tm)
+    stats = compare_rows(wl, out, rows, 1e-4, tail_mass=tm)
+    assert stats["rows"] >= len(rows) - 1 and stats["solved_rows"] >= 4, stats
+    solved = (out["status"] == 0) & (out["iterations"] > 0)
+    assert solved.sum() >= wl.B // 20, int(solved.sum())
+    assert np.median(out["support"]) < wl.V // 4 and out["support"].min() >= 1
+    for b in rows[:4]:
+        order = G.ratio_order(wl.p[b], wl.q[b], G.topk_support(wl.q[b], 0))
+        pt = float(np.sum(wl.p[b], dtype=np.float64))
+        _, _, F = G.prefix_psi(wl.p[b][order].astype(np.float64) / pt, wl.q[b][order], wl.n)
+        assert abs(out["accept_prob"][b] - (1.0 + F.min())) <= wl.n * tm + 2e-6

@@ -455,3 +455,45 @@ def test_logits_front_end_against_closed_forms_and_invariances():
         same, _, _ = G.solve_row_from_logits(tl, tl, T, n, 0, tol=0.0)
         assert abs(same.alpha_star - 1.0) < 1e-12
         assert sorted(int(t) for t in base.order) == sorted(int(t) for t in np.argsort(-dl, kind="stable")[:k])   # top-k of q = top-k of the draft logits
+
+
+# ------------------------------------------------------------------ nucleus cut of the draft
+def test_nucleus_cut_is_the_smallest_prefix_by_mass_and_costs_at_most_n_tail_mass():
+    """Sec. 5.1 / App. A: top-p sampling of the draft restricts the domain like top-k.  The cut support is
+    checked against the definition in exact rational arithmetic (the fewest tokens by decreasing q, ties to
+    the lower id, whose mass reaches 1 - tail_mass of the row); with tail_mass = 0 nothing changes; the
+    cut draft is the relaxed OTLP of the renormalised nucleus (LP over the full V); and against the uncut
+    draft alpha* moves by at most n * tail_mass (n draws avoid the dropped tokens with at least that
+    probability); drafts are then drawn from the cut, renormalised draft, under which the marginal is p."""
+    from fractions import Fraction
+    checked = cut_rows = 0
+    for i, (p, q) in enumerate(_random_rows(77, 40, 7, alphas=(0.05, 0.1, 0.3), mix=False)):
+        n = 2 + i % 2
+        assert G.topk_support(q, 0, 0.0) == G.topk_support(q, 0)
+        for delta in (1e-3, 3e-2, 0.2):
+            sup = G.topk_support(q, 0, delta)
+            ranked = sorted((j for j in range(7) if q[j] > 0), key=lambda j: (-Fraction(float(q[j])), j))
+            total = sum(Fraction(float(x)) for x in q)
+            need = (1 - Fraction(delta)) * total
+            run, want = Fraction(0), []
+            for j in ranked:
+                want.append(j); run += Fraction(float(q[j]))
+                if run >= need:
+                    break
+            # float64 running sums against exact ones: only a mass within rounding of the threshold could differ
+            margin = min(abs(sum(Fraction(float(q[j])) for j in ranked[:c]) - need) for c in range(1, len(ranked) + 1))
+            if margin > Fraction(1, 10 ** 12):
+                assert sup == sorted(want), (i, delta)
+                checked += 1
+            cut_rows += len(sup) < len(ranked)
+            full = G.solve_row(p, q, n, 0, tol=0.0)
+            sol = G.solve_row(p, q, n, 0, tol=0.0, tail_mass=delta)
+            assert sol.status == G.STATUS_OK and sorted(int(t) for t in sol.order) == sup
+            dropped = float(sum(Fraction(float(q[j])) for j in range(7) if j not in sup) / total)
+            assert dropped <= delta + 1e-12
+            assert abs(sol.alpha_star - full.alpha_star) <= n * dropped + 1e-9, (i, delta, sol.alpha_star, full.alpha_star)
+            qq = np.zeros(7); qq[sup] = _norm64(q[sup])
+            assert abs(sol.alpha_star - brute.relaxed_otlp_value(_norm64(p), qq, n)) < 1e-7
+            marg, acc, norm = brute.coupling_marginals(lambda t: G.policy_slice(sol, p, t), qq, n)
+            assert norm < 1e-12 and np.abs(marg - _norm64(p)).sum() < 1e-6 and abs(acc - sol.alpha_star) < 1e-9
+    assert checked >= 100 and cut_rows >= 40          # the cut really dropped tokens
