@@ -105,6 +105,24 @@ int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float to
              int B, int V, float* accept_prob, int* status, void* hip_stream);
 
 /*
+ * gr_solve for rows given as logits (App. A, first paragraph: temperature and top-k sampling only change how p
+ * and q are computed from the models' logits; Sec. 5.1 for the order): p = softmax(target_logits / T),
+ * q = softmax(draft_logits / T) with one temperature per row, never written to memory.  One pass over both
+ * rows keeps the k largest draft logits (they are the k largest q; ties: lower token id) and the target's
+ * softmax normaliser (online, in float64); the supports' p and q are float64 exponentials, and every order the method needs is decided on the logits
+ * themselves: decreasing q/p is decreasing (draft - target) logit, exact for float32 logits.
+ *
+ * target_logits, draft_logits [B, V] float32 row-major, finite (a NaN or infinite entry gives GR_ROW_BAD).
+ * temperature [B] float32, positive and finite (GR_ROW_BAD otherwise).
+ * k           top-k on the draft, 1..GR_MAX_SUPPORT (also k <= 0 or k >= V when V <= GR_MAX_SUPPORT); a larger
+ *             support, or a handle with tail_mass > 0, gives GR_EUNSUPPORTED.
+ * Everything else as gr_solve.  target_logits and temperature must stay valid until the last gr_verify /
+ * gr_policy_slice on this solve: they stand in for the p row there.
+ */
+int gr_solve_logits(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
+                    int n, int k, float tol, int B, int V, float* accept_prob, int* status, void* hip_stream);
+
+/*
  * Acceptance-only sweep: alpha*(k, n) = 1 + min_H psi(H) (Thm 3.1; by the order of decreasing q/p
  * and the best prefix, Sec. 5.1) for every top-k size in ks and every number of i.i.d. drafts in ns,
  * from one streaming pass over p and q: the quantity of the paper's acceptance-versus-(k, n) study

@@ -35,7 +35,7 @@ STATUS_OK, STATUS_TRUNC_CAP, STATUS_ITER_CAP, STATUS_BAD_ROW = 0, 1, 2, 3
 
 
 # --------------------------------------------------------------------------- steps 1-4
-def topk_support(q, k, tail_mass=0.0):
+def topk_support(q, k, tail_mass=0.0, key=None):
     """Tokens V_0 that top-k draft sampling can emit (App. "Top-k Sampling ..."): the k
     largest q (ties: lower token id), or every token with q > 0 when k <= 0 or k >= V.
     With tail_mass > 0 the support is also cut to a nucleus (App. A, first paragraph: top-p
@@ -44,12 +44,15 @@ def topk_support(q, k, tail_mass=0.0):
     that order -- reaches (1 - tail_mass) times the float64 row sum of q.  The tokens left
     out carry at most tail_mass of the draw mass, so n draws avoid them with probability
     at least 1 - n tail_mass: as an approximation of the uncut draft this moves alpha* and
-    the coupling by at most n tail_mass in total variation."""
+    the coupling by at most n tail_mass in total variation.
+    key: values that rise and fall with q (the draft logits behind a softmax); when given, "by
+    decreasing q" is decided on them, so that two logits whose q round to one value keep their order."""
     q = np.asarray(q)
+    by = q if key is None else np.asarray(key)
     pos = [i for i in range(q.shape[0]) if q[i] > 0]
     cut_k = 0 < k < q.shape[0] and len(pos) > k
     if cut_k or tail_mass > 0:
-        pos.sort(key=lambda i: (-float(q[i]), i))
+        pos.sort(key=lambda i: (-float(by[i]), i))
     if cut_k:
         pos = pos[:k]
     if tail_mass > 0:
@@ -61,10 +64,15 @@ def topk_support(q, k, tail_mass=0.0):
     return sorted(pos)
 
 
-def ratio_order(p, q, support):
+def ratio_order(p, q, support, key=None):
     """Sec. 5.1: tokens in decreasing order of q(i)/p(i).  The comparison is done by
     cross-multiplication (exact in float64 for float32-valued inputs); p = 0 ranks
-    first; ties go to the lower token id."""
+    first; ties go to the lower token id.  key: values that rise and fall with q(i)/p(i)
+    (draft logit minus target logit behind two softmaxes at one temperature); when given the
+    order is taken on them."""
+    if key is not None:
+        return sorted(support, key=lambda i: (-float(key[i]), i))
+
     def before(a, b):
         lhs = float(q[a]) * float(p[b]); rhs = float(q[b]) * float(p[a])
         if lhs != rhs:
@@ -391,7 +399,7 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
 
 
 # ----------------------------------------------------------------------- the row solve
-def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11, tail_mass=0.0):
+def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11, tail_mass=0.0, ratio_key=None, q_key=None):
     """Alg. 1 lines 1-2 and both convex programs, for one decode position (tail_mass: the nucleus cut of
     topk_support).
 
@@ -423,8 +431,8 @@ def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11, tail_m
     if bad:
         return RowSolution(V, n, np.zeros(0, int), {}, *(np.zeros(0),) * 4, np.zeros(1), np.zeros(1), 0, float("nan"),
                            np.zeros(0), np.zeros(0), np.zeros(0, int), [], np.zeros(0), STATUS_BAD_ROW)
-    support = topk_support(q, k, tail_mass)
-    order = ratio_order(p, q, support)
+    support = topk_support(q, k, tail_mass, q_key)
+    order = ratio_order(p, q, support, ratio_key)
     kk = len(order)
     p_total = float(np.sum(p, dtype=np.float64))   # float32 rows sum to 1 only to rounding
     p_s = np.array([float(p[i]) / p_total for i in order])
@@ -453,6 +461,8 @@ def solve_row(p, q, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11, tail_m
     blocks = []
 
     def by_q(positions):
+        if q_key is not None:
+            return sorted(positions, key=lambda m: (-float(q_key[order[m]]), order[m]))
         return sorted(positions, key=lambda m: (-q_raw[m], order[m]))
 
     # ---- truncation sets (Alg. 1: minimal T with gamma_T <= tol, resp. epsilon_T <= tol)
@@ -525,11 +535,15 @@ def softmax_from_logits(logits, temperature=1.0):
 
 def solve_row_from_logits(target_logits, draft_logits, temperature, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
     """Alg. 1 for a decode position given by its target and draft logits and one sampling temperature: p and q are
-    the float64 softmaxes (top-k is then applied to q as in solve_row; the k largest logits are the k largest q).
+    the float64 softmaxes.  Every order the method needs is decided on the logits themselves, where it is exact
+    for float32 logits: q/p is proportional to exp((d - t) / T), so decreasing q/p is decreasing d - t (Sec. 5.1),
+    and decreasing q is decreasing d (top-k support, truncation sets); ties go to the lower token id.
     Returns (RowSolution, p, q)."""
     p = softmax_from_logits(target_logits, temperature)
     q = softmax_from_logits(draft_logits, temperature)
-    return solve_row(p, q, n, k, tol=tol, max_T=max_T, max_iter=max_iter, rtol=rtol), p, q
+    d64 = np.asarray(draft_logits, np.float64)
+    return solve_row(p, q, n, k, tol=tol, max_T=max_T, max_iter=max_iter, rtol=rtol,
+                     ratio_key=d64 - np.asarray(target_logits, np.float64), q_key=d64), p, q
 
 
 # ----------------------------------------------------------------- slice and sampling

@@ -20,6 +20,7 @@ struct gr_handle_s {
     double* part_psum = nullptr; double* part_qsum = nullptr; int* part_bad = nullptr;
     double* newton_ws = nullptr;   // [max_B, kMaxT * (kMaxT + 1)] Jacobian scratch of the solver's Newton fallback
     double* piece_psum = nullptr; int piece_stride = 0;   // float64 sums of p per 256 tokens, [max_B, piece_stride]
+    float* piece_pref = nullptr; float* part_pref = nullptr;   // rows given as logits: the references of the piece sums and of the slices' sums
     // policy object of the last solve
     int* order = nullptr; int* block = nullptr; double* weight = nullptr; double* rho = nullptr; double* pnorm = nullptr;
     RowInfo* info = nullptr;
@@ -50,7 +51,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->newton_ws, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->newton_ws, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -76,11 +77,11 @@ PolicyView policy_view(gr_handle h) {
         const FullParams& f = h->full;
         pv.order = f.order; pv.block = f.blk; pv.weight = f.weight; pv.rho = f.rho;
         pv.rank_of = f.rank_of; pv.rho_id = f.rho_id; pv.stride = static_cast<size_t>(h->V) + 2;
-        pv.piece_psum = nullptr; pv.piece_stride = 0;
+        pv.piece_psum = nullptr; pv.piece_stride = 0; pv.piece_pref = nullptr;
     } else {
         pv.order = h->order; pv.block = h->block; pv.weight = h->weight; pv.rho = h->rho;
         pv.rank_of = nullptr; pv.rho_id = nullptr; pv.stride = kMaxSupport;
-        pv.piece_psum = h->piece_psum; pv.piece_stride = h->piece_stride;
+        pv.piece_psum = h->piece_psum; pv.piece_stride = h->piece_stride; pv.piece_pref = h->piece_pref;
     }
     return pv;
 }
@@ -159,6 +160,37 @@ int fill_sweep(SweepParams& sw, const int* ks, int nk, const int* ns, int nn, in
     return GR_OK;
 }
 
+// The LDS-resident path of gr_solve (temperature == nullptr: p and q are probabilities) and of gr_solve_logits.
+int solve_in_lds(gr_handle h, const float* p, const float* q, const float* temperature, int n, int k_eff, float tol, int B, int V,
+                 float* accept_prob, int* status, hipStream_t stream) {
+    h->full_mode = false;
+    const int splits = choose_splits(B, V);
+    int slice_len = (V + splits - 1) / splits;
+    slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;
+    h->solved = false;
+    mark(h, 0, stream);
+    if (temperature)
+        launch_select_logits(p, q, temperature, B, V, k_eff, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
+                             h->part_bad, h->part_pref, h->piece_psum, h->piece_pref, h->piece_stride, stream);
+    else
+        launch_select(p, q, B, V, k_eff, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
+                      h->part_bad, h->piece_psum, h->piece_stride, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    mark(h, 1, stream);
+    SolveParams sp;
+    sp.p = p; sp.q = q; sp.B = B; sp.V = V; sp.n = n; sp.k = k_eff; sp.splits = splits;
+    sp.tau = static_cast<double>(tol); sp.rel_tol = h->rel_tol; sp.max_iter = h->max_iter; sp.max_T = h->max_T;
+    sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
+    sp.part_bad = h->part_bad;
+    sp.logits = temperature ? 1 : 0; sp.temperature = temperature; sp.part_pref = h->part_pref;
+    sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
+    sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status; sp.newton_ws = h->newton_ws;
+    if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
+    mark(h, 2, stream);
+    h->solved = true; h->p = p; h->B = B; h->V = V; h->n = n;
+    return GR_OK;
+}
+
 }  // namespace
 
 extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int max_n, const gr_config* cfg) {
@@ -188,7 +220,8 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int ma
               dev_alloc(&h->rho, rows * kMaxSupport) && dev_alloc(&h->pnorm, rows * kMaxSupport) &&
               dev_alloc(&h->info, rows);
     h->piece_stride = (max_V + kSelTile - 1) / kSelTile * (kSelTile / 256) + kMaxSplits * (kSelTile / 256);
-    ok = ok && dev_alloc(&h->piece_psum, rows * h->piece_stride);
+    ok = ok && dev_alloc(&h->piece_psum, rows * h->piece_stride) && dev_alloc(&h->piece_pref, rows * h->piece_stride) &&
+         dev_alloc(&h->part_pref, rows * kMaxSplits);
     ok = ok && dev_alloc(&h->newton_ws, rows * kMaxT * (kMaxT + 1));
     if (ok && k_cap > kMaxSupport) {
         // supports above GR_MAX_SUPPORT live in HBM: 128 bytes per token of max_V and row, held until gr_destroy
@@ -243,27 +276,20 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
         h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
         return GR_OK;
     }
-    h->full_mode = false;
-    const int splits = choose_splits(B, V);
-    int slice_len = (V + splits - 1) / splits;
-    slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;
-    h->solved = false;
-    mark(h, 0, stream);
-    launch_select(p, q, B, V, k_eff, splits, slice_len, h->cand, h->cand_count, h->part_psum, h->part_qsum,
-                  h->part_bad, h->piece_psum, h->piece_stride, stream);
-    if (hipGetLastError() != hipSuccess) return GR_EHIP;
-    mark(h, 1, stream);
-    SolveParams sp;
-    sp.p = p; sp.q = q; sp.B = B; sp.V = V; sp.n = n; sp.k = k_eff; sp.splits = splits;
-    sp.tau = static_cast<double>(tol); sp.rel_tol = h->rel_tol; sp.max_iter = h->max_iter; sp.max_T = h->max_T;
-    sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
-    sp.part_bad = h->part_bad;
-    sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
-    sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status; sp.newton_ws = h->newton_ws;
-    if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
-    mark(h, 2, stream);
-    h->solved = true; h->p = p; h->B = B; h->V = V; h->n = n;
-    return GR_OK;
+    return solve_in_lds(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+}
+
+/* Rows given as logits: see gr_verify.h. */
+extern "C" int gr_solve_logits(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
+                               int n, int k, float tol, int B, int V, float* accept_prob, int* status, void* hip_stream) {
+    if (!h || !target_logits || !draft_logits || !temperature || !accept_prob || !status) return GR_EINVAL;
+    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
+    if (n < 1 || n > h->max_n) return GR_EINVAL;
+    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
+    const int k_eff = (k <= 0 || k >= V) ? V : k;
+    if (k_eff > kMaxSupport || h->tail_mass > 0.0) return GR_EUNSUPPORTED;   // only supports that the LDS-resident path holds
+    return solve_in_lds(h, target_logits, draft_logits, temperature, n, k_eff, tol, B, V, accept_prob, status,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,

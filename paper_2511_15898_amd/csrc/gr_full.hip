@@ -198,7 +198,7 @@ __device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_BAD; info.iterations = 0;
     info.alpha_star = __longlong_as_double(0x7ff8000000000000ll);
-    info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0;
+    info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
     fp.info[row] = info;
     fp.accept_prob[row] = __uint_as_float(0x7fc00000u);
     fp.status[row] = GR_ROW_BAD;
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     if (tid == 0) {
         RowInfo info;
         info.support = kk; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
-        info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0;
+        info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
         fp.info[row] = info;
     }
 }

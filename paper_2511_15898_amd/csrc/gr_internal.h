@@ -27,6 +27,8 @@ struct RowInfo {
     double p_total;     // float64 row sum of p
     double q_total;     // float64 row sum of q (before top-k)
     double node_tokens; // sum over evaluator calls of (quadrature nodes x active tokens)
+    double p_ref;       // rows given as logits: p(i) = exp((t_i - p_ref) inv_temp) / p_total ...
+    double inv_temp;    // ... with inv_temp = 1 / temperature; 0 for rows given as probabilities
 #ifdef GR_PHASE_CLOCKS
     long long clk[24];  // shader-clock cycles of thread 0 per phase of the solve kernel (profiling builds only)
     double errlog[24];  // stopping measure after each of the first evaluations
@@ -45,6 +47,8 @@ struct SolveParams {
     const double* part_psum;          // [B, splits]
     const double* part_qsum;          // [B, splits]
     const int* part_bad;              // [B, splits]
+    // rows given as logits (p = target logits, q unused): temperature [B], the slices' softmax references [B, splits]
+    int logits; const float* temperature; const float* part_pref;
     // policy object
     int* order; int* block; double* weight; double* rho; double* pnorm;   // [B, kMaxSupport]
     RowInfo* info;                    // [B]
@@ -78,6 +82,9 @@ void launch_full_prologue(const FullParams& fp, hipStream_t stream);
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
                    double* piece_psum, int piece_stride, hipStream_t stream);
+void launch_select_logits(const float* target_logits, const float* draft_logits, const float* temperature, int B, int V, int k,
+                          int splits, int slice_len, unsigned long long* cand, int* cand_count, double* psum, double* qsum,
+                          int* bad, float* part_pref, double* piece_psum, float* piece_pref, int piece_stride, hipStream_t stream);
 hipError_t launch_solve(const SolveParams& sp, hipStream_t stream);
 // The policy object as the verify and slice kernels read it.  Top-k policies: arrays [B, stride] with
 // stride = kMaxSupport, rank_of = rho_id = nullptr.  Full-vocabulary policies: stride = V + 2, plus the
@@ -88,6 +95,7 @@ struct PolicyView {
     size_t stride;
     const double* piece_psum;   // [B, piece_stride] float64 sums of p over pieces of 256 tokens, or nullptr
     int piece_stride;
+    const float* piece_pref;    // rows given as logits: the reference each piece sum is relative to
 };
 void launch_verify(const float* p, int B, int V, int n, const PolicyView& pv, const RowInfo* info, const int* drafts,
                    const float* uniforms, int* token, unsigned char* accepted, hipStream_t stream);
@@ -245,11 +253,39 @@ __device__ __forceinline__ void wave_sequential_scan(const double* x, double* ou
 }
 #pragma clang fp contract(fast)
 
+// e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
+// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
+__device__ __forceinline__ double exp_neg(double y, const double* tab) {
+    const double yc = fmin(y, 1000.0);
+    const double kf = rint(yc * 46.166241308446828);
+    const int ki = static_cast<int>(kf);
+    const double tv = tab[ki & 31];
+    double r = fma(kf, -(6.93147180369123816490e-01 / 32.0), yc);
+    r = -fma(kf, -(1.90821492927058770002e-10 / 32.0), r);
+    double p = 8.33333333333333333333e-03;
+    p = fma(p, r, 4.16666666666666666667e-02);
+    p = fma(p, r, 1.66666666666666666667e-01);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p * tv, -(ki >> 5));                          // 2^-1442 flushes to 0
+}
+
 // Candidate key: larger q first, ties to the lower token id.  q >= 0, so its bit pattern is
 // monotone; the low word holds ~id so that a plain 64-bit compare gives the order.
 __device__ __forceinline__ unsigned long long make_key(float q, int id) {
     return (static_cast<unsigned long long>(__float_as_uint(q)) << 32) |
            static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<unsigned>(id));
+}
+// The same for a draft logit (any finite float): its bit pattern made monotone over the whole line.
+__device__ __forceinline__ unsigned long long make_key_logit(float d, int id) {
+    const unsigned b = __float_as_uint(d);
+    const unsigned mono = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return (static_cast<unsigned long long>(mono) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<unsigned>(id));
+}
+__device__ __forceinline__ float key_logit(unsigned long long key) {
+    const unsigned mono = static_cast<unsigned>(key >> 32);
+    return __uint_as_float((mono & 0x80000000u) ? (mono & 0x7FFFFFFFu) : ~mono);
 }
 __device__ __forceinline__ int key_id(unsigned long long key) {
     return static_cast<int>(0xFFFFFFFFu - static_cast<unsigned>(key & 0xFFFFFFFFull));

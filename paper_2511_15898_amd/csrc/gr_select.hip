@@ -13,16 +13,28 @@ namespace gr {
 // threshold; when a further tile might overflow the buffer it is cut back to its k largest keys and
 // the threshold is raised to the k-th.  The buffer never overflows: before each tile it holds at most
 // kSelCap - kSelTile keys and a tile appends at most kSelTile.
-__global__ __launch_bounds__(kThreads) void select_kernel(
+//
+// LOGITS: p and q are the target and draft logits and `temperature` [B] the sampling temperature of each row
+// (App. A: temperature only changes how p and q come from the logits).  The k largest q are the k largest
+// draft logits, so the keys carry the draft logit (as a monotone 32-bit pattern); the draft needs no
+// normaliser, because q is renormalised over the support anyway.  The target's normaliser is an online
+// softmax: every wave keeps a reference r (the largest target logit it has seen, raised tile by tile) and
+// its lanes the float64 sums of exp((t - r) / T); part_psum / part_pref get the
+// slice's sum and reference, piece_psum / piece_pref those of every 256 tokens.
+template <bool LOGITS>
+__global__ __launch_bounds__(kThreads, 8) void select_kernel(
     const float* __restrict__ p, const float* __restrict__ q, int V, int k, int slice_len,
     unsigned long long* __restrict__ cand, int* __restrict__ cand_count,
     double* __restrict__ part_psum, double* __restrict__ part_qsum, int* __restrict__ part_bad,
-    double* __restrict__ piece_psum, int piece_stride) {
+    double* __restrict__ piece_psum, int piece_stride,
+    const float* __restrict__ temperature, float* __restrict__ part_pref, float* __restrict__ piece_pref) {
     __shared__ unsigned long long keys[kSelCap];
     __shared__ int hist[256];
     __shared__ int pick[4];
     __shared__ int count;
     __shared__ double red[kWaves];
+    __shared__ float wref[kWaves];
+    __shared__ double e2tab[32];                           // 2^(-j/32), the table of exp_neg (LOGITS only)
 
     const int tid = threadIdx.x;
     const int s = blockIdx.x, b = blockIdx.y, splits = gridDim.x;
@@ -40,6 +52,16 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     unsigned long long theta = 0x00000000FFFFFFFFull;
     double ps = 0.0, qs = 0.0;
     int bad = 0;
+    // LOGITS: a temperature that is not a positive finite number marks the row bad
+    double inv_temp = 0.0;
+    float inv_temp_f = 0.f;
+    float ref = -__builtin_inff();
+    if (LOGITS) {
+        const float T = temperature[b];
+        if (!(T > 0.f) || !(T <= 3.0e38f)) bad = 1; else { inv_temp = 1.0 / static_cast<double>(T); inv_temp_f = 1.f / T; }
+        if (tid < 32) e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
+        __syncthreads();
+    }
 
     for (int base = v0; base < v1; base += kSelTile) {
         const int i0 = base + tid * 4;
@@ -57,6 +79,69 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 pv[j] = in ? pr[i0 + j] : 0.f;
             }
         }
+        if (LOGITS) {
+            // Entries beyond the slice read as -inf (no mass, never a candidate), like a masked token.  A NaN or a
+            // +inf anywhere makes the sum of the eight values NaN or +inf and marks the row bad (so do finite
+            // logits beyond 3e37, which no model emits).  Then the wave's reference rises to the largest target
+            // logit of the tile, the sums so far are rescaled, and the tile's terms are added.
+            if (!(vec && i0 + 3 < v1)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) if (!(i0 + j < v1)) { pv[j] = -__builtin_inff(); qv[j] = -__builtin_inff(); }
+            }
+            const float probe = ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((qv[0] + qv[1]) + (qv[2] + qv[3]));
+            bad |= !(probe < 3.0e38f);
+            float m4 = fmaxf(fmaxf(pv[0], pv[1]), fmaxf(pv[2], pv[3]));
+            if (__any(m4 > ref)) {                                 // the wave's reference rises (rare after the first tiles)
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) m4 = fmaxf(m4, __shfl_xor(m4, o));
+                ps = (ref > -3.0e38f) ? ps * exp_neg((static_cast<double>(m4) - static_cast<double>(ref)) * inv_temp, e2tab) : 0.0;
+                ref = m4;
+            }
+            // Terms more than 25 temperatures below the reference (each below 1.4e-11 of it) take the hardware's
+            // float32 exponential: their relative error of 1e-7 moves the sum by at most 1.4e-18 V of the reference's
+            // own term (2e-13 at V = 128256).  The others go through the float64 routine, one per lane and round
+            // (few lanes hold any).
+            double e4 = 0.0;
+            if (ref > -3.0e38f) {
+                const double r = static_cast<double>(ref);
+                unsigned pend = 0u;
+                float far_sum[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float y = (ref - pv[j]) * inv_temp_f;            // +inf for a masked entry
+#ifdef GR_SEL_ALLF32
+                    const bool far = true;
+#else
+                    const bool far = y > 25.f;
+#endif
+                    far_sum[j] = far ? exp2f(-y * 1.44269504088896341f) : 0.f;
+                    if (!far) pend |= 1u << j;
+                }
+                e4 = static_cast<double>((far_sum[0] + far_sum[1]) + (far_sum[2] + far_sum[3]));   // each below 1.4e-11: float32 adds lose nothing that matters
+                while (__any(pend != 0u)) {
+                    if (pend != 0u) {
+                        const int j = __ffs(static_cast<int>(pend)) - 1;
+                        const float tj = j == 0 ? pv[0] : (j == 1 ? pv[1] : (j == 2 ? pv[2] : pv[3]));
+                        e4 += exp_neg((r - static_cast<double>(tj)) * inv_temp, e2tab);
+                        pend &= pend - 1u;
+                    }
+                }
+            }
+            ps += e4;
+            const double pw = wave_sum(e4);
+            if (piece_psum && (tid & 63) == 0) {
+                const size_t at = static_cast<size_t>(b) * piece_stride + (base >> 8) + (tid >> 6);
+                piece_psum[at] = pw; piece_pref[at] = ref;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned long long key = make_key_logit(qv[j], i0 + j);
+                if (qv[j] > -3.0e38f && key > theta) {
+                    const int slot = atomicAdd(&count, 1);
+                    keys[slot] = key;                              // slot < kSelCap by construction
+                }
+            }
+        } else {
         // float64 sum of p over the 256 tokens this wave holds (slices start on tile boundaries, so the
         // pieces line up over the whole row): the rejection walk of the verify kernel starts from these
         {
@@ -75,6 +160,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 const int slot = atomicAdd(&count, 1);
                 keys[slot] = key;                                  // slot < kSelCap by construction
             }
+        }
         }
         __syncthreads();
         const int c = count;
@@ -117,14 +203,27 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
         }
     }
     __syncthreads();
-    const double pt = block_sum(ps, red);
-    const double qt = block_sum(qs, red);
+    double pt, qt;
+    float slice_ref = 0.f;
+    if (LOGITS) {
+        // the waves' sums, each relative to its own reference, brought to the slice's largest reference
+        if ((tid & 63) == 0) wref[tid >> 6] = ref;
+        __syncthreads();
+        slice_ref = fmaxf(fmaxf(wref[0], wref[1]), fmaxf(wref[2], wref[3]));
+        const double mine = (ref > -3.0e38f) ? ps * exp_neg((static_cast<double>(slice_ref) - static_cast<double>(ref)) * inv_temp, e2tab) : 0.0;
+        pt = block_sum(mine, red);
+        qt = 1.0;
+    } else {
+        pt = block_sum(ps, red);
+        qt = block_sum(qs, red);
+    }
     const int anybad = block_sum_i(bad, red);
     if (tid == 0) {
         cand_count[b * splits + s] = min(pick[0], kMaxSupport);
         part_psum[b * splits + s] = pt;
         part_qsum[b * splits + s] = qt;
         part_bad[b * splits + s] = anybad;
+        if (LOGITS) part_pref[b * splits + s] = slice_ref;
     }
 }
 
@@ -132,8 +231,16 @@ void launch_select(const float* p, const float* q, int B, int V, int k, int spli
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
                    double* piece_psum, int piece_stride, hipStream_t stream) {
     dim3 grid(splits, B);
-    hipLaunchKernelGGL(select_kernel, grid, dim3(kThreads), 0, stream, p, q, V, k, slice_len, cand,
-                       cand_count, psum, qsum, bad, piece_psum, piece_stride);
+    hipLaunchKernelGGL(select_kernel<false>, grid, dim3(kThreads), 0, stream, p, q, V, k, slice_len, cand,
+                       cand_count, psum, qsum, bad, piece_psum, piece_stride, nullptr, nullptr, nullptr);
+}
+
+void launch_select_logits(const float* target_logits, const float* draft_logits, const float* temperature, int B, int V, int k,
+                          int splits, int slice_len, unsigned long long* cand, int* cand_count, double* psum, double* qsum,
+                          int* bad, float* part_pref, double* piece_psum, float* piece_pref, int piece_stride, hipStream_t stream) {
+    dim3 grid(splits, B);
+    hipLaunchKernelGGL(select_kernel<true>, grid, dim3(kThreads), 0, stream, target_logits, draft_logits, V, k, slice_len, cand,
+                       cand_count, psum, qsum, bad, piece_psum, piece_stride, temperature, part_pref, piece_pref);
 }
 
 }  // namespace gr

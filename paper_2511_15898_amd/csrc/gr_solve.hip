@@ -85,6 +85,7 @@ struct Lds {
         struct {
             int cnt0[KS + 2]; int cnt1[KS + 2]; int ids[KS]; int byq[KS];
             double qd[KS]; double accb[KS];
+            double dlt[KS]; double dval[KS];   // rows given as logits: draft minus target logit, draft logit
             double P[KS + 1]; double S[KS + 1]; double G0[KS + 2]; double G1[KS + 2];
         };
         struct {
@@ -163,24 +164,6 @@ template <class LdsT> __device__ __forceinline__ double wg_max(LdsT& L, int& par
     double a[1] = {wave_max(v)};
     wg_reduce<1>(L, par, a, {kOpMax});
     return a[0];
-}
-
-// e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
-// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
-__device__ __forceinline__ double exp_neg(double y, const double* tab) {
-    const double yc = fmin(y, 1000.0);
-    const double kf = rint(yc * 46.166241308446828);
-    const int ki = static_cast<int>(kf);
-    const double tv = tab[ki & 31];
-    double r = fma(kf, -(6.93147180369123816490e-01 / 32.0), yc);
-    r = -fma(kf, -(1.90821492927058770002e-10 / 32.0), r);
-    double p = 8.33333333333333333333e-03;
-    p = fma(p, r, 4.16666666666666666667e-02);
-    p = fma(p, r, 1.66666666666666666667e-01);
-    p = fma(p, r, 0.5);
-    p = fma(p, r, 1.0);
-    p = fma(p, r, 1.0);
-    return ldexp(p * tv, -(ki >> 5));                          // 2^-1442 flushes to 0
 }
 
 // 1/x from the hardware estimate and two Newton steps (about 1e-16 relative; x = 0, infinite or NaN gives NaN or 0).
@@ -1047,19 +1030,39 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
     const int n = sp.n, V = sp.V;
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
-    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0;
+    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
 
     // ---- merge the slices
     int total = 0, bad = 0;
     double ptot = 0.0, qtot = 0.0;
-    for (int s = 0; s < sp.splits; ++s) {
-        total += sp.cand_count[row * sp.splits + s];
-        bad |= sp.part_bad[row * sp.splits + s];
-        ptot += sp.part_psum[row * sp.splits + s];
-        qtot += sp.part_qsum[row * sp.splits + s];
+    double p_ref = 0.0, inv_temp = 0.0;
+    if (sp.logits) {
+        // rows given as logits: the slices' softmax sums are brought to the row's largest reference; q needs no
+        // normaliser (it is renormalised over the support)
+        const float T = sp.temperature[row];
+        inv_temp = 1.0 / static_cast<double>(T);
+        float m = -__builtin_inff();
+        for (int s = 0; s < sp.splits; ++s) m = fmaxf(m, sp.part_pref[row * sp.splits + s]);
+        p_ref = static_cast<double>(m);
+        for (int s = 0; s < sp.splits; ++s) {
+            total += sp.cand_count[row * sp.splits + s];
+            bad |= sp.part_bad[row * sp.splits + s];
+            const float r = sp.part_pref[row * sp.splits + s];
+            if (r > -3.0e38f) ptot += sp.part_psum[row * sp.splits + s] * exp((static_cast<double>(r) - p_ref) * inv_temp);
+        }
+        qtot = 1.0;
+        if (!(ptot > 0.0) || !(ptot < 1e300) || !(m > -3.0e38f)) bad = 1;
+    } else {
+        for (int s = 0; s < sp.splits; ++s) {
+            total += sp.cand_count[row * sp.splits + s];
+            bad |= sp.part_bad[row * sp.splits + s];
+            ptot += sp.part_psum[row * sp.splits + s];
+            qtot += sp.part_qsum[row * sp.splits + s];
+        }
+        if (!(fabs(ptot - 1.0) <= 1e-3) || !(fabs(qtot - 1.0) <= 1e-3)) bad = 1;
     }
-    info.p_total = ptot; info.q_total = qtot;
-    if (bad || !(fabs(ptot - 1.0) <= 1e-3) || !(fabs(qtot - 1.0) <= 1e-3) || total <= 0 || total > kSelCap) {
+    info.p_total = ptot; info.q_total = qtot; info.p_ref = p_ref; info.inv_temp = sp.logits ? inv_temp : 0.0;
+    if (bad || total <= 0 || total > kSelCap) {
         if (tid == 0) {
             info.status = GR_ROW_BAD;
             info.alpha_star = __longlong_as_double(0x7ff8000000000000ll);
@@ -1090,12 +1093,24 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
         const unsigned long long key = L.keys[i];
         if (key >= theta) {
             const int slot = atomicAdd(&L.count, 1);
-            if (slot < KS) { L.ids[slot] = key_id(key); L.accb[slot] = static_cast<double>(key_q(key)); }
+            if (slot < KS) { L.ids[slot] = key_id(key); L.accb[slot] = static_cast<double>(sp.logits ? key_logit(key) : key_q(key)); }
         }
     }
     __syncthreads();
     // unsorted: token ids in ids, q in accb (exact float values), p gathered into G0
-    if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
+    if (sp.logits) {
+        // p = exp((t - p_ref) / T) (divided by the row's sum with the other p below), q = exp((d - largest d) / T),
+        // and the two keys every order is decided on: d - t for the ratio (q/p is proportional to
+        // exp((d - t) / T); exact for float32 logits) and d itself for q
+        const double d = tid < kk ? L.accb[tid] : -1e300;
+        const double dmax = block_max<kSW>(d, L.redn);
+        if (tid < kk) {
+            const double t = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
+            L.G0[tid] = exp((t - p_ref) * inv_temp);
+            L.dlt[tid] = d - t; L.dval[tid] = d;
+            L.accb[tid] = exp((d - dmax) * inv_temp);
+        }
+    } else if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
     if (tid < kk) { L.cnt0[tid] = 0; L.cnt1[tid] = 0; }
     __syncthreads();
     GR_CLK(L, 0);
@@ -1107,17 +1122,28 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
         const int per = kST / parts;                       // tokens a part can hold
         const int me = tid % per, part = tid / per;
         if (me < kk) {
-            const double qa = L.accb[me], pa = L.G0[me];
             const int ta = L.ids[me];
             const int j0 = (kk * part) / parts, j1 = (kk * (part + 1)) / parts;
             int rank = 0, qrank = 0;
+            if (sp.logits) {
+                const double ka = L.dlt[me], da = L.dval[me];
 #pragma unroll 4
-            for (int j = j0; j < j1; ++j) {
-                const double qj = L.accb[j];
-                const double lhs = qj * pa, rhs = qa * L.G0[j];   // j before me?
-                const int lower = static_cast<int>(L.ids[j] < ta);
-                rank += static_cast<int>(lhs > rhs) | (static_cast<int>(lhs == rhs) & lower);
-                qrank += static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & lower);
+                for (int j = j0; j < j1; ++j) {
+                    const double kj = L.dlt[j], dj = L.dval[j];
+                    const int lower = static_cast<int>(L.ids[j] < ta);
+                    rank += static_cast<int>(kj > ka) | (static_cast<int>(kj == ka) & lower);
+                    qrank += static_cast<int>(dj > da) | (static_cast<int>(dj == da) & lower);
+                }
+            } else {
+                const double qa = L.accb[me], pa = L.G0[me];
+#pragma unroll 4
+                for (int j = j0; j < j1; ++j) {
+                    const double qj = L.accb[j];
+                    const double lhs = qj * pa, rhs = qa * L.G0[j];   // j before me?
+                    const int lower = static_cast<int>(L.ids[j] < ta);
+                    rank += static_cast<int>(lhs > rhs) | (static_cast<int>(lhs == rhs) & lower);
+                    qrank += static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & lower);
+                }
             }
             if (parts > 1) { atomicAdd(&L.cnt0[me], rank); atomicAdd(&L.cnt1[me], qrank); }
             else { L.cnt0[me] = rank; L.cnt1[me] = qrank; }

@@ -31,6 +31,13 @@ struct Slice {
     int mode;
 };
 
+// Entry t of the row that `info` describes, before the division by info.p_total: the stored probability, or, for a
+// row given as logits (App. A: temperature only changes how p comes from the logits), exp((t - p_ref) / T).
+__device__ __forceinline__ double p_entry(const float* prow, int t, const RowInfo& info) {
+    const double x = static_cast<double>(prow[t]);
+    return info.inv_temp > 0.0 ? exp((x - info.p_ref) * info.inv_temp) : x;
+}
+
 // All threads call; result in LDS `S`.  order/block/weight: this row's policy arrays.
 // rank_of: token -> rank of a full-vocabulary policy (nullptr for a top-k policy, whose ranks are
 // found by a scan of `order`).
@@ -65,7 +72,7 @@ __device__ void build_slice(Slice& S, const RowInfo& info, const int* order, con
         const int pos = S.pos[tid];
         S.wv[tid] = pos >= 0 ? weight[pos] : 0.0;
         S.bv[tid] = pos >= 0 ? block[pos] : -1;
-        S.pv[tid] = static_cast<double>(prow[S.tok[tid]]);
+        S.pv[tid] = p_entry(prow, S.tok[tid], info);
     }
     __syncthreads();
     if (tid == 0) {
@@ -125,7 +132,7 @@ __device__ void tile_weights(double* w, const Slice& S, const RowInfo& info, con
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int t = base + tid * 4 + j;
-        w[tid * 4 + j] = t < V ? f * static_cast<double>(prow[t]) : 0.0;
+        w[tid * 4 + j] = t < V ? f * p_entry(prow, t, info) : 0.0;
     }
     __syncthreads();
     if (S.mode == kInner) {
@@ -214,13 +221,15 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     // a full-vocabulary policy whose drafts all lie in H* spreads the slack over scale * rho_id[t]
     const bool dense = rid != nullptr && S.mode == kInner;
     const double* pieces = (pv.piece_psum && !dense) ? pv.piece_psum + static_cast<size_t>(row) * pv.piece_stride : nullptr;
+    const bool from_logits = info.inv_temp > 0.0;           // piece sums are then relative to a reference of their own
+    const float* prefs = (pieces && from_logits) ? pv.piece_pref + static_cast<size_t>(row) * pv.piece_stride : nullptr;
     const int n_special = dense ? 0 : (S.mode == kInner ? info.support : S.nd);
     int sp_tok = -1; double sp_w = 0.0;
     if (tid < n_special) {
         if (S.mode == kInner) { sp_tok = o[tid]; sp_w = tid >= info.h ? S.scale * rh[tid] : 0.0; }
         else { sp_tok = S.tok[tid]; sp_w = 0.0; }
     }
-    const double sp_delta = sp_tok >= 0 ? sp_w - f * static_cast<double>(prow[sp_tok]) : 0.0;
+    const double sp_delta = sp_tok >= 0 ? sp_w - f * p_entry(prow, sp_tok, info) : 0.0;
     int lo = 0, len = V;
     double cum = c;
     bool beyond = false;                      // the draw lies beyond the total by rounding: take the last token with mass
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
                 double sa = 0.0;
                 for (int sub = lane; sub < g; sub += 64) {
                     const int idx = (lo >> 8) + pc * g + sub;
-                    if (idx < npv) sa += pieces[idx];
+                    if (idx < npv) sa += prefs ? pieces[idx] * exp((static_cast<double>(prefs[idx]) - info.p_ref) * info.inv_temp) : pieces[idx];
                 }
                 sa = wave_sum(sa);
                 if (lane == 0) seg[pc] = f * sa;
@@ -252,6 +261,17 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
                 }
                 sa = wave_sum(sa);
                 if (lane == 0) seg[pc] = S.scale * sa;
+            }
+        } else if (from_logits) {                       // no piece sums on this handle: exponentials of the whole range
+            for (int pc = wvv; pc < np; pc += kWaves) {
+                double sa = 0.0;
+                for (int sub = 0; sub < g; ++sub) {
+                    const int t0 = lo + pc * cs + sub * 256 + lane * 4;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) if (t0 + j < end) sa += p_entry(prow, t0 + j, info);
+                }
+                sa = wave_sum(sa);
+                if (lane == 0) seg[pc] = f * sa;
             }
         } else
         // two pieces per round and up to eight loads of each in flight: one workgroup streams the row,
@@ -314,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void verify_kernel(
     }
     {
         const int t = lo + tid;
-        w[tid] = tid < len ? (dense ? S.scale * rid[t] : f * static_cast<double>(prow[t])) : 0.0;
+        w[tid] = tid < len ? (dense ? S.scale * rid[t] : f * p_entry(prow, t, info)) : 0.0;
         __syncthreads();
         if (sp_tok >= lo && sp_tok < lo + len) w[sp_tok - lo] = sp_w;
         __syncthreads();

@@ -88,23 +88,30 @@ def tiny(B: int = 1000, V: int = 8, n: int = 2, seed_sub: int = 0) -> Workload:
     return _finish("tiny", p, q, n, 0, rng)
 
 
-def small(B: int = 64, V: int = 1024, n: int = 4, k: int = 32, seed_sub: int = 0) -> Workload:
-    """Config 2: target logits 3*N(0,1); draft logits = target + N(0, std 0.5)."""
+def small(B: int = 64, V: int = 1024, n: int = 4, k: int = 32, seed_sub: int = 0, keep_logits: bool = False) -> Workload:
+    """Config 2: target logits 3*N(0,1); draft logits = target + N(0, std 0.5).  keep_logits: the float32 logits
+    (before the division by the temperature, here 1) go to meta["target_logits"] / meta["draft_logits"]."""
     rng = np.random.default_rng(BASE_SEED + 1000 * 2 + seed_sub)
     tl = 3.0 * rng.standard_normal((B, V))
     dl = tl + 0.5 * rng.standard_normal((B, V))
-    return _finish("small", _softmax32(tl), _softmax32(dl), n, k, rng)
+    meta = {"temps": np.ones(B)}
+    if keep_logits:
+        meta.update(target_logits=tl.astype(np.float32), draft_logits=dl.astype(np.float32))
+    return _finish("small", _softmax32(tl), _softmax32(dl), n, k, rng, meta)
 
 
 def llm_shaped(B: int = 256, V: int = 32000, n: int = 4, k: int = 64, temperature=1.0,
                corr: float = 0.8, near_identical_frac: float = 0.0, seed_sub: int = 0,
-               cfg: int = 3, name: str = "llm") -> Workload:
+               cfg: int = 3, name: str = "llm", keep_logits: bool = False) -> Workload:
     """Configs 3-5: heavy-tailed target logits 4*Gumbel(0,1); draft logits =
     corr*target + N(0,1); both divided by the row's temperature.  ``temperature`` may
     be a scalar or a (lo, hi) pair (uniform per row).  A fraction of rows may carry a
-    draft that is the target plus N(0, std 0.01) noise (acceptance close to 1)."""
+    draft that is the target plus N(0, std 0.01) noise (acceptance close to 1).  keep_logits: the float32
+    logits (before the division by the temperature) go to meta["target_logits"] / meta["draft_logits"]."""
     rng = np.random.default_rng(BASE_SEED + 1000 * cfg + seed_sub)
     p = np.empty((B, V), np.float32); q = np.empty((B, V), np.float32)
+    tls = np.empty((B, V), np.float32) if keep_logits else None
+    dls = np.empty((B, V), np.float32) if keep_logits else None
     if np.ndim(temperature) == 0:
         temps = np.full(B, float(temperature))
     else:
@@ -118,12 +125,17 @@ def llm_shaped(B: int = 256, V: int = 32000, n: int = 4, k: int = 64, temperatur
         else:
             dl = corr * tl + rng.standard_normal(V)
         p[b] = _softmax32(tl / temps[b]); q[b] = _softmax32(dl / temps[b])
-    return _finish(name, p, q, n, k, rng, {"temps": temps, "near": near})
+        if keep_logits:
+            tls[b] = tl; dls[b] = dl
+    meta = {"temps": temps, "near": near}
+    if keep_logits:
+        meta.update(target_logits=tls, draft_logits=dls)
+    return _finish(name, p, q, n, k, rng, meta)
 
 
-def large_vocab(B: int = 256, V: int = 128256, n: int = 8, k: int = 128, seed_sub: int = 0) -> Workload:
+def large_vocab(B: int = 256, V: int = 128256, n: int = 8, k: int = 128, seed_sub: int = 0, keep_logits: bool = False) -> Workload:
     """Config 4: the roofline configuration."""
-    return llm_shaped(B, V, n, k, temperature=1.0, corr=0.7, seed_sub=seed_sub, cfg=4, name="large")
+    return llm_shaped(B, V, n, k, temperature=1.0, corr=0.7, seed_sub=seed_sub, cfg=4, name="large", keep_logits=keep_logits)
 
 
 def stress(B: int = 1024, V: int = 128256, n: int = 8, k: int = 128, seed_sub: int = 0) -> Workload:

@@ -457,6 +457,31 @@ def test_logits_front_end_against_closed_forms_and_invariances():
         assert sorted(int(t) for t in base.order) == sorted(int(t) for t in np.argsort(-dl, kind="stable")[:k])   # top-k of q = top-k of the draft logits
 
 
+def test_orders_taken_on_the_logits_are_the_orders_of_the_softmaxed_rows():
+    """Sec. 5.1 asks for decreasing q/p; behind two softmaxes at one temperature that is decreasing d - t.  The
+    checker's order from logits is held against q/p = exp((d - t) / T) evaluated with 60 decimal digits (exact
+    for this purpose), with ties -- equal logit differences, equal draft logits -- resolved to the lower id."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    rng = np.random.default_rng(53)
+    for trial in range(8):
+        V = int(rng.integers(12, 40)); T = float(rng.uniform(0.4, 1.6))
+        tl = (3.0 * rng.standard_normal(V)).astype(np.float32); dl = (0.8 * tl + rng.standard_normal(V)).astype(np.float32)
+        if trial % 2:                                   # planted ties: the same difference twice, the same draft logit twice
+            tl[7] = tl[2] + np.float32(0.5); dl[7] = dl[2] + np.float32(0.5)
+            if float(dl[7]) - float(tl[7]) != float(dl[2]) - float(tl[2]):
+                dl[7] = dl[2]; tl[7] = tl[2]
+            dl[9] = dl[4]
+        sol, p, q = G.solve_row_from_logits(tl, dl, T, 3, 0, tol=0.0, max_T=1)
+        ratio = [((Decimal(float(dl[i])) - Decimal(float(tl[i])) ) / Decimal(T)).exp() for i in range(V)]
+        want = sorted(range(V), key=lambda i: (-ratio[i], i))
+        assert [int(t) for t in sol.order] == want
+        qd = [(Decimal(float(dl[i])) / Decimal(T)).exp() for i in range(V)]
+        k = V // 2
+        want_k = sorted(sorted(range(V), key=lambda i: (-qd[i], i))[:k])
+        assert G.topk_support(q, k, key=dl.astype(np.float64)) == want_k
+
+
 # ------------------------------------------------------------------ nucleus cut of the draft
 def test_nucleus_cut_is_the_smallest_prefix_by_mass_and_costs_at_most_n_tail_mass():
     """Sec. 5.1 / App. A: top-p sampling of the draft restricts the domain like top-k.  The cut support is
