@@ -172,6 +172,29 @@ int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
 
 /* Test / inspection entry points --------------------------------------------------- */
 
+/*
+ * Multi-step verification over a tree of draft paths (App. "Multi-Step Experiments": K i.i.d. paths of length L
+ * are drafted autoregressively from the draft model; the verifier advances from the root with n = the number of
+ * drafted continuations of the current node until it lands off the tree; a row whose solve fails is sampled from p).
+ * For each of S sequences and each level, sequences are grouped by n; every group is gathered, solved with
+ * gr_solve(n) and sampled with gr_verify, and the paths that drew the emitted token go on to the next level.
+ *
+ * p, q       DEVICE [S, K, L, V] float32: the target / draft distribution after the first l tokens of path a of
+ *            sequence s (paths with equal prefixes must carry equal rows; level 0 is the same row for all paths).
+ * paths      HOST [S, K, L] int32 drafted tokens (path a's token l drawn from the top-k renormalised q row (s, a, l)).
+ * uniforms   HOST [S, L] float32 in [0, 1), one per level.
+ * k, tol     as in gr_solve.  K <= max_n and S <= max_B of the handle.
+ * out_tokens HOST [S, L] int32: the tokens emitted, -1 beyond the last.  out_len [S]: how many (the walk emits one
+ *            token per level visited; no bonus token after a fully accepted tree).  out_accepted [S]: how many of
+ *            them were drafts.  out_fallbacks [S] or NULL: levels whose row had a status other than GR_ROW_OK.
+ * The first call allocates staging for max_B rows of max_V tokens (8 max_V bytes per row; GR_ENOMEM); every call
+ * synchronises the stream once per level and group, and leaves the handle without a policy (GR_ESTATE for a
+ * gr_verify that follows).
+ */
+int gr_tree_walk(gr_handle h, const float* p, const float* q, const int* paths, const float* uniforms,
+                 int S, int K, int L, int V, int k, float tol,
+                 int* out_tokens, int* out_len, int* out_accepted, int* out_fallbacks, void* hip_stream);
+
 /* Dense slice of the transport for the drafted tuple, normalised by pdraft(drafts) (Eq. "cases" with
  * the residual lift of Eq. (3); Eq. "approx-c" when truncated; Alg. 1 "return normalized C"):
  * pi [B, V] float32 out = pi(.|drafts);  accept_given_drafts [B] float32 out = sum of pi over the row's

@@ -19,7 +19,7 @@ GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED, GR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 GR_NOALLOC_MAX_B = 256
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -56,6 +56,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.gr_tree_walk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
     lib.gr_solve_stats.argtypes = [vp] * 4
@@ -189,6 +190,26 @@ def gr_accept_sweep_noalloc(p: torch.Tensor, q: torch.Tensor, ks, ns, accept_pro
     if rc != GR_OK:
         raise GrError(rc, "gr_accept_sweep_noalloc")
     return accept_prob, status
+
+
+def gr_tree_walk(handle: int, p: torch.Tensor, q: torch.Tensor, paths, uniforms, k: int, tol: float, stream=None):
+    """p, q: [S, K, L, V] float32 CUDA tensors; paths: [S, K, L] int32 and uniforms: [S, L] float32 host arrays (numpy).
+    Returns host arrays (tokens [S, L], length [S], accepted [S], fallbacks [S])."""
+    import numpy as np
+    if p.dim() != 4 or p.shape != q.shape:
+        raise TypeError("gr_tree_walk: p and q must both be [S, K, L, V]")
+    S, K, L, V = p.shape
+    paths = np.ascontiguousarray(paths, dtype=np.int32); uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+    if paths.shape != (S, K, L) or uniforms.shape != (S, L):
+        raise TypeError("gr_tree_walk: paths must be [S, K, L] and uniforms [S, L]")
+    tokens = np.empty((S, L), np.int32); length = np.empty(S, np.int32); accepted = np.empty(S, np.int32); fallbacks = np.empty(S, np.int32)
+    rc = load_library().gr_tree_walk(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), paths.ctypes.data, uniforms.ctypes.data,
+                                     S, K, L, V, k, tol, tokens.ctypes.data, length.ctypes.data, accepted.ctypes.data,
+                                     fallbacks.ctypes.data, _stream(stream))
+    _solved_shape.pop(handle, None)
+    if rc != GR_OK:
+        raise GrError(rc, "gr_tree_walk")
+    return tokens, length, accepted, fallbacks
 
 
 def _check_drafts(handle: int, drafts: torch.Tensor, what: str, V: int | None = None) -> None:

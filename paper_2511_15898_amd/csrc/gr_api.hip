@@ -1,5 +1,6 @@
 // C ABI of the Global Resolution verifier: handle, argument checks, kernel launches.
 #include <new>
+#include <vector>
 
 #include "gr_internal.h"
 
@@ -33,6 +34,9 @@ struct gr_handle_s {
     void* full_ws = nullptr; size_t full_ws_bytes = 0;
     FullParams full = {};
     bool full_mode = false;
+    // staging of gr_tree_walk (allocated by its first call): gathered rows, drafts, uniforms, results, row offsets
+    float* tw_p = nullptr; float* tw_q = nullptr; int* tw_drafts = nullptr; float* tw_u = nullptr; int* tw_tok = nullptr;
+    unsigned char* tw_ok = nullptr; long long* tw_idx = nullptr; float* tw_acc = nullptr; int* tw_status = nullptr;
     // last solve
     bool solved = false;
     const float* p = nullptr;
@@ -51,7 +55,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->newton_ws, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status, h->newton_ws, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -352,6 +356,92 @@ extern "C" int gr_verify(gr_handle h, const int* drafts, const float* uniforms, 
     if (hipGetLastError() != hipSuccess) return GR_EHIP;
     mark(h, 4, stream);
     if (h->profile && h->prof_count < kProfSlots) ++h->prof_count;
+    return GR_OK;
+}
+
+// ---- multi-step walk over a tree of draft paths
+namespace {
+
+// dst row j = src row at element offset idx[j] (V floats), for both distributions.
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(const float* __restrict__ p, const float* __restrict__ q,
+                                                                const long long* __restrict__ idx, float* __restrict__ dp,
+                                                                float* __restrict__ dq, int V) {
+    const long long src = idx[blockIdx.x];
+    const size_t dst = static_cast<size_t>(blockIdx.x) * V;
+    for (int i = threadIdx.x; i < V; i += kThreads) { dp[dst + i] = p[src + i]; dq[dst + i] = q[src + i]; }
+}
+
+}  // namespace
+
+extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const int* paths, const float* uniforms,
+                            int S, int K, int L, int V, int k, float tol,
+                            int* out_tokens, int* out_len, int* out_accepted, int* out_fallbacks, void* hip_stream) {
+    if (!h || !p || !q || !paths || !uniforms || !out_tokens || !out_len || !out_accepted) return GR_EINVAL;
+    if (S <= 0 || K < 1 || L < 1 || V <= 0 || S > h->max_B || V > h->max_V || K > h->max_n) return GR_EINVAL;
+    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!h->tw_p) {
+        const size_t rows = static_cast<size_t>(h->max_B), cols = static_cast<size_t>(h->max_V);
+        const bool ok = dev_alloc(&h->tw_p, rows * cols) && dev_alloc(&h->tw_q, rows * cols) && dev_alloc(&h->tw_drafts, rows * GR_MAX_N) &&
+                        dev_alloc(&h->tw_u, rows) && dev_alloc(&h->tw_tok, rows) && dev_alloc(&h->tw_ok, rows) && dev_alloc(&h->tw_idx, rows) &&
+                        dev_alloc(&h->tw_acc, rows) && dev_alloc(&h->tw_status, rows);
+        if (!ok) {
+            void* ptrs[] = {h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status};
+            for (void* ptr : ptrs) (void)hipFree(ptr);
+            h->tw_p = h->tw_q = h->tw_u = h->tw_acc = nullptr; h->tw_drafts = h->tw_tok = h->tw_status = nullptr; h->tw_ok = nullptr; h->tw_idx = nullptr;
+            (void)hipGetLastError();
+            return GR_ENOMEM;
+        }
+    }
+    // the state of every sequence lives on the host: the paths that still agree with the tokens emitted so far
+    std::vector<unsigned> active(S, K >= 32 ? 0xFFFFFFFFu : ((1u << K) - 1u));
+    std::vector<char> alive(S, 1);
+    for (int s = 0; s < S; ++s) { out_len[s] = 0; out_accepted[s] = 0; if (out_fallbacks) out_fallbacks[s] = 0; }
+    for (int i = 0; i < S * L; ++i) out_tokens[i] = -1;
+    std::vector<int> seqs, drafts, tok, st; std::vector<long long> idx; std::vector<float> us; std::vector<unsigned char> okv;
+    for (int l = 0; l < L; ++l) {
+        for (int n = 1; n <= K; ++n) {
+            seqs.clear(); drafts.clear(); idx.clear(); us.clear();
+            for (int s = 0; s < S; ++s) {
+                if (!alive[s] || __builtin_popcount(active[s]) != n) continue;
+                const int a0 = __builtin_ctz(active[s]);
+                seqs.push_back(s);
+                idx.push_back(((static_cast<long long>(s) * K + a0) * L + l) * V);
+                for (int a = 0; a < K; ++a) if (active[s] >> a & 1u) drafts.push_back(paths[(static_cast<size_t>(s) * K + a) * L + l]);
+                us.push_back(uniforms[static_cast<size_t>(s) * L + l]);
+            }
+            const int cnt = static_cast<int>(seqs.size());
+            if (cnt == 0) continue;
+            if (hipMemcpyAsync(h->tw_idx, idx.data(), sizeof(long long) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess ||
+                hipMemcpyAsync(h->tw_drafts, drafts.data(), sizeof(int) * cnt * n, hipMemcpyHostToDevice, stream) != hipSuccess ||
+                hipMemcpyAsync(h->tw_u, us.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess) return GR_EHIP;
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(cnt), dim3(kThreads), 0, stream, p, q, h->tw_idx, h->tw_p, h->tw_q, V);
+            if (hipGetLastError() != hipSuccess) return GR_EHIP;
+            int rc = gr_solve(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
+            if (rc != GR_OK) return rc;
+            rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);
+            if (rc != GR_OK) return rc;
+            tok.resize(cnt); st.resize(cnt); okv.resize(cnt);
+            if (hipMemcpyAsync(tok.data(), h->tw_tok, sizeof(int) * cnt, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+                hipMemcpyAsync(okv.data(), h->tw_ok, cnt, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+                hipMemcpyAsync(st.data(), h->tw_status, sizeof(int) * cnt, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+                hipStreamSynchronize(stream) != hipSuccess) return GR_EHIP;
+            for (int j = 0; j < cnt; ++j) {
+                const int s = seqs[j];
+                out_tokens[static_cast<size_t>(s) * L + l] = tok[j];
+                out_len[s] = l + 1;
+                if (out_fallbacks && st[j] != GR_ROW_OK) ++out_fallbacks[s];
+                if (!okv[j] || tok[j] < 0) { alive[s] = 0; continue; }
+                ++out_accepted[s];
+                unsigned keep = 0u;
+                for (int a = 0; a < K; ++a)
+                    if ((active[s] >> a & 1u) && paths[(static_cast<size_t>(s) * K + a) * L + l] == tok[j]) keep |= 1u << a;
+                active[s] = keep;
+                if (!keep) alive[s] = 0;                         // cannot happen: an accepted token is one of the drafts
+            }
+        }
+    }
+    h->solved = false;                                           // the policy left in the handle belongs to a gathered batch
     return GR_OK;
 }
 

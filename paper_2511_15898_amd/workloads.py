@@ -142,3 +142,27 @@ def stress(B: int = 1024, V: int = 128256, n: int = 8, k: int = 128, seed_sub: i
     """Config 5 cell: per-row temperature in [0.5, 1.5], 10 % near-identical rows."""
     return llm_shaped(B, V, n, k, temperature=(0.5, 1.5), corr=0.7, near_identical_frac=0.10,
                       seed_sub=seed_sub, cfg=5, name="stress")
+
+
+def draft_tree(S: int = 8, K: int = 3, L: int = 4, V: int = 4096, k: int = 32, corr: float = 0.8, seed_sub: int = 0):
+    """A tree of K i.i.d. draft paths of length L per sequence (stands in for the paper's multi-step runs on
+    Gemma-2 27B/2B, App. "Multi-Step Experiments"): the target logits of a node are 4*Gumbel(0,1) and its draft
+    logits corr*target + N(0,1), both a seeded function of the sequence and of the node's prefix, so that paths
+    with equal prefixes see equal rows; each path draws its next token from the top-k renormalised draft row
+    with its own stream.  Returns (p [S,K,L,V], q [S,K,L,V], paths [S,K,L] int32, uniforms [S,L] float32)."""
+    p = np.empty((S, K, L, V), np.float32); q = np.empty((S, K, L, V), np.float32)
+    paths = np.empty((S, K, L), np.int32)
+    for s in range(S):
+        for a in range(K):
+            prefix = []
+            for l in range(L):
+                node = np.random.default_rng([BASE_SEED, 7000 + seed_sub, s] + prefix)
+                tl = 4.0 * node.gumbel(0.0, 1.0, size=V)
+                dl = corr * tl + node.standard_normal(V)
+                p[s, a, l] = _softmax32(tl); q[s, a, l] = _softmax32(dl)
+                draw = np.random.default_rng([BASE_SEED, 8000 + seed_sub, s, a, l])
+                tok = int(draw_drafts(q[s, a, l][None, :], k, 1, draw)[0, 0])
+                paths[s, a, l] = tok
+                prefix.append(tok)
+    u = np.random.default_rng([BASE_SEED, 9000 + seed_sub]).random((S, L)).astype(np.float32)
+    return p, q, paths, np.minimum(u, np.float32(1.0 - 2.0 ** -24))

@@ -522,3 +522,69 @@ def test_nucleus_cut_is_the_smallest_prefix_by_mass_and_costs_at_most_n_tail_mas
             marg, acc, norm = brute.coupling_marginals(lambda t: G.policy_slice(sol, p, t), qq, n)
             assert norm < 1e-12 and np.abs(marg - _norm64(p)).sum() < 1e-6 and abs(acc - sol.alpha_star) < 1e-9
     assert checked >= 100 and cut_rows >= 40          # the cut really dropped tokens
+
+
+# ------------------------------------------------------------------ multi-step walk over a draft tree
+def test_tree_walk_emits_tokens_distributed_as_the_target_model():
+    """App. "Multi-Step Experiments": K i.i.d. draft paths, n = the paths through the current node.  On a
+    vocabulary of three tokens every draft tree (3^(K L) of them) and every outcome is enumerated with the exact
+    slices in place of the uniform draws: the first token must have the root's target distribution, and given
+    that it was accepted the second must have the target distribution of its prefix -- which fails if the walk
+    kept the wrong paths, counted drafts wrongly or conditioned on the wrong rows.  Then the sampler itself:
+    with uniforms it must pick, level by level, what the inverse CDF of those slices picks."""
+    from oracle import tree_walk as TW
+    rng = np.random.default_rng(404)
+    V, K, L = 3, 2, 2
+    rows = {}
+
+    def node(prefix):
+        if prefix not in rows:
+            r = np.random.default_rng([7, len(prefix)] + list(prefix))
+            rows[prefix] = (_norm64(r.dirichlet(np.ones(V)) + 0.05).astype(np.float32), _norm64(r.dirichlet(np.ones(V)) + 0.05).astype(np.float32))
+        return rows[prefix]
+
+    first = np.zeros(V); second = {x: np.zeros(V) for x in range(V)}; reach = {x: 0.0 for x in range(V)}
+    for toks in itertools.product(range(V), repeat=K * L):
+        paths = [toks[a * L:(a + 1) * L] for a in range(K)]
+        mass = 1.0
+        for a in range(K):
+            for l in range(L):
+                q = node(tuple(paths[a][:l]))[1].astype(np.float64)
+                mass *= q[paths[a][l]] / q.sum()
+        p0, q0 = node(())
+        sol0 = G.solve_row(p0, q0, K, 0, tol=0.0)
+        pi0, _ = G.policy_slice(sol0, p0, [paths[a][0] for a in range(K)])
+        first += mass * pi0
+        for x in set(paths[a][0] for a in range(K)):            # accepted first tokens
+            act = [a for a in range(K) if paths[a][0] == x]
+            p1, q1 = node((x,))
+            sol1 = G.solve_row(p1, q1, len(act), 0, tol=0.0)
+            pi1, _ = G.policy_slice(sol1, p1, [paths[a][1] for a in act])
+            second[x] += mass * pi0[x] * pi1; reach[x] += mass * pi0[x]
+    assert np.abs(first - _norm64(node(())[0])).max() < 1e-9
+    for x in range(V):
+        assert reach[x] > 0 and np.abs(second[x] / reach[x] - _norm64(node((x,))[0])).max() < 1e-9, x
+    for trial in range(200):
+        paths = []
+        for a in range(K):
+            pre = []
+            for l in range(L):
+                q = node(tuple(pre))[1].astype(np.float64)
+                pre.append(int(rng.choice(V, p=q / q.sum())))
+            paths.append(pre)
+        u = rng.random(L)
+        p_nodes = [[node(tuple(paths[a][:l]))[0] for l in range(L)] for a in range(K)]
+        q_nodes = [[node(tuple(paths[a][:l]))[1] for l in range(L)] for a in range(K)]
+        out, nacc, fb, _ = TW.tree_walk(p_nodes, q_nodes, paths, u, 0, 0.0)
+        act = list(range(K)); want = []; oks = 0
+        for l in range(L):
+            pr, qr = node(tuple(want))
+            sol = G.solve_row(pr, qr, len(act), 0, tol=0.0)
+            pi, _ = G.policy_slice(sol, pr, [paths[a][l] for a in act])
+            tok, ok, _ = G.sample_token(pi, [paths[a][l] for a in act], float(u[l]))
+            want.append(tok)
+            if not ok:
+                break
+            oks += 1
+            act = [a for a in act if paths[a][l] == tok]
+        assert out == want and fb == 0 and nacc == oks
