@@ -129,7 +129,11 @@ int gr_solve_logits(gr_handle h, const float* target_logits, const float* draft_
  * (Sec. 7, first experiment; top-k as in App. "Top-k Sampling for the Relaxed OTLP").  No convex
  * program runs.
  * p, q        [B, V] float32 device arrays, as for gr_solve.
- * ks          HOST array of nk top-k sizes, 1 <= nk <= GR_SWEEP_MAX_K, each 1..GR_MAX_SUPPORT.
+ * ks          HOST array of nk top-k sizes, 1 <= nk <= GR_SWEEP_MAX_K; k <= 0 or k >= V means no top-k.  When every
+ *             k is at most GR_MAX_SUPPORT the grid is served from one streaming pass; otherwise (the study runs k
+ *             up to the whole vocabulary) the handle must have been created with max_k at least the largest
+ *             (GR_EINVAL otherwise) and the whole grid runs on the HBM-resident ordering: one sort by q/p, one
+ *             by q, masked prefix scans.
  * ns          HOST array of nn draft counts, 1 <= nn <= GR_SWEEP_MAX_N, each 1..GR_SWEEP_MAX_DRAFTS.
  * accept_prob [B, nk, nn] float32 device out (NaN for a bad row).   status [B] int32 device out:
  *             GR_ROW_OK or GR_ROW_BAD.

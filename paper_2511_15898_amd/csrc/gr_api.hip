@@ -32,6 +32,7 @@ struct gr_handle_s {
     int prof_count = 0;
     // full-vocabulary path: workspace (allocated by gr_create when k_cap exceeds GR_MAX_SUPPORT) and the arguments of the last such solve
     void* full_ws = nullptr; size_t full_ws_bytes = 0;
+    double* sweep_mass = nullptr;  // [max_B, kSweepMaxK] q mass of each top-k support of a sweep that runs in the workspace
     FullParams full = {};
     bool full_mode = false;
     // staging of gr_tree_walk (allocated by its first call): gathered rows, drafts, uniforms, results, row offsets
@@ -55,7 +56,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status, h->newton_ws, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status, h->sweep_mass, h->newton_ws, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -230,7 +231,7 @@ extern "C" int gr_create(gr_handle* out, int max_B, int max_V, int max_k, int ma
     if (ok && k_cap > kMaxSupport) {
         // supports above GR_MAX_SUPPORT live in HBM: 128 bytes per token of max_V and row, held until gr_destroy
         const size_t need = full_ws_bytes(rows, static_cast<size_t>(max_V) + 2);
-        ok = hipMalloc(&h->full_ws, need) == hipSuccess;
+        ok = hipMalloc(&h->full_ws, need) == hipSuccess && dev_alloc(&h->sweep_mass, rows * kSweepMaxK);
         if (ok) h->full_ws_bytes = need;
     }
     if (!ok) { free_all(h); delete h; (void)hipGetLastError(); return GR_ENOMEM; }
@@ -300,10 +301,39 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
                                int B, int V, float* accept_prob, int* status, void* hip_stream) {
     if (!h || !p || !q || !ks || !ns || !accept_prob || !status) return GR_EINVAL;
     if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    {
+        // a top-k above GR_MAX_SUPPORT anywhere in the grid (k <= 0 or k >= V: no top-k): the whole grid runs on
+        // the HBM-resident ordering
+        int kmax = 0;
+        if (nk < 1 || nk > kSweepMaxK || nn < 1 || nn > kSweepMaxN) return GR_EINVAL;
+        for (int i = 0; i < nk; ++i) { const int ke = (ks[i] <= 0 || ks[i] >= V) ? V : ks[i]; if (ke > kmax) kmax = ke; }
+        if (kmax > kMaxSupport) {
+            if (kmax > h->k_cap) return GR_EINVAL;                   // the handle holds no workspace for such a support
+            if (V >= (1 << 24)) return GR_EUNSUPPORTED;
+            FullSweep fs;
+            fs.nk = nk; fs.nn = nn;
+            for (int i = 0; i < kSweepMaxK; ++i) fs.ks[i] = i < nk ? ((ks[i] <= 0 || ks[i] >= V) ? V : ks[i]) : 0;
+            for (int i = 0; i < kSweepMaxN; ++i) {
+                if (i < nn && (ns[i] < 1 || ns[i] > kSweepMaxDrafts)) return GR_EINVAL;
+                fs.ns[i] = i < nn ? ns[i] : 1;
+            }
+            h->solved = false;
+            const int rc = prepare_full(h, B, V);
+            if (rc != GR_OK) return rc;
+            FullParams& f = h->full;
+            f.p = p; f.q = q; f.B = B; f.V = V; f.n = 1; f.k = kmax; f.max_T = h->max_T; f.max_iter = h->max_iter;
+            f.tau = 0.0; f.rel_tol = h->rel_tol; f.tail_mass = 0.0;
+            f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
+            fs.mass = h->sweep_mass; fs.accept_prob = accept_prob; fs.status = status;
+            launch_full_sweep(f, fs, stream);
+            if (hipGetLastError() != hipSuccess) return GR_EHIP;
+            return GR_OK;
+        }
+    }
     SweepParams sw;
     const int rcf = fill_sweep(sw, ks, nk, ns, nn, V);
     if (rcf != GR_OK) return rcf;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int splits = choose_splits(B, V);
     int slice_len = (V + splits - 1) / splits;
     slice_len = (slice_len + kSelTile - 1) / kSelTile * kSelTile;

@@ -692,6 +692,146 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     }
 }
 
+// ---- acceptance sweep over supports that do not fit LDS (the first experiment of Sec. 7 runs the top-k size up to
+// the whole vocabulary).  Behind full_order_kernel with the grid's largest k: kernel A ranks the support by
+// decreasing q (ties by token id) and leaves, by ratio rank, p / sum p, q and the q rank of every token, plus the
+// q mass of each top-k support of the grid; kernel B takes the masked prefix sums along the ratio order and
+// the minimum of F(m) = P_m - Q_m^n for every cell (Thm 3.1, Sec. 5.1).  Only min F is reported, to 1e-5, so these
+// sums are parallel float64 scans like those of the LDS-resident sweep.
+__global__ __launch_bounds__(kThreads) void full_sweep_rank_kernel(FullParams fp, FullSweep fs) {
+    __shared__ SortLds S;
+    __shared__ double red[kWaves];
+    const int tid = threadIdx.x, row = blockIdx.x;
+    const int V = fp.V;
+    const size_t vs = static_cast<size_t>(V) + 2;
+    const RowInfo info = fp.info[row];
+    if (info.status == GR_ROW_BAD) return;
+    const int kk = info.support;
+    const float* pr = fp.p + static_cast<size_t>(row) * V;
+    const float* qr = fp.q + static_cast<size_t>(row) * V;
+    const int* order = fp.order + row * vs;
+    unsigned long long* k0 = fp.key0 + row * vs; unsigned long long* k1 = fp.key1 + row * vs;
+    int* v0 = fp.val0 + row * vs; int* v1 = fp.val1 + row * vs;
+    double* pn = fp.pn + row * vs; double* qn = fp.qn + row * vs;
+    int* qrank = fp.blk + row * vs;                              // by ratio rank: the token's rank by decreasing q
+    for (int r0 = tid; r0 < kk; r0 += 4 * kThreads) {
+        int id[4]; float qv[4], pv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const int r = r0 + j * kThreads; id[j] = r < kk ? order[r] : 0; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { qv[j] = qr[id[j]]; pv[j] = pr[id[j]]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + j * kThreads;
+            if (r < kk) {
+                const unsigned long long qb = static_cast<unsigned long long>(~__float_as_uint(qv[j]) & 0x7FFFFFFFu);
+                k0[r] = (qb << 24) | static_cast<unsigned long long>(id[j]);
+                v0[r] = r;
+                pn[r] = static_cast<double>(pv[j]) / info.p_total;
+                qn[r] = static_cast<double>(qv[j]);
+            }
+        }
+    }
+    __syncthreads();
+    const int res = block_radix_sort(k0, v0, k1, v1, kk, S);
+    const int* sorted = res ? v1 : v0;
+    // sorted[j] = ratio rank of the token of q rank j; the q mass of the first k of them for every k of the grid
+    double part[kSweepMaxK];
+#pragma unroll
+    for (int a = 0; a < kSweepMaxK; ++a) part[a] = 0.0;
+    for (int j = tid; j < kk; j += kThreads) {
+        const int r = sorted[j];
+        qrank[r] = j;
+        const double qv = qn[r];
+#pragma unroll
+        for (int a = 0; a < kSweepMaxK; ++a) if (a < fs.nk && j < fs.ks[a]) part[a] += qv;
+    }
+#pragma unroll
+    for (int a = 0; a < kSweepMaxK; ++a) {
+        const double t = block_sum(part[a], red);
+        if (tid == 0 && a < fs.nk) fs.mass[row * kSweepMaxK + a] = t;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void full_sweep_scan_kernel(FullParams fp, FullSweep fs) {
+    __shared__ double wtot[2][kWaves];
+    __shared__ double cell[kSweepMaxK][kSweepMaxN][kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
+    const size_t vs = static_cast<size_t>(fp.V) + 2;
+    const int cells = fs.nk * fs.nn;
+    float* out = fs.accept_prob + static_cast<size_t>(row) * cells;
+    const RowInfo info = fp.info[row];
+    if (info.status == GR_ROW_BAD) {
+        for (int c = tid; c < cells; c += kThreads) out[c] = __uint_as_float(0x7fc00000u);
+        if (tid == 0) fs.status[row] = GR_ROW_BAD;
+        return;
+    }
+    const int kk = info.support;
+    const double* pn = fp.pn + row * vs; const double* qn = fp.qn + row * vs;
+    const int* qrank = fp.blk + row * vs;
+    for (int c = tid; c < kSweepMaxK * kSweepMaxN * kWaves; c += kThreads) (&cell[0][0][0])[c] = 0.0;   // F(0) = 0: the empty prefix
+    double carryP[kSweepMaxK], carryS[kSweepMaxK], mass[kSweepMaxK];
+#pragma unroll
+    for (int a = 0; a < kSweepMaxK; ++a) { carryP[a] = 0.0; carryS[a] = 0.0; mass[a] = a < fs.nk ? fs.mass[row * kSweepMaxK + a] : 1.0; }
+    __syncthreads();
+    for (int t0 = 0; t0 < kk; t0 += 4 * kThreads) {             // 1024 ranks per round, four consecutive ones per thread
+        double pv[4], qv[4]; int qrk[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = t0 + 4 * tid + j;
+            pv[j] = r < kk ? pn[r] : 0.0; qv[j] = r < kk ? qn[r] : 0.0; qrk[j] = r < kk ? qrank[r] : 0x7fffffff;
+        }
+#pragma unroll
+        for (int a = 0; a < kSweepMaxK; ++a) {
+            if (a >= fs.nk) continue;                            // uniform over the workgroup
+            const int ka = fs.ks[a];
+            double lp[4], ls[4];
+            double accp = 0.0, accs = 0.0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { const bool on = qrk[j] < ka; accp += on ? pv[j] : 0.0; accs += on ? qv[j] : 0.0; lp[j] = accp; ls[j] = accs; }
+            // exclusive prefix of the threads' sums over the workgroup
+            double ip = accp, is = accs;
+            for (int o = 1; o < 64; o <<= 1) {
+                const double up = __shfl_up(ip, o), us = __shfl_up(is, o);
+                if (lane >= o) { ip += up; is += us; }
+            }
+            if (lane == 63) { wtot[0][wv] = ip; wtot[1][wv] = is; }
+            __syncthreads();
+            double bp = carryP[a] + (ip - accp), bs = carryS[a] + (is - accs), tp = 0.0, ts = 0.0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) { if (w < wv) { bp += wtot[0][w]; bs += wtot[1][w]; } tp += wtot[0][w]; ts += wtot[1][w]; }
+            carryP[a] += tp; carryS[a] += ts;
+            const double inv = 1.0 / mass[a];
+            for (int b = 0; b < fs.nn; ++b) {
+                double m = 0.0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // a rank outside this support repeats the prefix before it; ranks beyond the support add nothing
+                    const double F = (bp + lp[j]) - ipow((bs + ls[j]) * inv, fs.ns[b]);
+                    m = fmin(m, (t0 + 4 * tid + j < kk) ? F : 0.0);
+                }
+                m = wave_min(m);
+                if (lane == 0) cell[a][b][wv] = fmin(cell[a][b][wv], m);
+            }
+            __syncthreads();                                     // wtot is rewritten by the next k
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < cells; c += kThreads) {
+        const int a = c / fs.nn, b = c % fs.nn;
+        double t = cell[a][b][0];
+        for (int w = 1; w < kWaves; ++w) t = fmin(t, cell[a][b][w]);
+        out[c] = static_cast<float>(1.0 + t);
+    }
+    if (tid == 0) fs.status[row] = GR_ROW_OK;
+}
+
+void launch_full_sweep(const FullParams& fp, const FullSweep& fs, hipStream_t stream) {
+    hipLaunchKernelGGL(full_order_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);
+    hipLaunchKernelGGL(full_sweep_rank_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp, fs);
+    hipLaunchKernelGGL(full_sweep_scan_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp, fs);
+}
+
 void launch_full_prologue(const FullParams& fp, hipStream_t stream) {
     hipLaunchKernelGGL(full_order_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);
     hipLaunchKernelGGL(full_scan_kernel, dim3(fp.B), dim3(kThreads), 0, stream, fp);

@@ -79,6 +79,8 @@ struct FullParams {
 constexpr size_t kFullBytesPerToken = 2 * 8 + 2 * 4 + 2 * 4 + 8 * 8 + 5 * 4 + 4 + 8;
 
 void launch_full_prologue(const FullParams& fp, hipStream_t stream);
+struct FullSweep;
+void launch_full_sweep(const FullParams& fp, const FullSweep& fs, hipStream_t stream);
 void launch_select(const float* p, const float* q, int B, int V, int k, int splits, int slice_len,
                    unsigned long long* cand, int* cand_count, double* psum, double* qsum, int* bad,
                    double* piece_psum, int piece_stride, hipStream_t stream);
@@ -117,6 +119,14 @@ struct SweepParams {
     int* status;                  // [B]
 };
 hipError_t launch_sweep(const SweepParams& sw, int B, hipStream_t stream);
+// The grid of a sweep whose largest support lives in the HBM workspace.
+struct FullSweep {
+    int nk, nn;
+    int ks[kSweepMaxK]; int ns[kSweepMaxN];   // ks: V for "no top-k"
+    double* mass;                 // [B, kSweepMaxK] q mass of each top-k support
+    float* accept_prob;           // [B, nk, nn]
+    int* status;                  // [B]
+};
 hipError_t solve_kernel_setup();
 
 // ---------------------------------------------------------------- device helpers

@@ -10,10 +10,10 @@ pytestmark = pytest.mark.gpu
 ABS_TOL = 1e-5          # spec tolerance on alpha*
 
 
-def _sweep(p, q, ks, ns):
+def _sweep(p, q, ks, ns, max_k=gr.GR_MAX_SUPPORT):
     dev = torch.device("cuda:0")
     B, V = p.shape
-    h = gr.gr_create(B, V)
+    h = gr.gr_create(B, V, max_k=max_k)
     try:
         acc, st = gr.gr_accept_sweep(h, torch.from_numpy(p).to(dev), torch.from_numpy(q).to(dev), ks, ns)
         torch.cuda.synchronize()
@@ -141,3 +141,34 @@ def test_random_grids(seed):
         acc, st = _sweep(np.ascontiguousarray(p), np.ascontiguousarray(q), ks, ns)
         assert np.all(st == 0), (seed, case)
         _check(p, q, ks, ns, range(B), acc)
+
+
+def test_top_k_sizes_up_to_the_whole_vocabulary():
+    """Sec. 7, first experiment: the acceptance study runs k from 10 to V.  Grids that reach beyond GR_MAX_SUPPORT
+    run on the HBM-resident ordering; every cell against the checker on mid-size rows, cells at or below
+    GR_MAX_SUPPORT also against the streaming route, and acceptance must not fall when k grows at n = 1...
+    (it need not be monotone in k for n > 1, so only the checker decides there)."""
+    wl = W.llm_shaped(B=12, V=5000, n=4, k=0, seed_sub=71)
+    ks, ns = [10, 100, 256, 1000, 4999, 0], [1, 2, 4, 8, 16]
+    acc, st = _sweep(wl.p, wl.q, ks, ns, max_k=0)
+    assert np.all(st == 0)
+    _check(wl.p, wl.q, ks, ns, range(wl.B), acc)
+    small, _ = _sweep(wl.p, wl.q, [10, 100, 256], ns)
+    assert np.abs(small - acc[:, :3, :]).max() < 2e-6
+    assert np.all(np.diff(acc, axis=2) >= -1e-6)
+    with pytest.raises(gr.GrError) as e:                  # a handle without the workspace refuses the large grid
+        _sweep(wl.p, wl.q, ks, ns)
+    assert e.value.code == gr.GR_EINVAL
+    # rows with exact zeros in q and a top-k above the number of positive entries
+    q = wl.q.copy(); q[:, ::3] = 0.0; q = (q / q.sum(1, keepdims=True, dtype=np.float32)).astype(np.float32)
+    acc, st = _sweep(wl.p, q, [300, 2000, 0], [2, 5], max_k=0)
+    _check(wl.p, q, [300, 2000, 0], [2, 5], range(wl.B), acc)
+
+
+def test_top_k_sizes_up_to_the_whole_vocabulary_at_full_width():
+    """Two rows of the large-vocabulary configuration, k up to V = 128256 (the checker orders 128256 tokens per k)."""
+    wl = W.large_vocab(B=2)
+    ks, ns = [128, 1000, 10000, 0], [2, 8]
+    acc, st = _sweep(wl.p, wl.q, ks, ns, max_k=0)
+    assert np.all(st == 0)
+    _check(wl.p, wl.q, ks, ns, range(wl.B), acc)
