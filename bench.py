@@ -85,11 +85,13 @@ def bench_sweep(args):
     from paper_2511_15898_amd import binding as gr, workloads as W
     wl = W.large_vocab()
     ks, ns = [8, 16, 32, 64, 128, 256], list(range(1, 11))
+    if args.sweep_to_v:
+        ks = [10, 100, 1000, 10000, 100000, 0]          # the study's grid: powers of ten up to the whole vocabulary (0)
     dev = torch.device("cuda:0")
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
     acc = torch.empty((wl.B, len(ks), len(ns)), dtype=torch.float32, device=dev)
     st = torch.empty(wl.B, dtype=torch.int32, device=dev)
-    h = gr.gr_create(wl.B, wl.V)
+    h = gr.gr_create(wl.B, wl.V, max_k=0 if args.sweep_to_v else gr.GR_MAX_SUPPORT)
     for _ in range(args.warmup):
         gr.gr_accept_sweep(h, p, q, ks, ns, acc, st)
     torch.cuda.synchronize()
@@ -109,6 +111,8 @@ def bench_sweep(args):
         c0 = time.perf_counter(); rows = 0
         while rows < wl.B and time.perf_counter() - c0 < 10.0:
             G.acceptance_sweep(wl.p[rows], wl.q[rows], ks, ns); rows += 1
+            if args.sweep_to_v:
+                break                                   # the checker orders 128256 tokens per k: one row is the sample
         cdt = time.perf_counter() - c0
         cpu = {"value": rows / cdt, "unit": "rows/s", "cores": 1, "kind": "oracle",
                "sample": f"first {rows} rows of the same batch, {cdt:.1f} s, single thread"}
@@ -119,7 +123,7 @@ def bench_sweep(args):
         "config": {"workload": f"sweep on {wl.name}: B={wl.B} rows x V={wl.V} vocab, top-k in {ks}, drafts in {ns}",
                    "B": wl.B, "V": wl.V, "ks": ks, "ns": ns, "cells_per_row": len(ks) * len(ns)},
         "status_histogram": [int(x) for x in np.bincount(st.cpu().numpy(), minlength=4)],
-        "roofline": {"bound": "hbm", "kernel": "select_kernel + sweep_kernel (one gr_accept_sweep call)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("full_order + full_sweep_rank + full_sweep_scan kernels" if args.sweep_to_v else "select_kernel + sweep_kernel") + " (one gr_accept_sweep call)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "call_ms": call_ms},
         "cpu_baseline": cpu,
@@ -136,6 +140,11 @@ def main():
                     help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    ap.add_argument("--logits", action="store_true",
+                    help="side measurement: feed the same rows as float32 logits and temperatures to gr_solve_logits "
+                         "(workloads large / llm / small); the drafts of the probability rows are kept")
+    ap.add_argument("--sweep-to-v", action="store_true",
+                    help="workload sweep: run the top-k sizes up to the whole vocabulary (HBM-resident ordering)")
     ap.add_argument("--tail-mass", type=float, default=0.0,
                     help="nucleus cut of the draft (gr_config.tail_mass) for workloads without a top-k; 0: none")
     ap.add_argument("--streams", type=int, default=3,
@@ -155,8 +164,13 @@ def main():
     import torch
     from paper_2511_15898_amd import binding as gr, workloads as W
 
-    wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small, "stress": W.stress,
-          "stress_full": lambda: W.stress(k=0)}[args.workload]()     # stress_full: no top-k, the support is the whole row
+    if args.logits and args.workload not in ("large", "llm", "small"):
+        sys.exit("bench.py: --logits goes with the workloads large, llm and small")
+    if args.logits:
+        wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small}[args.workload](keep_logits=True)
+    else:
+        wl = {"large": W.large_vocab, "llm": W.llm_shaped, "small": W.small, "stress": W.stress,
+              "stress_full": lambda: W.stress(k=0)}[args.workload]()     # stress_full: no top-k, the support is the whole row
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.tol)      # before the GPU is touched: it forks workers
     dev = torch.device("cuda:0")
     p = torch.from_numpy(wl.p).to(dev); q = torch.from_numpy(wl.q).to(dev)
@@ -165,8 +179,17 @@ def main():
     tok = torch.empty(wl.B, dtype=torch.int32, device=dev); ok = torch.empty(wl.B, dtype=torch.uint8, device=dev)
     h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n, flags=0 if args.no_events else gr.GR_FLAG_PROFILE, tail_mass=args.tail_mass)
 
+    if args.logits:
+        # the float32 logits stand in for p and q (never written as probabilities); a draft that the logits' top-k
+        # does not hold (float32 ties of q) gives token -1 for that row and changes no timing
+        p = torch.from_numpy(wl.meta["target_logits"]).to(dev); q = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
+        temps = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
+
     def step():
-        gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
+        if args.logits:
+            gr.gr_solve_logits(h, p, q, temps, wl.n, wl.k, args.tol, acc, st)
+        else:
+            gr.gr_solve(h, p, q, wl.n, wl.k, args.tol, acc, st)
         gr.gr_verify(h, d, u, tok, ok)
 
     if args.pmc_copy:
@@ -217,7 +240,10 @@ def main():
         def pstep(i):
             j = i % ns
             a, s_, t_, o_ = outs[j]
-            gr.gr_solve(hs[j], ins[j][0], ins[j][1], wl.n, wl.k, args.tol, a, s_, stream=ss[j])
+            if args.logits:
+                gr.gr_solve_logits(hs[j], ins[j][0], ins[j][1], temps, wl.n, wl.k, args.tol, a, s_, stream=ss[j])
+            else:
+                gr.gr_solve(hs[j], ins[j][0], ins[j][1], wl.n, wl.k, args.tol, a, s_, stream=ss[j])
             gr.gr_verify(hs[j], d, u, t_, o_, stream=ss[j])
 
         for i in range(max(args.warmup, 2 * ns)):
@@ -299,7 +325,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
-                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "streams": 1},
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "rows_given_as": "logits" if args.logits else "probabilities", "streams": 1},
         "step_events": step_events,
         "pipelined": pipelined,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],

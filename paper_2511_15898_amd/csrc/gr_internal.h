@@ -264,14 +264,15 @@ __device__ __forceinline__ void wave_sequential_scan(const double* x, double* ou
 #pragma clang fp contract(fast)
 
 // e^{-y} for y >= 0 with a 32-entry table: y = k ln2/32 + r, |r| <= ln2/64, e^{-y} =
-// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15).
+// 2^-(k>>5) * tab[k&31] * e^{-r} with tab[j] = 2^(-j/32) and a degree-5 polynomial (error < 3e-15 + 1.2e-16 y:
+// the reduction is one fused multiply-add with the double nearest to ln2/32, whose own error times k is all
+// that is lost; beyond y = 40 the result is below 1e-17 of anything it is added to).
 __device__ __forceinline__ double exp_neg(double y, const double* tab) {
     const double yc = fmin(y, 1000.0);
     const double kf = rint(yc * 46.166241308446828);
     const int ki = static_cast<int>(kf);
     const double tv = tab[ki & 31];
-    double r = fma(kf, -(6.93147180369123816490e-01 / 32.0), yc);
-    r = -fma(kf, -(1.90821492927058770002e-10 / 32.0), r);
+    const double r = -fma(kf, -(6.93147180559945309417e-01 / 32.0), yc);
     double p = 8.33333333333333333333e-03;
     p = fma(p, r, 4.16666666666666666667e-02);
     p = fma(p, r, 1.66666666666666666667e-01);
@@ -279,6 +280,23 @@ __device__ __forceinline__ double exp_neg(double y, const double* tab) {
     p = fma(p, r, 1.0);
     p = fma(p, r, 1.0);
     return ldexp(p * tv, -(ki >> 5));                          // 2^-1442 flushes to 0
+}
+
+// Two of them at once, so that both table entries are on their way before either polynomial starts (the table read
+// is the one long latency of the routine).
+__device__ __forceinline__ void exp_neg2(double y0, double y1, const double* tab, double& x0, double& x1) {
+    const double c0 = fmin(y0, 1000.0), c1 = fmin(y1, 1000.0);
+    const double k0 = rint(c0 * 46.166241308446828), k1 = rint(c1 * 46.166241308446828);
+    const int i0 = static_cast<int>(k0), i1 = static_cast<int>(k1);
+    const double t0 = tab[i0 & 31], t1 = tab[i1 & 31];
+    const double r0 = -fma(k0, -(6.93147180559945309417e-01 / 32.0), c0), r1 = -fma(k1, -(6.93147180559945309417e-01 / 32.0), c1);
+    double p0 = 8.33333333333333333333e-03, p1 = 8.33333333333333333333e-03;
+    p0 = fma(p0, r0, 4.16666666666666666667e-02); p1 = fma(p1, r1, 4.16666666666666666667e-02);
+    p0 = fma(p0, r0, 1.66666666666666666667e-01); p1 = fma(p1, r1, 1.66666666666666666667e-01);
+    p0 = fma(p0, r0, 0.5); p1 = fma(p1, r1, 0.5);
+    p0 = fma(p0, r0, 1.0); p1 = fma(p1, r1, 1.0);
+    p0 = fma(p0, r0, 1.0); p1 = fma(p1, r1, 1.0);
+    x0 = ldexp(p0 * t0, -(i0 >> 5)); x1 = ldexp(p1 * t1, -(i1 >> 5));
 }
 
 // Candidate key: larger q first, ties to the lower token id.  q >= 0, so its bit pattern is

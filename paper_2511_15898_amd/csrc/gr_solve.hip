@@ -293,8 +293,7 @@ __device__ __forceinline__ double pick_series(NodeRec<D>& rec, const double (&T)
 // for k <= C (C = D: exact; C = 4 for a token so small that its higher terms cannot reach the z^n
 // coefficient within 1e-11).
 template <int D, int C>
-__device__ __forceinline__ void phase1_token(double (&K)[D], const TokRec<D>& r, double t, const double* tab) {
-    const double x = exp_neg(t * r.aw, tab);
+__device__ __forceinline__ void phase1_token(double (&K)[D], const TokRec<D>& r, double x) {
     const double v = fma(-x, x, x), s = fma(-2.0, x, 1.0);
     K[0] = fma(x, r.e[0], K[0]);
     if constexpr (C >= 2) {
@@ -315,18 +314,18 @@ __device__ __forceinline__ void phase1_range(double (&K)[D], const TokRec<D>* tr
     for (int b = first; b < last; b += 2 * NS) {           // uniform trip count; the pad record has x = 0
         const int i1 = b + tsub + NS, i2 = b + tsub + 2 * NS;
         const TokRec<D> nxt = trec[i1 < last ? i1 : pad];
-        phase1_token<D, C>(K, cur, t, tab);
+        double x0, x1;
+        exp_neg2(t * cur.aw, t * nxt.aw, tab, x0, x1);
+        phase1_token<D, C>(K, cur, x0);
         cur = trec[i2 < last ? i2 : pad];
-        phase1_token<D, C>(K, nxt, t, tab);
+        phase1_token<D, C>(K, nxt, x1);
     }
 }
 
 // Phase 3, one token at one node: (e^u - 1) / (1 + x (e^u - 1)) = sum_k g_k(x) u^k / k!, so the
 // leave-one-out coefficient is sum_{k <= C} g_k(x) (q^k / k!) T_{n-k}.
 template <int D, int C>
-__device__ __forceinline__ void phase3_pair(const NodeRec<D>& c, const double (&e)[D], double wt, const double* tab,
-                                            double& acc, double& at) {
-    const double x = exp_neg(c.t * wt, tab);
+__device__ __forceinline__ void phase3_pair(const NodeRec<D>& c, const double (&e)[D], double x, double& acc, double& at) {
     const double v = fma(-x, x, x), s = fma(-2.0, x, 1.0);
     double g[C];
     cum_g_from<1, C>(v, s, g);
@@ -366,9 +365,11 @@ __device__ __forceinline__ void phase3_range(LdsT& L, int first, int last, int p
         for (int r = 0; r < rounds; r += 2) {
             const int j1 = ns + (r + 1) * nsub, j2 = ns + (r + 2) * nsub;
             const NodeRec<D> nxt = L.nrec[wv][j1 < NPW ? j1 : ns];
-            phase3_pair<D, C>(cur, tr.e, tr.aw, L.e2tab, acc, at);
+            double x0, x1;
+            exp_neg2(cur.t * tr.aw, nxt.t * tr.aw, L.e2tab, x0, x1);
+            phase3_pair<D, C>(cur, tr.e, x0, acc, at);
             cur = L.nrec[wv][j2 < NPW ? j2 : ns];
-            if (r + 1 < rounds) phase3_pair<D, C>(nxt, tr.e, tr.aw, L.e2tab, acc, at);
+            if (r + 1 < rounds) phase3_pair<D, C>(nxt, tr.e, x1, acc, at);
         }
         if (ts_log <= 5) { acc += __shfl_xor(acc, 32); at += __shfl_xor(at, 32); }
         if (ts_log <= 4) { acc += __shfl_xor(acc, 16); at += __shfl_xor(at, 16); }
