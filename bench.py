@@ -140,6 +140,9 @@ def main():
                     help="large = the configuration the metric is quoted on; the others are side measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events")
+    ap.add_argument("--event-stride", type=int, default=4,
+                    help="record the per-kernel HIP events on every N-th step of the timed region (five event records per "
+                         "step cost about 8 %% of a step here); the per-step events are recorded on every step")
     ap.add_argument("--logits", action="store_true",
                     help="side measurement: feed the same rows as float32 logits and temperatures to gr_solve_logits "
                          "(workloads large / llm / small); the drafts of the probability rows are kept")
@@ -203,6 +206,7 @@ def main():
     torch.cuda.synchronize()
     if not args.no_events:
         gr.gr_profile_read(h)                      # drop the warm-up events
+        gr.gr_profile_stride(h, max(1, args.event_stride))
     # HIP events around every step on the stream the kernels are launched on (torch's current stream)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if not args.no_events else None
     t0 = time.perf_counter()
@@ -310,6 +314,7 @@ def main():
         roofline["region"] = "the timed region: one stream, one batch at a time (launch durations from HIP events)"
         roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
         roofline["events_steps"] = prof["steps"]
+        roofline["events_every"] = max(1, args.event_stride)
         roofline["select_hbm_frac"] = algo_bytes / (kernels[first] * 1e-3) / 1e9 / HBM_PEAK_GBS
         roofline["step_hbm_frac"] = algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
         if step_events:

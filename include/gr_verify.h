@@ -238,6 +238,11 @@ int gr_solve_stats(gr_handle h, int* evaluations, double* node_tokens, void* hip
  * All four outputs are HOST pointers. */
 int gr_profile_read(gr_handle h, double* select_ms, double* solve_ms, double* verify_ms, int* steps);
 
+/* Measurement hook: record the events of GR_FLAG_PROFILE only on every stride-th gr_solve (and the gr_verify that
+ * follows it), so that a timed loop is not slowed by five event records per step.  stride >= 1 (GR_EINVAL);
+ * GR_ESTATE on a handle created without GR_FLAG_PROFILE.  The count starts again with the next gr_solve. */
+int gr_profile_stride(gr_handle h, int stride);
+
 const char* gr_strerror(int code);
 
 #ifdef __cplusplus

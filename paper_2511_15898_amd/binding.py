@@ -19,7 +19,7 @@ GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED, GR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 GR_NOALLOC_MAX_B = 256
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_profile_stride", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -61,6 +61,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_policy_export.argtypes = [vp] * 9
     lib.gr_solve_stats.argtypes = [vp] * 4
     lib.gr_policy_export_row.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
+    lib.gr_profile_stride.argtypes = [vp, ci]
     lib.gr_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.gr_strerror.argtypes = [ci]
@@ -276,6 +277,12 @@ def gr_policy_export_row(handle: int, row: int, count: int, device, stream=None)
     if rc != GR_OK:
         raise GrError(rc, "gr_policy_export_row")
     return out
+
+
+def gr_profile_stride(handle: int, stride: int) -> None:
+    rc = load_library().gr_profile_stride(handle, stride)
+    if rc != GR_OK:
+        raise GrError(rc, "gr_profile_stride")
 
 
 def gr_solve_stats(handle: int, B: int, device, stream=None) -> dict:

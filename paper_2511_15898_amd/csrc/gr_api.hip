@@ -28,6 +28,8 @@ struct gr_handle_s {
     // optional per-kernel timing (gr_config.flags bit 0): events around every launch, read back
     // by gr_profile_read
     bool profile = false;
+    int prof_stride = 1, prof_tick = 0;   // events are recorded on every prof_stride-th solve (and the verify that follows it)
+    bool prof_now = false;
     hipEvent_t ev[kProfSlots][5] = {};
     int prof_count = 0;
     // full-vocabulary path: workspace (allocated by gr_create when k_cap exceeds GR_MAX_SUPPORT) and the arguments of the last such solve
@@ -47,7 +49,8 @@ struct gr_handle_s {
 namespace {
 
 void mark(gr_handle h, int which, hipStream_t stream) {
-    if (h->profile && h->prof_count < kProfSlots) (void)hipEventRecord(h->ev[h->prof_count][which], stream);
+    if (which == 0) h->prof_now = h->profile && (h->prof_tick++ % h->prof_stride == 0);
+    if (h->prof_now && h->prof_count < kProfSlots) (void)hipEventRecord(h->ev[h->prof_count][which], stream);
 }
 
 template <typename T>
@@ -385,7 +388,8 @@ extern "C" int gr_verify(gr_handle h, const int* drafts, const float* uniforms, 
     launch_verify(h->p, h->B, h->V, h->n, policy_view(h), h->info, drafts, uniforms, token, accepted, stream);
     if (hipGetLastError() != hipSuccess) return GR_EHIP;
     mark(h, 4, stream);
-    if (h->profile && h->prof_count < kProfSlots) ++h->prof_count;
+    if (h->prof_now && h->prof_count < kProfSlots) ++h->prof_count;
+    h->prof_now = false;
     return GR_OK;
 }
 
@@ -472,6 +476,13 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
         }
     }
     h->solved = false;                                           // the policy left in the handle belongs to a gathered batch
+    return GR_OK;
+}
+
+extern "C" int gr_profile_stride(gr_handle h, int stride) {
+    if (!h || stride < 1) return GR_EINVAL;
+    if (!h->profile) return GR_ESTATE;
+    h->prof_stride = stride; h->prof_tick = 0;
     return GR_OK;
 }
 
