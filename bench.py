@@ -31,9 +31,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64 lanes x 2 flop x 2.4 GHz)
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) on the default
-# workload, scaled by what the same counters read for a 256 MiB device copy in the same run
+# workload, scaled by what the same counters read for the device copy of 8 V B bytes that this script runs itself
 # (profiles/hbm_traffic_large_vocab.md).  Only valid for that workload at the default tau.
-MEASURED_TRAFFIC_BYTES = {"select_kernel": 266632000, "solve_kernel": 8921000, "verify_kernel": 603000}
+MEASURED_TRAFFIC_BYTES = {"select_kernel": 266580000, "solve_kernel": 27911000, "verify_kernel": 637000}
 
 
 def _oracle_row(job):
