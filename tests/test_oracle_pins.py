@@ -588,3 +588,43 @@ def test_tree_walk_emits_tokens_distributed_as_the_target_model():
             oks += 1
             act = [a for a in act if paths[a][l] == tok]
         assert out == want and fb == 0 and nacc == oks
+
+
+# ------------------------------------------------------------------ the convex programs against the paper's own minimiser
+def test_solver_reaches_the_minimiser_that_l_bfgs_b_finds_on_the_objective_itself():
+    """Thm 6.5 / Thm 6.4 define the weights as the minimiser of Theta_T / Phi_T.  The objective is written out here by
+    tuple enumeration (sum over draft tuples of pdraft * log(slack + sum of e^alpha over the distinct block tokens
+    drawn) minus target . alpha) and minimised with SciPy's L-BFGS-B, the paper's own choice, on numerical gradients:
+    nothing of the checker's evaluators or of its iteration enters.  The checker's solve_scaling must land on the same
+    point; so must a manufactured problem whose targets are the routed masses of known weights."""
+    from scipy.optimize import minimize
+    rng = np.random.default_rng(606)
+    for trial in range(10):
+        slack = trial % 2
+        m = int(rng.integers(2, 6)); n = int(rng.integers(2, 4))
+        q = rng.dirichlet(np.ones(m + 1))[:m] * rng.uniform(0.5, 0.95)
+        ctx = float(rng.uniform(0.0, 1.0 - q.sum())) if trial % 3 else 0.0
+        w_true = np.exp(rng.normal(0.0, 1.5, size=m))
+        target, slack_target = G.routed_enum(n, ctx, slack, q, w_true)         # a problem with a known solution
+        probs = [ctx] + [float(x) for x in q]
+        tuples = []
+        for tup in itertools.product(range(m + 1), repeat=n):
+            mass = float(np.prod([probs[a] for a in tup]))
+            members = sorted({a - 1 for a in tup if a > 0})
+            if mass > 0.0 and (members or slack):
+                tuples.append((mass, members))
+
+        def objective(alpha):
+            w = np.exp(alpha)
+            return sum(mass * math.log(slack + sum(w[j] for j in members)) for mass, members in tuples) - float(target @ alpha)
+
+        best = minimize(objective, np.zeros(m), method="L-BFGS-B", options={"ftol": 1e-15, "gtol": 1e-10, "maxiter": 2000})
+        w_ref = np.exp(best.x)
+        w, evals, err = G.solve_scaling(n, ctx, slack, q, target, slack_target, np.ones(m))
+        assert err <= 1e-10
+        if slack == 0:                                  # Phi_T is flat along a common factor: compare shares
+            w_ref = w_ref / w_ref.sum(); w = w / w.sum(); want = w_true / w_true.sum()
+        else:
+            want = w_true
+        assert np.abs(w / want - 1.0).max() < 1e-8, (trial, w, want)
+        assert np.abs(w_ref / want - 1.0).max() < 2e-4, (trial, w_ref, want)      # the library minimiser, to its own accuracy
