@@ -394,6 +394,24 @@ def solve_scaling(n, ctx, slack, q, target, slack_target, w0, rtol=1e-11, max_it
     if max_iter > 400:
         alpha, evals, err = newton_polish(n, ctx, slack, q, target, slack_target, best_alpha.copy(), rtol,
                                           max_iter - 400, evaluator)
+        if err > rtol:
+            # Both iterations can strand on a weight that a mixed step threw far beyond its value (the routed mass
+            # of such a token no longer feels its weight).  The stationary point is unique (Thm 6.5; Thm 6.4 up
+            # to a common factor), so a library root finder started from the start weights must reach the same
+            # point: SciPy's hybrid Powell method on the same equations.
+            from scipy.optimize import root
+
+            def equations(a):
+                R, R0 = evaluator(n, ctx, slack, q, np.exp(a if slack else a - a.max()))
+                common = math.log(slack_target / R0) if slack else math.log(target.sum() / R.sum())
+                return np.log(target / R) - common
+
+            sol = root(equations, np.log(np.asarray(w0, np.float64)), method="hybr", tol=1e-13)
+            a = sol.x if slack else sol.x - sol.x.max()
+            f = equations(a)
+            evals += int(sol.nfev) + 1
+            if np.all(np.isfinite(f)) and float(np.max(np.abs(f))) < err:
+                alpha, err = a, float(np.max(np.abs(f)))
         return np.exp(alpha), 400 + evals, err
     return np.exp(alpha), max_iter, err
 

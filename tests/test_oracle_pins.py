@@ -628,3 +628,17 @@ def test_solver_reaches_the_minimiser_that_l_bfgs_b_finds_on_the_objective_itsel
             want = w_true
         assert np.abs(w / want - 1.0).max() < 1e-8, (trial, w, want)
         assert np.abs(w_ref / want - 1.0).max() < 2e-4, (trial, w_ref, want)      # the library minimiser, to its own accuracy
+
+
+def test_a_target_that_nearly_exhausts_its_token_is_still_solved():
+    """A row met by a randomised run: the last token of H* has a target of 92 % of its draw probability, so its
+    weight is large (about 380) and a mixed fixed-point step can throw it so far out that the routed masses stop
+    feeling it.  The minimiser is unique (Thm 6.5): the checker must find it, and the coupling it builds must have
+    marginal p and the optimal acceptance (Sec. 3.1, Thm 3.1)."""
+    p = np.array([0.00347583, 0.81121342, 0.09828163, 0.05606862, 0.0309605], np.float64)
+    q = np.array([0.03470613, 0.89321866, 0.05135588, 0.02071933, 0.0], np.float64)
+    p = (p / p.sum()).astype(np.float32); q = (q / q.sum()).astype(np.float32)
+    sol = _check_coupling(p, q, 3, 0, 0.0, 1e-6, 1e-9)
+    assert sol.h == 4 and sol.status == G.STATUS_OK
+    w = {int(t): float(sol.w[m]) for m, t in enumerate(sol.order)}
+    assert 300.0 < w[3] < 500.0 and 50.0 < w[2] < 80.0
