@@ -138,6 +138,15 @@ def test_stress_full_vocab_cell_at_full_batch():
         _, _, F = G.prefix_psi(wl.p[b][order].astype(np.float64) / pt, wl.q[b][order], wl.n)
         assert abs(out["accept_prob"][b] - (1.0 + F.min())) < 1e-5
         assert out["h_size"][b] == int(np.argmin(F)) or np.sort(F)[1] - np.sort(F)[0] < 1e-13
+    # rows whose programs ran (status OK with evaluations): order, |H*|, residuals, blocks, slice and token of
+    # four of them against the checker, which orders all 128256 tokens of each
+    ran = np.flatnonzero((out["status"] == gr.GR_ROW_OK) & (out["iterations"] > 0))
+    assert ran.size >= wl.B // 20, ran.size
+    rows = [int(b) for b in ran[:: max(1, ran.size // 4)][:4]]
+    again = run_gpu(wl, 1e-4, export_rows=rows)
+    assert np.array_equal(again["status"], out["status"]) and np.array_equal(again["token"], out["token"])
+    stats = compare_rows(wl, again, rows, 1e-4)
+    assert stats["rows"] == 4 and stats["solved_rows"] + stats["fragile"] == 4 and stats["solved_rows"] >= 2, stats
 
 
 @pytest.mark.parametrize("V,n,k,tol", [(5000, 4, 300, 1e-4), (3000, 2, 1000, 1e-4), (1200, 8, 257, 1e-3)])
