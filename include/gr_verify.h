@@ -114,8 +114,9 @@ int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float to
  *
  * target_logits, draft_logits [B, V] float32 row-major, finite (a NaN or infinite entry gives GR_ROW_BAD).
  * temperature [B] float32, positive and finite (GR_ROW_BAD otherwise).
- * k           top-k on the draft, 1..GR_MAX_SUPPORT (also k <= 0 or k >= V when V <= GR_MAX_SUPPORT); a larger
- *             support, or a handle with tail_mass > 0, gives GR_EUNSUPPORTED.
+ * k           top-k on the draft, as in gr_solve (a support above GR_MAX_SUPPORT runs on the HBM-resident path, where
+ *             the orders are sorts on the draft logit and on draft minus target logit, and needs a handle created
+ *             with max_k at least that large).  A handle with tail_mass > 0 gives GR_EUNSUPPORTED.
  * Everything else as gr_solve.  target_logits and temperature must stay valid until the last gr_verify /
  * gr_policy_slice on this solve: they stand in for the p row there.
  */

@@ -168,6 +168,29 @@ int fill_sweep(SweepParams& sw, const int* ks, int nk, const int* ns, int nn, in
     return GR_OK;
 }
 
+// The HBM-resident path (a support above GR_MAX_SUPPORT: no top-k, or a large one) of gr_solve (temperature == nullptr)
+// and of gr_solve_logits.
+int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* temperature, int n, int k_eff, float tol, int B, int V,
+                 float* accept_prob, int* status, hipStream_t stream) {
+    if (V >= (1 << 24)) return GR_EUNSUPPORTED;
+    h->solved = false;
+    const int rc = prepare_full(h, B, V);
+    if (rc != GR_OK) return rc;
+    FullParams& f = h->full;
+    f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.k = k_eff; f.max_T = h->max_T; f.max_iter = h->max_iter;
+    f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol; f.tail_mass = h->tail_mass;
+    f.logits = temperature ? 1 : 0; f.temperature = temperature;
+    f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
+    mark(h, 0, stream);
+    launch_full_prologue(f, stream);
+    if (hipGetLastError() != hipSuccess) return GR_EHIP;
+    mark(h, 1, stream);
+    if (launch_full_programs(f, stream) != hipSuccess) return GR_EHIP;
+    mark(h, 2, stream);
+    h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
+    return GR_OK;
+}
+
 // The LDS-resident path of gr_solve (temperature == nullptr: p and q are probabilities) and of gr_solve_logits.
 int solve_in_lds(gr_handle h, const float* p, const float* q, const float* temperature, int n, int k_eff, float tol, int B, int V,
                  float* accept_prob, int* status, hipStream_t stream) {
@@ -265,25 +288,7 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
     if (k_eff <= kMaxSupport && h->tail_mass > 0.0) return GR_EUNSUPPORTED;   // the nucleus cut is for the HBM-resident path
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (k_eff > kMaxSupport) {
-        // a support above GR_MAX_SUPPORT (no top-k, or a large one): the HBM-resident path
-        if (V >= (1 << 24)) return GR_EUNSUPPORTED;
-        h->solved = false;
-        const int rc = prepare_full(h, B, V);
-        if (rc != GR_OK) return rc;
-        FullParams& f = h->full;
-        f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.k = k_eff; f.max_T = h->max_T; f.max_iter = h->max_iter;
-        f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol; f.tail_mass = h->tail_mass;
-        f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
-        mark(h, 0, stream);
-        launch_full_prologue(f, stream);
-        if (hipGetLastError() != hipSuccess) return GR_EHIP;
-        mark(h, 1, stream);
-        if (launch_full_programs(f, stream) != hipSuccess) return GR_EHIP;
-        mark(h, 2, stream);
-        h->solved = true; h->full_mode = true; h->p = p; h->B = B; h->V = V; h->n = n;
-        return GR_OK;
-    }
+    if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
     return solve_in_lds(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
 }
 
@@ -295,7 +300,11 @@ extern "C" int gr_solve_logits(gr_handle h, const float* target_logits, const fl
     if (n < 1 || n > h->max_n) return GR_EINVAL;
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
-    if (k_eff > kMaxSupport || h->tail_mass > 0.0) return GR_EUNSUPPORTED;   // only supports that the LDS-resident path holds
+    if (h->tail_mass > 0.0) return GR_EUNSUPPORTED;                         // the nucleus cut is defined on probabilities
+    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;          // the handle holds no workspace for such a support
+    if (k_eff > kMaxSupport)
+        return solve_in_hbm(h, target_logits, draft_logits, temperature, n, k_eff, tol, B, V, accept_prob, status,
+                            static_cast<hipStream_t>(hip_stream));
     return solve_in_lds(h, target_logits, draft_logits, temperature, n, k_eff, tol, B, V, accept_prob, status,
                         static_cast<hipStream_t>(hip_stream));
 }
@@ -326,7 +335,7 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
             if (rc != GR_OK) return rc;
             FullParams& f = h->full;
             f.p = p; f.q = q; f.B = B; f.V = V; f.n = 1; f.k = kmax; f.max_T = h->max_T; f.max_iter = h->max_iter;
-            f.tau = 0.0; f.rel_tol = h->rel_tol; f.tail_mass = 0.0;
+            f.tau = 0.0; f.rel_tol = h->rel_tol; f.tail_mass = 0.0; f.logits = 0; f.temperature = nullptr;
             f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
             fs.mass = h->sweep_mass; fs.accept_prob = accept_prob; fs.status = status;
             launch_full_sweep(f, fs, stream);

@@ -198,7 +198,7 @@ __device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_BAD; info.iterations = 0;
     info.alpha_star = __longlong_as_double(0x7ff8000000000000ll);
-    info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
+    info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0; info.q_ref = 0.0;
     fp.info[row] = info;
     fp.accept_prob[row] = __uint_as_float(0x7fc00000u);
     fp.status[row] = GR_ROW_BAD;
@@ -227,19 +227,47 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     unsigned long long* k0 = fp.key0 + row * vs; unsigned long long* k1 = fp.key1 + row * vs;
     int* v0 = fp.val0 + row * vs; int* v1 = fp.val1 + row * vs;
 
-    double ps = 0.0, qs = 0.0; int bad = 0;
-    for (int i = tid; i < V; i += kThreads) {
-        const float pv = pr[i], qv = qr[i];
-        bad |= !(qv >= 0.f) | !(pv >= 0.f);
-        ps += static_cast<double>(pv); qs += static_cast<double>(qv);
+    double ptot, qtot;
+    double p_ref = 0.0, q_ref = 0.0, inv_temp = 0.0;
+    if (fp.logits) {
+        // rows given as logits: the largest target and draft logit, then the target's softmax sum relative to it;
+        // q needs no sum (it is renormalised over the support).  A NaN or +inf anywhere, or a temperature that is not
+        // positive and finite, marks the row bad; -inf is a masked token.
+        const float T = fp.temperature[row];
+        float tm = -__builtin_inff(), dm = -__builtin_inff(); int bad = !(T > 0.f) || !(T <= 3.0e38f);
+        for (int i = tid; i < V; i += kThreads) {
+            const float pv = pr[i], qv = qr[i];
+            bad |= !(pv + qv < 3.0e38f);
+            tm = fmaxf(tm, pv); dm = fmaxf(dm, qv);
+        }
+        p_ref = block_max(static_cast<double>(tm), red);
+        q_ref = block_max(static_cast<double>(dm), red);
+        const int anybad = block_sum_i(bad, red);
+        inv_temp = anybad ? 0.0 : 1.0 / static_cast<double>(T);
+        double ps = 0.0;
+        if (!anybad && p_ref > -3.0e38 && q_ref > -3.0e38)
+            for (int i = tid; i < V; i += kThreads) ps += exp((static_cast<double>(pr[i]) - p_ref) * inv_temp);
+        ptot = block_sum(ps, red); qtot = 1.0;
+        if (anybad || !(ptot >= 1.0) || !(ptot < 1e300)) {
+            if (tid == 0) mark_bad(fp, row, ptot, qtot);
+            return;
+        }
+    } else {
+        double ps = 0.0, qs = 0.0; int bad = 0;
+        for (int i = tid; i < V; i += kThreads) {
+            const float pv = pr[i], qv = qr[i];
+            bad |= !(qv >= 0.f) | !(pv >= 0.f);
+            ps += static_cast<double>(pv); qs += static_cast<double>(qv);
+        }
+        ptot = block_sum(ps, red);
+        qtot = block_sum(qs, red);
+        const int anybad = block_sum_i(bad, red);
+        if (anybad || !(fabs(ptot - 1.0) <= 1e-3) || !(fabs(qtot - 1.0) <= 1e-3)) {
+            if (tid == 0) mark_bad(fp, row, ptot, qtot);
+            return;
+        }
     }
-    const double ptot = block_sum(ps, red);
-    const double qtot = block_sum(qs, red);
-    const int anybad = block_sum_i(bad, red);
-    if (anybad || !(fabs(ptot - 1.0) <= 1e-3) || !(fabs(qtot - 1.0) <= 1e-3)) {
-        if (tid == 0) mark_bad(fp, row, ptot, qtot);
-        return;
-    }
+    const bool lg = fp.logits != 0;
     // With a top-k below the number of positive entries, or a nucleus cut (tail_mass > 0; Sec. 5.1: top-p/k
     // sampling of the draft restricts the domain): order the candidates by decreasing q (ties by token id)
     // and flag the first k' of them; the support is then the flagged tokens.
@@ -291,10 +319,10 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
         for (int t0 = 0; t0 < V; t0 += 4 * kThreads) {           // 1024 tokens per round
             float qv[4]; unsigned long long mask[4]; bool take[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { const int i = t0 + j * kThreads + tid; qv[j] = i < V ? qr[i] : 0.f; }
+            for (int j = 0; j < 4; ++j) { const int i = t0 + j * kThreads + tid; qv[j] = i < V ? qr[i] : (lg ? -__builtin_inff() : 0.f); }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                take[j] = qv[j] > 0.f && (!cut || (static_cast<double>(qv[j]) >= qmin && static_cast<int>(__float_as_uint(qv[j]) >> 19) >= bstar));
+                take[j] = (lg ? qv[j] > -3.0e38f : qv[j] > 0.f) && (!cut || (static_cast<double>(qv[j]) >= qmin && static_cast<int>(__float_as_uint(qv[j]) >> 19) >= bstar));
                 mask[j] = __ballot(take[j]);
                 if (lane == 0) wtot[j * kWaves + wv] = __popcll(mask[j]);
             }
@@ -311,7 +339,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
                 const int i = t0 + j * kThreads + tid;
                 if (take[j]) {
                     const int off = cnt + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
-                    k0[off] = static_cast<unsigned long long>(~__float_as_uint(qv[j]));   // ties: the sort is stable and this is token order
+                    k0[off] = static_cast<unsigned long long>(lg ? ~mono32(qv[j]) : ~__float_as_uint(qv[j]));   // ties: the sort is stable and this is token order
                     v0[off] = i;
                 }
                 if (i < V) member[i] = 0;
@@ -357,8 +385,8 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int i = t0 + j * kThreads + tid;
-            qv[j] = i < V ? qr[i] : 0.f; pv[j] = i < V ? pr[i] : 1.f;
-            in[j] = by_flag ? (i < V && member[i] != 0) : qv[j] > 0.f;
+            qv[j] = i < V ? qr[i] : (lg ? -__builtin_inff() : 0.f); pv[j] = i < V ? pr[i] : 1.f;
+            in[j] = by_flag ? (i < V && member[i] != 0) : (lg ? qv[j] > -3.0e38f : qv[j] > 0.f);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -377,8 +405,11 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
         for (int j = 0; j < 4; ++j) {
             if (in[j]) {
                 const int off = kk + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
-                const double ratio = static_cast<double>(qv[j]) / static_cast<double>(pv[j]);   // p = 0 gives +inf: first
-                k0[off] = ~static_cast<unsigned long long>(__double_as_longlong(ratio));
+                // rows given as logits: q/p is proportional to exp((d - t) / T), so the order is that of d - t (exact in
+                // float64 for float32 logits; a masked target gives +inf: first)
+                const double ratio = lg ? static_cast<double>(qv[j]) - static_cast<double>(pv[j])
+                                        : static_cast<double>(qv[j]) / static_cast<double>(pv[j]);   // p = 0 gives +inf: first
+                k0[off] = lg ? ~mono64(ratio) : ~static_cast<unsigned long long>(__double_as_longlong(ratio));
                 v0[off] = t0 + j * kThreads + tid;
             }
         }
@@ -397,7 +428,8 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     if (tid == 0) {
         RowInfo info;
         info.support = kk; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
-        info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
+        info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = ptot; info.q_total = qtot; info.node_tokens = 0.0;
+        info.p_ref = p_ref; info.inv_temp = inv_temp; info.q_ref = q_ref;
         fp.info[row] = info;
     }
 }
@@ -435,8 +467,13 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
         for (int j = 0; j < 4; ++j) {
             const int r = r0 + j * kThreads;
             if (r < kk) {
-                pn[r] = static_cast<double>(pv[j]) / info.p_total;
-                qn[r] = static_cast<double>(qv[j]);              // raw q for now
+                if (fp.logits) {
+                    pn[r] = exp((static_cast<double>(pv[j]) - info.p_ref) * info.inv_temp) / info.p_total;
+                    qn[r] = exp((static_cast<double>(qv[j]) - info.q_ref) * info.inv_temp);
+                } else {
+                    pn[r] = static_cast<double>(pv[j]) / info.p_total;
+                    qn[r] = static_cast<double>(qv[j]);          // raw q for now
+                }
                 inT[r] = 0;
             }
         }
@@ -600,7 +637,10 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
             const int r = r0 + j * kThreads;
             if (r < kk) {
                 // q < 2, so bit 31 of ~bits(q) is always set: it carries the class instead (seven digits, not eight)
-                const unsigned long long qb = static_cast<unsigned long long>((~__float_as_uint(qv[j]) & 0x7FFFFFFFu) | (r < h ? 0u : 0x80000000u));
+                // rows given as logits: decreasing q is decreasing draft logit, whose pattern needs all 32 bits; the class moves up
+                const unsigned long long qb = fp.logits
+                    ? (static_cast<unsigned long long>(~mono32(qv[j])) | (r < h ? 0ull : 0x100000000ull))
+                    : static_cast<unsigned long long>((~__float_as_uint(qv[j]) & 0x7FFFFFFFu) | (r < h ? 0u : 0x80000000u));
                 k0[r] = (qb << 24) | static_cast<unsigned long long>(id[j]);
                 v0[r] = r;
             }

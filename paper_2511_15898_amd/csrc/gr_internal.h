@@ -29,6 +29,7 @@ struct RowInfo {
     double node_tokens; // sum over evaluator calls of (quadrature nodes x active tokens)
     double p_ref;       // rows given as logits: p(i) = exp((t_i - p_ref) inv_temp) / p_total ...
     double inv_temp;    // ... with inv_temp = 1 / temperature; 0 for rows given as probabilities
+    double q_ref;       // rows given as logits on the HBM-resident path: q(i) proportional to exp((d_i - q_ref) inv_temp)
 #ifdef GR_PHASE_CLOCKS
     long long clk[24];  // shader-clock cycles of thread 0 per phase of the solve kernel (profiling builds only)
     double errlog[24];  // stopping measure after each of the first evaluations
@@ -64,6 +65,7 @@ struct FullParams {
     int k;             // top-k on q (V: none)
     double tau, rel_tol;
     double tail_mass;  // nucleus cut of the draft: share of the draw mass that may be left out (0: none)
+    int logits; const float* temperature;   // rows given as logits (p = target logits, q = draft logits), one temperature per row
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p
     int* byq;          // ranks by (inside H* first, decreasing q, token id)
@@ -311,6 +313,15 @@ __device__ __forceinline__ unsigned long long make_key_logit(float d, int id) {
     const unsigned b = __float_as_uint(d);
     const unsigned mono = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
     return (static_cast<unsigned long long>(mono) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - static_cast<unsigned>(id));
+}
+// A double as a 64-bit pattern that rises with it (any finite value or infinity).
+__device__ __forceinline__ unsigned long long mono64(double x) {
+    const unsigned long long b = static_cast<unsigned long long>(__double_as_longlong(x));
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ unsigned mono32(float x) {
+    const unsigned b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 __device__ __forceinline__ float key_logit(unsigned long long key) {
     const unsigned mono = static_cast<unsigned>(key >> 32);

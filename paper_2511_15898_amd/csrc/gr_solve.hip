@@ -1031,7 +1031,7 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
     const int n = sp.n, V = sp.V;
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_OK; info.iterations = 0;
-    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0;
+    info.alpha_star = 0.0; info.res_total = 0.0; info.p_total = 0.0; info.q_total = 0.0; info.node_tokens = 0.0; info.p_ref = 0.0; info.inv_temp = 0.0; info.q_ref = 0.0;
 
     // ---- merge the slices
     int total = 0, bad = 0;
@@ -1377,7 +1377,11 @@ __global__ __launch_bounds__(kThreadsOf<D>) void full_programs_kernel(FullParams
     const double Fh = F[h];
 
     // tokens outside the support keep all of p as residual; then the support by rank
-    for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
+    if (fp.logits) {
+        for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = exp((static_cast<double>(pr[i]) - info.p_ref) * info.inv_temp) / info.p_total; }
+    } else {
+        for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = static_cast<double>(pr[i]) / info.p_total; }
+    }
     __syncthreads();
     for (int r0 = tid; r0 < kk; r0 += 4 * kST) {             // four independent chains of gathers per thread in flight
         int bl[4], hi[4], id[4]; double top[4], t[4], qv[4], rv[4];

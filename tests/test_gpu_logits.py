@@ -27,10 +27,12 @@ def _drafts_from_logits(wl, rows, seed):
     return drafts
 
 
-def _run_logits(wl, tol, drafts):
+def _run_logits(wl, tol, drafts, export_rows=None):
+    """A support above GR_MAX_SUPPORT has no dense export: its rows listed in `export_rows` are fetched one by one."""
     import torch
     from paper_2511_15898_amd import binding as gr
     dev = torch.device("cuda:0")
+    full = (wl.V if (wl.k <= 0 or wl.k >= wl.V) else wl.k) > gr.GR_MAX_SUPPORT
     tl = torch.from_numpy(wl.meta["target_logits"]).to(dev); dl = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
     T = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
     d = torch.from_numpy(drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)
@@ -40,9 +42,23 @@ def _run_logits(wl, tol, drafts):
         tok, ok = gr.gr_verify(h, d, u)
         out = {"accept_prob": acc, "status": st, "token": tok, "accepted": ok}
         out["pi"], out["accept_given"] = gr.gr_policy_slice(h, d, wl.V)
-        out.update(gr.gr_policy_export(h, wl.B, dev))
+        rows = {}
+        if full:
+            for name in ("support", "h_size", "iterations"):
+                out[name] = torch.empty(wl.B, dtype=torch.int32, device=dev)
+            rc = gr.load_library().gr_policy_export(h, None, None, None, None, out["support"].data_ptr(), out["h_size"].data_ptr(),
+                                                    out["iterations"].data_ptr(), torch.cuda.current_stream().cuda_stream)
+            assert rc == 0, rc
+            torch.cuda.synchronize()
+            sup = out["support"].cpu().numpy()
+            for b in (export_rows or []):
+                rows[b] = {k: v.cpu().numpy() for k, v in gr.gr_policy_export_row(h, b, int(sup[b]), dev).items()}
+        else:
+            out.update(gr.gr_policy_export(h, wl.B, dev))
         torch.cuda.synchronize()
         out = {k: v.cpu().numpy() for k, v in out.items()}
+        if full:
+            out["rows"] = rows
     finally:
         gr.gr_destroy(h)
     return out
@@ -63,9 +79,10 @@ def _compare(wl, out, rows, tol, drafts):
             continue
         kk = len(sol.order)
         assert out["status"][b] == sol.status and out["support"][b] == kk and out["h_size"][b] == sol.h, (b, out["h_size"][b], sol.h)
-        assert np.array_equal(out["order"][b, :kk], sol.order), (b, "ratio order differs")
-        assert np.array_equal(out["block"][b, :kk], sol.block_of), (b, "block split differs")
-        assert np.abs(out["rho"][b, :kk] - sol.rho).max() < 1e-12, (b, "residuals differ")
+        g = out["rows"][b] if "rows" in out else {k: out[k][b, :kk] for k in ("order", "block", "rho")}
+        assert np.array_equal(g["order"], sol.order), (b, "ratio order differs")
+        assert np.array_equal(g["block"], sol.block_of), (b, "block split differs")
+        assert np.abs(g["rho"] - sol.rho).max() < 1e-12, (b, "residuals differ")
         stats["programs"] += sum(1 for blk in sol.blocks if blk.iters > 0)
         dpi = float(np.abs(out["pi"][b] - pi).max()); stats["max_dpi"] = max(stats["max_dpi"], dpi)
         assert dpi < ABS_TOL, (b, dpi)
@@ -142,8 +159,20 @@ def test_logits_entry_point_rows_and_errors():
         assert st[0] == 0 and abs(acc[0] - out["accept_prob"][0]) < 1e-7 and abs(acc[1] - out["accept_prob"][1]) < 1e-5
         with pytest.raises(gr.GrError) as e:
             gr.gr_solve_logits(h, tl, dl, T, wl.n, 300, 1e-6)
-        assert e.value.code == gr.GR_EUNSUPPORTED
+        assert e.value.code == gr.GR_EINVAL                 # this handle holds no workspace for a support of 300
         with pytest.raises(TypeError):
             gr.gr_solve_logits(h, tl, dl, T[:3], wl.n, wl.k, 1e-6)
     finally:
         gr.gr_destroy(h)
+
+
+@pytest.mark.parametrize("V,n,k,tol", [(3000, 4, 0, 1e-4), (5000, 2, 300, 1e-4), (2000, 8, 1000, 1e-3), (777, 3, 0, 1e-3)])
+def test_logits_with_supports_above_the_lds_capacity(V, n, k, tol):
+    """Rows given as logits whose support exceeds GR_MAX_SUPPORT (no top-k, or a large one): the HBM-resident path
+    sorts on the draft logit and on draft minus target logit; every row against the checker."""
+    wl = W.llm_shaped(B=10, V=V, n=n, k=k, temperature=(0.5, 1.5), near_identical_frac=0.2, seed_sub=300 + n, keep_logits=True)
+    drafts = _drafts_from_logits(wl, set(range(wl.B)), 15)
+    out = _run_logits(wl, tol, drafts, export_rows=range(wl.B))
+    st = _compare(wl, out, range(wl.B), tol, drafts)
+    assert st["rows"] == wl.B and st["fragile"] < wl.B
+    assert np.any(out["status"] == 0)
