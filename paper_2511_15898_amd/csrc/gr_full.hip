@@ -194,6 +194,34 @@ __device__ int block_prefix_sum_excl(int v, int* buf0, int* buf1, int* total) {
     return excl;
 }
 
+// chist[4096]: members per magnitude class of a positive float (its bit pattern >> 19: exponent and four mantissa
+// bits; every member lies below the class's upper edge, so count x edge bounds the class's mass).  Classes are
+// dropped from the bottom while that bound stays within `budget`; returns the lowest class that stays (0 when every
+// class would fit: nothing is dropped then).  dscan: LDS double[kThreads], bsel: LDS int.  All threads call.
+__device__ int class_threshold(const int* chist, double budget, double* dscan, int* bsel) {
+    const int tid = threadIdx.x;
+    // thread t owns classes 16 t .. 16 t + 15; prefix of the bounds over the threads, serially by thread 0
+    double local = 0.0;
+    for (int c = 16 * tid; c < 16 * tid + 16; ++c)
+        local += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
+    dscan[tid] = local;
+    if (tid == 0) *bsel = 4096;
+    __syncthreads();
+    if (tid == 0) { double run = 0.0; for (int t = 0; t < kThreads; ++t) { const double v = dscan[t]; dscan[t] = run; run += v; } }
+    __syncthreads();
+    {
+        double run = dscan[tid];                                 // bound on the mass of all classes below 16 tid
+        for (int c = 16 * tid; c < 16 * tid + 16; ++c) {
+            run += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
+            if (run > budget) { atomicMin(bsel, c); break; }     // class c cannot be dropped whole
+        }
+    }
+    __syncthreads();
+    const int b = *bsel;
+    __syncthreads();
+    return b == 4096 ? 0 : b;
+}
+
 __device__ void mark_bad(const FullParams& fp, int row, double ptot, double qtot) {
     RowInfo info;
     info.support = 0; info.h = 0; info.status = GR_ROW_BAD; info.iterations = 0;
@@ -294,26 +322,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
                 if (static_cast<double>(qv) >= qmin && qv > 0.f) atomicAdd(&chist[__float_as_uint(qv) >> 19], 1);
             }
             __syncthreads();
-            // thread t owns classes 16 t .. 16 t + 15; prefix of the mass bounds over the threads, serially by thread 0
-            double local = 0.0;
-            for (int c = 16 * tid; c < 16 * tid + 16; ++c)
-                local += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
-            dscan[tid] = local;
-            if (tid == 0) bsel = 4096;
-            __syncthreads();
-            if (tid == 0) { double run = 0.0; for (int t = 0; t < kThreads; ++t) { const double v = dscan[t]; dscan[t] = run; run += v; } }
-            __syncthreads();
-            {
-                double run = dscan[tid];                             // bound on the mass of all classes below 16 tid
-                for (int c = 16 * tid; c < 16 * tid + 16; ++c) {
-                    run += static_cast<double>(chist[c]) * static_cast<double>(__uint_as_float((static_cast<unsigned>(c) + 1u) << 19));
-                    if (run > 0.5 * budget) { atomicMin(&bsel, c); break; }    // class c cannot be dropped whole
-                }
-            }
-            __syncthreads();
-            bstar = bsel;                                            // 4096: every class fits the budget (degenerate; keep all)
-            if (bstar == 4096) bstar = 0;
-            __syncthreads();
+            bstar = class_threshold(chist, 0.5 * budget, dscan, &bsel);
         }
         int cnt = 0;
         for (int t0 = 0; t0 < V; t0 += 4 * kThreads) {           // 1024 tokens per round
@@ -607,7 +616,9 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
 // epsilon_T <= tau outside), size of every program, row status.
 __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     __shared__ SortLds S;
-    __shared__ int cnt_in, cnt_out, act_in, capped;
+    __shared__ int cnt_in, cnt_out, act_in, capped, bsel;
+    __shared__ int wtot[8 * kWaves];
+    __shared__ double dscan[kThreads];
     __shared__ double wx[2][64];
     __shared__ double wo[2][65];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, row = blockIdx.x;
@@ -625,32 +636,72 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     const int* blk = fp.blk + row * vs; const int* blo = fp.blo + row * vs;
     int* inT = fp.inT + row * vs; int* bcount = fp.bcount + row * vs;
 
-    // ranks by (inside H* first, decreasing q, token id); four independent gathers per thread in flight
-    for (int r0 = tid; r0 < kk; r0 += 4 * kThreads) {
-        int id[4]; float qv[4];
+    // A token joins a truncation set only while the mass before it leaves more than tau.  The lowest-q tokens whose
+    // normalised masses sum to at most tau / n can therefore never join: before any of them lies everything else of
+    // its side, so what is left is at most Q^n - (Q - tau/n)^n <= tau.  They are left out of the sort (found, safely,
+    // with the magnitude-class histogram: count x upper edge bounds a class's mass); the walk over the others is
+    // the same arithmetic as before.
+    int bstar = 0;
+    if (fp.tau > 0.0) {
+        int* chist = reinterpret_cast<int*>(&S.wcnt[0][0][0]);
+        for (int c = tid; c < 4096; c += kThreads) chist[c] = 0;
+        __syncthreads();
+        for (int r = tid; r < kk; r += kThreads) {
+            const float qf = static_cast<float>(qn[r]);
+            if (qf > 0.f) atomicAdd(&chist[__float_as_uint(qf) >> 19], 1);
+        }
+        __syncthreads();
+        bstar = class_threshold(chist, (fp.tau / static_cast<double>(n)) * (1.0 - 1e-6), dscan, &bsel);   // the margin covers the rounding of q to float
+    }
+    // ranks by (inside H* first, decreasing q, token id) of the tokens that stay, compacted in rank order
+    int kept = 0, kept_in = 0;
+    for (int t0 = 0; t0 < kk; t0 += 4 * kThreads) {               // 1024 ranks per round
+        int id[4]; float qv[4]; bool take[4]; unsigned long long mask[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { const int r = r0 + j * kThreads; id[j] = r < kk ? order[r] : 0; }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) qv[j] = qr[id[j]];
+        for (int j = 0; j < 4; ++j) { const int r = t0 + j * kThreads + tid; id[j] = r < kk ? order[r] : 0; }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int r = r0 + j * kThreads;
-            if (r < kk) {
+            const int r = t0 + j * kThreads + tid;
+            qv[j] = qr[id[j]];
+            const float qf = r < kk ? static_cast<float>(qn[r]) : 0.f;
+            take[j] = r < kk && (bstar == 0 || static_cast<int>(__float_as_uint(qf) >> 19) >= bstar);
+            mask[j] = __ballot(take[j]);
+            const unsigned long long in_mask = __ballot(take[j] && r < h);
+            if (lane == 0) { wtot[j * kWaves + wv] = __popcll(mask[j]); wtot[4 * kWaves + j * kWaves + wv] = __popcll(in_mask); }
+        }
+        __syncthreads();
+        int run = 0, run_in = 0, offs[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int g = 0; g < 4 * kWaves; ++g) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (g == j * kWaves + wv) offs[j] = run;
+            run += wtot[g]; run_in += wtot[4 * kWaves + g];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = t0 + j * kThreads + tid;
+            if (take[j]) {
+                const int off = kept + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
                 // q < 2, so bit 31 of ~bits(q) is always set: it carries the class instead (seven digits, not eight)
                 // rows given as logits: decreasing q is decreasing draft logit, whose pattern needs all 32 bits; the class moves up
                 const unsigned long long qb = fp.logits
                     ? (static_cast<unsigned long long>(~mono32(qv[j])) | (r < h ? 0ull : 0x100000000ull))
                     : static_cast<unsigned long long>((~__float_as_uint(qv[j]) & 0x7FFFFFFFu) | (r < h ? 0u : 0x80000000u));
-                k0[r] = (qb << 24) | static_cast<unsigned long long>(id[j]);
-                v0[r] = r;
+                k0[off] = (qb << 24) | static_cast<unsigned long long>(id[j]);
+                v0[off] = r;
             }
         }
+        kept += run; kept_in += run_in;
+        __syncthreads();
     }
     if (tid == 0) { cnt_in = 0; cnt_out = 0; act_in = 0; capped = 0; }
     __syncthreads();
-    const int res = block_radix_sort(k0, v0, k1, v1, kk, S);
-    const int* sorted = res ? v1 : v0;
-    for (int i = tid; i < kk; i += kThreads) byq[i] = sorted[i];
+    const int* sorted = v0;
+    if (kept > 0) {
+        const int res = block_radix_sort(k0, v0, k1, v1, kept, S);
+        sorted = res ? v1 : v0;
+    }
+    for (int i = tid; i < kept; i += kThreads) byq[i] = sorted[i];
     __syncthreads();
     const double Qh = Q[h];
     // wave 0 walks H* by decreasing q, wave 1 the other tokens: a token joins T while the mass before
@@ -658,8 +709,8 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
     // The walk only counts; the ranks and masses of the next two rounds are already on their way.
     if (wv < 2) {
 #pragma clang fp contract(off)
-        const int first = wv == 0 ? 0 : h;
-        const int len = wv == 0 ? h : kk - h;
+        const int first = wv == 0 ? 0 : kept_in;                 // the tokens of H* that stayed come first
+        const int len = wv == 0 ? kept_in : kept - kept_in;
         const double bound = wv == 0 ? ipow(Qh, n) : 1.0;
         double acc = wv == 0 ? 0.0 : Qh;
         int taken = 0;
@@ -707,7 +758,7 @@ __global__ __launch_bounds__(kThreads) void full_trunc_kernel(FullParams fp) {
         for (int i0 = tid; i0 < nout; i0 += 4 * kThreads) {
             int r[4]; double t[4]; int bl[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { const int i = i0 + j * kThreads; r[j] = i < nout ? byq[h + i] : -1; }
+            for (int j = 0; j < 4; ++j) { const int i = i0 + j * kThreads; r[j] = i < nout ? byq[kept_in + i] : -1; }
 #pragma unroll
             for (int j = 0; j < 4; ++j) { t[j] = r[j] >= 0 ? tgt[r[j]] : 0.0; bl[j] = r[j] >= 0 ? blk[r[j]] : 0; }
 #pragma unroll
