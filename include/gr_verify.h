@@ -150,7 +150,8 @@ int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, 
 /*
  * gr_accept_sweep for callers that cannot allocate device memory or create a handle: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and arithmetic as
- * gr_accept_sweep, without the handle; the selection scratch (candidate keys and partial sums, 16.2 KB per row)
+ * gr_accept_sweep, without the handle, for top-k sizes of 1..GR_MAX_SUPPORT (GR_EINVAL beyond: the HBM-resident
+ * ordering lives in a handle's workspace); the selection scratch (candidate keys and partial sums, 16.2 KB per row)
  * is a fixed array in the library's device image, so B is limited to GR_NOALLOC_MAX_B rows (GR_ECAPACITY
  * beyond; 4.2 MB per GPU, held until the process ends).  The call allocates nothing, frees nothing and does
  * not synchronise.  The array's address on the current device is looked up on the first call on that device

@@ -436,6 +436,7 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
             return GR_ENOMEM;
         }
     }
+    try {
     // the state of every sequence lives on the host: the paths that still agree with the tokens emitted so far
     std::vector<unsigned> active(S, K >= 32 ? 0xFFFFFFFFu : ((1u << K) - 1u));
     std::vector<char> alive(S, 1);
@@ -486,6 +487,10 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
     }
     h->solved = false;                                           // the policy left in the handle belongs to a gathered batch
     return GR_OK;
+    } catch (const std::bad_alloc&) {                            // host vectors: nothing may cross the C boundary
+        h->solved = false;
+        return GR_ENOMEM;
+    }
 }
 
 extern "C" int gr_profile_stride(gr_handle h, int stride) {
