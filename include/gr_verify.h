@@ -212,7 +212,8 @@ int gr_policy_slice(gr_handle h, const int* drafts, float* pi, float* accept_giv
  * unspecified): order = token ids by decreasing q/p (Sec. 5.1); block = 0 for H* (Thm 3.1), b >= 1 for the
  * b-th outer block (ranks between two consecutive suffix-minimum records of psi, Lemma 6.3);
  * weight = e^{alpha_i}, the softmax parameters of Thm 6.5 (inside H*) / Thm 6.4 (outside), float64;
- * rho = p(i) - p_i, the outer residuals of Thm 6.2, float64.
+ * rho = p(i) - p_i, the outer residuals of Thm 6.2, float64.  The weights of a row whose status is not GR_ROW_OK
+ * are unspecified (such a row is sampled from p).
  * support, h_size, iterations: [B] int32.  Any pointer may be NULL. */
 int gr_policy_export(gr_handle h, int* order, int* block, double* weight, double* rho,
                      int* support, int* h_size, int* iterations, void* hip_stream);

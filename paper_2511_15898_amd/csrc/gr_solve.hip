@@ -1376,6 +1376,8 @@ __global__ __launch_bounds__(kThreadsOf<D>) void full_programs_kernel(FullParams
     double* weight = fp.weight + row * vs; double* rho_id = fp.rho_id + row * vs; int* rank_of = fp.rank_of + row * vs;
     const double Fh = F[h];
 
+    // a row that exceeded the cap on |T| is sampled from p (no dense arrays, no weights are read for it)
+    if (info.status != GR_ROW_OK) return;
     // tokens outside the support keep all of p as residual; then the support by rank
     if (fp.logits) {
         for (int i = tid; i < V; i += kST) { rank_of[i] = -1; rho_id[i] = exp((static_cast<double>(pr[i]) - info.p_ref) * info.inv_temp) / info.p_total; }
