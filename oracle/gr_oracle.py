@@ -13,14 +13,18 @@ Steps (paper citations in each function):
   5. truncated convex programs               Thm 6.4 (outer), Thm 6.5 (inner), Alg. 1
   6. transport slice pi(.|omega)             Eq. (cases), Eq. (approx-c), Lemma 6.6
   7. single-step multi-draft sampling        App. A, multi-draft procedure
-  8. rows given as logits and a temperature  App. A, first paragraph
+  8. rows given as logits and a temperature  App. A, first paragraph; Sec. 5.1 for the orders
+  9. nucleus (top-p) cut of the draft        Sec. 5.1, App. A (option of step 1)
+The multi-step walk over a tree of draft paths (App. "Multi-Step Experiments") is in tree_walk.py.
 
 Where the paper leaves a choice open the reading taken is stated at the function.
-Parity status: every function below is pinned by tests/test_oracle_*.py against brute
-force (all 2^V subsets, the relaxed OTLP as an explicit LP, tuple enumeration), the n=1
-closed form and the marginal / monotonicity invariants -- except the inverse-CDF entry
-order of `sample_token`, which is a convention of this build (parity unpinned by the
-paper; its distribution is pinned).
+Parity status: every function below is pinned by tests/test_oracle_pins.py against brute
+force (all 2^V subsets, the relaxed OTLP as an explicit LP, tuple enumeration, SciPy's
+L-BFGS-B on the enumerated objective, exact rational and 60-digit arithmetic for the cuts
+and orders), the n=1 closed form and the marginal / monotonicity invariants -- except the
+inverse-CDF entry order of `sample_token` and the "not converged" status of a one-draft
+program whose target reaches its token's draw probability, which are conventions of this
+build (parity unpinned by the paper; the sampled distribution is pinned).
 """
 from __future__ import annotations
 
