@@ -162,6 +162,16 @@ __device__ __forceinline__ double wave_sum(double v) {
     v += dpp_move<kDppMirror>(v);
     return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
+// The float32 sum over the wave, for sums that need no more (one move and one add per level).
+__device__ __forceinline__ float wave_sum_f32(float v) {
+    v += __int_as_float(dpp_move<kDppXor1>(__float_as_int(v)));
+    v += __int_as_float(dpp_move<kDppXor2>(__float_as_int(v)));
+    v += __int_as_float(dpp_move<kDppHalfMirror>(__float_as_int(v)));
+    v += __int_as_float(dpp_move<kDppMirror>(__float_as_int(v)));
+    const int b = __float_as_int(v);
+    return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
 __device__ __forceinline__ double wave_max(double v) {
     v = fmax(v, dpp_move<kDppXor1>(v));
     v = fmax(v, dpp_move<kDppXor2>(v));

@@ -54,11 +54,12 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(
     int bad = 0;
     // LOGITS: a temperature that is not a positive finite number marks the row bad
     double inv_temp = 0.0;
-    float inv_temp_f = 0.f;
+    float scale2 = 0.f;                                    // log2(e) / T
+    float theta_d = -__builtin_inff();                    // the draft logit of the threshold key
     float ref = -__builtin_inff();
     if (LOGITS) {
         const float T = temperature[b];
-        if (!(T > 0.f) || !(T <= 3.0e38f)) bad = 1; else { inv_temp = 1.0 / static_cast<double>(T); inv_temp_f = 1.f / T; }
+        if (!(T > 0.f) || !(T <= 3.0e38f)) bad = 1; else { inv_temp = 1.0 / static_cast<double>(T); scale2 = 1.44269504088896341f / T; }
         if (tid < 32) e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
         __syncthreads();
     }
@@ -105,19 +106,16 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(
             if (ref > -3.0e38f) {
                 const double r = static_cast<double>(ref);
                 unsigned pend = 0u;
-                float far_sum[4];
+                float fs = 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float y = (ref - pv[j]) * inv_temp_f;            // +inf for a masked entry
-#ifdef GR_SEL_ALLF32
-                    const bool far = true;
-#else
-                    const bool far = y > 25.f;
-#endif
-                    far_sum[j] = far ? exp2f(-y * 1.44269504088896341f) : 0.f;
-                    if (!far) pend |= 1u << j;
+                    const float a = (pv[j] - ref) * scale2;                // log2 of the term; -inf for a masked entry
+                    const bool near = a >= -36.0673760222f;                // 25 temperatures, in bits
+                    const float f = __builtin_amdgcn_exp2f(a);                 // the bare instruction: results below 2^-126 flush to 0, which is what they are worth here
+                    fs += near ? 0.f : f;                                  // each below 1.4e-11: float32 adds lose nothing that matters
+                    pend |= near ? (1u << j) : 0u;
                 }
-                e4 = static_cast<double>((far_sum[0] + far_sum[1]) + (far_sum[2] + far_sum[3]));   // each below 1.4e-11: float32 adds lose nothing that matters
+                e4 = static_cast<double>(fs);
                 while (__any(pend != 0u)) {
                     if (pend != 0u) {
                         const int j = __ffs(static_cast<int>(pend)) - 1;
@@ -128,17 +126,21 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(
                 }
             }
             ps += e4;
-            const double pw = wave_sum(e4);
+            // the pieces' sums only steer the rejection walk (1e-7 relative is plenty): float32 reduction
+            const float pw = wave_sum_f32(static_cast<float>(e4));
             if (piece_psum && (tid & 63) == 0) {
                 const size_t at = static_cast<size_t>(b) * piece_stride + (base >> 8) + (tid >> 6);
-                piece_psum[at] = pw; piece_pref[at] = ref;
+                piece_psum[at] = static_cast<double>(pw); piece_pref[at] = ref;
             }
+            // candidates: the draft logit against the threshold's own logit first, the full key (ties by id) only then
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const unsigned long long key = make_key_logit(qv[j], i0 + j);
-                if (qv[j] > -3.0e38f && key > theta) {
-                    const int slot = atomicAdd(&count, 1);
-                    keys[slot] = key;                              // slot < kSelCap by construction
+                if (qv[j] >= theta_d && qv[j] > -3.0e38f) {
+                    const unsigned long long key = make_key_logit(qv[j], i0 + j);
+                    if (key > theta) {
+                        const int slot = atomicAdd(&count, 1);
+                        keys[slot] = key;                          // slot < kSelCap by construction
+                    }
                 }
             }
         } else {
@@ -167,6 +169,7 @@ __global__ __launch_bounds__(kThreads, 8) void select_kernel(
         __syncthreads();
         if (c + kSelTile > kSelCap && c > k) {
             theta = block_kth_largest(keys, c, k, hist, pick);
+            if (LOGITS) theta_d = key_logit(theta);
             // keep the k keys >= theta, in place: read all, then write the survivors
             unsigned long long mine[kSelCap / kThreads];
 #pragma unroll
