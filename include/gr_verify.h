@@ -66,14 +66,13 @@ typedef struct {
                           target (this implies Alg. 1's  ||grad||_1 <= 5*tol); <= 0 selects 1e-8, an order
                           above the error of the quadrature behind the routed masses */
     int    flags;      /* 0, or GR_FLAG_PROFILE */
-    double tail_mass;  /* nucleus (top-p) cut of the draft, for supports above GR_MAX_SUPPORT (Sec. 5.1: top-p/k
-                          sampling of the draft restricts the domain; App. A): the support is the fewest tokens by
-                          decreasing q (ties: lower token id) whose running sum reaches (1 - tail_mass) of the
-                          row's q mass, cut further to the top k when a top-k is given; drafts must then be
-                          drawn from q renormalised over that support.  As an approximation of the uncut
-                          draft it moves alpha* and the coupling by at most n * tail_mass.  0: no cut;
-                          must lie in [0, 1).  gr_solve with a top-k of at most GR_MAX_SUPPORT on a handle
-                          with tail_mass > 0 returns GR_EUNSUPPORTED */
+    double tail_mass;  /* nucleus (top-p) cut of the draft (Sec. 5.1: top-p/k sampling of the draft restricts the
+                          domain; App. A): the support is the fewest tokens by decreasing q (ties: lower token id)
+                          whose running sum reaches (1 - tail_mass) of the row's q mass, cut further to the top k
+                          when a top-k is given; drafts must then be drawn from q renormalised over that support.
+                          As an approximation of the uncut draft it moves alpha* and the coupling by at most
+                          n * tail_mass.  0: no cut; must lie in [0, 1).  Rows given as logits do not take it
+                          (gr_solve_logits on such a handle returns GR_EUNSUPPORTED) */
 } gr_config;
 
 #define GR_FLAG_PROFILE 1      /* record HIP events around every kernel launch (see gr_profile_read) */

@@ -211,6 +211,7 @@ int solve_in_lds(gr_handle h, const float* p, const float* q, const float* tempe
     SolveParams sp;
     sp.p = p; sp.q = q; sp.B = B; sp.V = V; sp.n = n; sp.k = k_eff; sp.splits = splits;
     sp.tau = static_cast<double>(tol); sp.rel_tol = h->rel_tol; sp.max_iter = h->max_iter; sp.max_T = h->max_T;
+    sp.tail_mass = temperature ? 0.0 : h->tail_mass;
     sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
     sp.part_bad = h->part_bad;
     sp.logits = temperature ? 1 : 0; sp.temperature = temperature; sp.part_pref = h->part_pref;
@@ -286,7 +287,6 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
     if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
-    if (k_eff <= kMaxSupport && h->tail_mass > 0.0) return GR_EUNSUPPORTED;   // the nucleus cut is for the HBM-resident path
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
     return solve_in_lds(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);

@@ -41,6 +41,7 @@ struct SolveParams {
     int B, V, n, k, splits;
     double tau;         // the paper's error threshold, float32 value widened
     double rel_tol;
+    double tail_mass;   // nucleus cut of the draft (0: none)
     int max_iter, max_T;
     // select kernel output
     const unsigned long long* cand;   // [B, splits, kMaxSupport] keys

@@ -1089,7 +1089,7 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
     __syncthreads();
     unsigned long long theta = 0ull;
     if (total > sp.k) theta = block_kth_largest<kST>(L.keys, total, sp.k, L.hist, L.pick);
-    const int kk = min(total, sp.k);
+    int kk = min(total, sp.k);
     for (int i = tid; i < total; i += kST) {
         const unsigned long long key = L.keys[i];
         if (key >= theta) {
@@ -1098,6 +1098,32 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
         }
     }
     __syncthreads();
+    if (sp.tail_mass > 0.0 && !sp.logits) {
+        // Nucleus cut of the draft (Sec. 5.1: top-p/k sampling of the draft restricts the domain): the candidates by
+        // decreasing q (ties by token id), their running sum added one after the other, and the support ends with the
+        // first token at which it reaches (1 - tail_mass) of the row's q mass.
+        int qr_ = 0;
+        if (tid < kk) {
+            const double qa = L.accb[tid]; const int ta = L.ids[tid];
+            for (int j = 0; j < kk; ++j) { const double qj = L.accb[j]; qr_ += static_cast<int>(qj > qa) | (static_cast<int>(qj == qa) & static_cast<int>(L.ids[j] < ta)); }
+            L.qd[qr_] = qa;
+        }
+        __syncthreads();
+        {
+#pragma clang fp contract(off)
+            if ((tid >> 6) == 0) wave_sequential_scan(L.qd, L.S, kk, 0.0);
+        }
+        __syncthreads();
+        const double need = (1.0 - sp.tail_mass) * qtot;
+        const double first = block_min<kSW>((tid < kk && L.S[tid + 1] >= need) ? static_cast<double>(tid + 1) : static_cast<double>(kk), L.redn);
+        const int keep = static_cast<int>(first);             // ranks 0 .. keep - 1 by q stay
+        const bool stay = tid < kk && qr_ < keep;
+        const int myid = tid < kk ? L.ids[tid] : 0; const double myq = tid < kk ? L.accb[tid] : 0.0;
+        __syncthreads();
+        if (stay) { L.ids[qr_] = myid; L.accb[qr_] = myq; }    // any order serves: the ranks are counted again below
+        kk = keep;
+        __syncthreads();
+    }
     // unsorted: token ids in ids, q in accb (exact float values), p gathered into G0
     if (sp.logits) {
         // p = exp((t - p_ref) / T) (divided by the row's sum with the other p below), q = exp((d - largest d) / T),

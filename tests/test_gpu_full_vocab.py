@@ -162,11 +162,13 @@ def test_top_k_above_the_lds_capacity(V, n, k, tol):
 
 
 @pytest.mark.parametrize("V,n,k,tail_mass,tol", [(5000, 4, 0, 1e-6, 1e-4), (5000, 2, 0, 1e-3, 1e-4), (3000, 8, 0, 1e-4, 1e-3),
-                                                 (5000, 4, 300, 1e-3, 1e-4), (777, 3, 0, 0.05, 1e-3)])
+                                                 (5000, 4, 300, 1e-3, 1e-4), (777, 3, 0, 0.05, 1e-3),
+                                                 (5000, 4, 64, 1e-3, 1e-4), (1024, 3, 200, 0.05, 1e-3), (200, 2, 0, 0.01, 1e-4)])
 def test_nucleus_cut_of_the_draft(V, n, k, tail_mass, tol):
     """gr_config.tail_mass (Sec. 5.1 / App. A: top-p sampling of the draft restricts the domain): every row
     against the checker with the same cut -- support size, order, blocks, programs, slice, token -- and
-    alpha* against the uncut run within n * tail_mass."""
+    alpha* against the uncut run within n * tail_mass.  The last three cases have supports of at most
+    GR_MAX_SUPPORT tokens and run on the LDS-resident path."""
     from oracle import gr_oracle as G
     wl = W.llm_shaped(B=24, V=V, n=n, k=k, seed_sub=60 + n)
     out = run_gpu(wl, tol, export_rows=range(wl.B), tail_mass=tail_mass)
