@@ -186,6 +186,8 @@ int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
  *
  * p, q       DEVICE [S, K, L, V] float32: the target / draft distribution after the first l tokens of path a of
  *            sequence s (paths with equal prefixes must carry equal rows; level 0 is the same row for all paths).
+ * temperature HOST [S] float32 or NULL.  Not NULL: p and q hold the models' logits and every level is solved with
+ *            gr_solve_logits at the sequence's temperature.
  * paths      HOST [S, K, L] int32 drafted tokens (path a's token l drawn from the top-k renormalised q row (s, a, l)).
  * uniforms   HOST [S, L] float32 in [0, 1), one per level.
  * k, tol     as in gr_solve.  K <= max_n and S <= max_B of the handle.
@@ -196,8 +198,8 @@ int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
  * synchronises the stream once per level and group, and leaves the handle without a policy (GR_ESTATE for a
  * gr_verify that follows).
  */
-int gr_tree_walk(gr_handle h, const float* p, const float* q, const int* paths, const float* uniforms,
-                 int S, int K, int L, int V, int k, float tol,
+int gr_tree_walk(gr_handle h, const float* p, const float* q, const float* temperature, const int* paths,
+                 const float* uniforms, int S, int K, int L, int V, int k, float tol,
                  int* out_tokens, int* out_len, int* out_accepted, int* out_fallbacks, void* hip_stream);
 
 /* Dense slice of the transport for the drafted tuple, normalised by pdraft(drafts) (Eq. "cases" with

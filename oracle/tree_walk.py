@@ -19,9 +19,11 @@ from __future__ import annotations
 from . import gr_oracle as G
 
 
-def tree_walk(p_nodes, q_nodes, paths, uniforms, k=0, tol=1e-6, max_T=0):
+def tree_walk(p_nodes, q_nodes, paths, uniforms, k=0, tol=1e-6, max_T=0, temperature=None):
     """p_nodes[a][l], q_nodes[a][l]: the target / draft distributions after the first l tokens of path a (paths with
     the same first l tokens carry the same rows); paths[a][l]: the drafted tokens; uniforms[l]: one per level.
+    temperature: when given, p_nodes / q_nodes hold the models' logits and every level goes through
+    solve_row_from_logits at that temperature (App. A, first paragraph).
     Returns (tokens emitted, number of them that were accepted drafts, levels that used the fallback, the smallest
     distance of a uniform to a CDF edge over the levels visited)."""
     K, L = len(paths), len(paths[0])
@@ -30,9 +32,12 @@ def tree_walk(p_nodes, q_nodes, paths, uniforms, k=0, tol=1e-6, max_T=0):
     for l in range(L):
         a0 = active[0]
         drafts = [int(paths[a][l]) for a in active]
-        sol = G.solve_row(p_nodes[a0][l], q_nodes[a0][l], len(active), k, tol=tol, max_T=max_T)
+        if temperature is None:
+            sol, p_row = G.solve_row(p_nodes[a0][l], q_nodes[a0][l], len(active), k, tol=tol, max_T=max_T), p_nodes[a0][l]
+        else:
+            sol, p_row, _ = G.solve_row_from_logits(p_nodes[a0][l], q_nodes[a0][l], temperature, len(active), k, tol=tol, max_T=max_T)
         fallbacks += sol.status != G.STATUS_OK
-        tok, accepted, _, _, edge = G.verify_row(sol, p_nodes[a0][l], drafts, uniforms[l])
+        tok, accepted, _, _, edge = G.verify_row(sol, p_row, drafts, uniforms[l])
         edge_min = min(edge_min, edge)
         out.append(int(tok))
         if not accepted:

@@ -56,7 +56,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
-    lib.gr_tree_walk.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
+    lib.gr_tree_walk.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
     lib.gr_solve_stats.argtypes = [vp] * 4
@@ -193,8 +193,9 @@ def gr_accept_sweep_noalloc(p: torch.Tensor, q: torch.Tensor, ks, ns, accept_pro
     return accept_prob, status
 
 
-def gr_tree_walk(handle: int, p: torch.Tensor, q: torch.Tensor, paths, uniforms, k: int, tol: float, stream=None):
-    """p, q: [S, K, L, V] float32 CUDA tensors; paths: [S, K, L] int32 and uniforms: [S, L] float32 host arrays (numpy).
+def gr_tree_walk(handle: int, p: torch.Tensor, q: torch.Tensor, paths, uniforms, k: int, tol: float, temperature=None, stream=None):
+    """p, q: [S, K, L, V] float32 CUDA tensors (the models' logits when `temperature`, a host array [S], is given);
+    paths: [S, K, L] int32 and uniforms: [S, L] float32 host arrays (numpy).
     Returns host arrays (tokens [S, L], length [S], accepted [S], fallbacks [S])."""
     import numpy as np
     if p.dim() != 4 or p.shape != q.shape:
@@ -203,8 +204,14 @@ def gr_tree_walk(handle: int, p: torch.Tensor, q: torch.Tensor, paths, uniforms,
     paths = np.ascontiguousarray(paths, dtype=np.int32); uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
     if paths.shape != (S, K, L) or uniforms.shape != (S, L):
         raise TypeError("gr_tree_walk: paths must be [S, K, L] and uniforms [S, L]")
+    tptr = None
+    if temperature is not None:
+        temperature = np.ascontiguousarray(temperature, dtype=np.float32)
+        if temperature.shape != (S,):
+            raise TypeError("gr_tree_walk: temperature must be [S]")
+        tptr = temperature.ctypes.data
     tokens = np.empty((S, L), np.int32); length = np.empty(S, np.int32); accepted = np.empty(S, np.int32); fallbacks = np.empty(S, np.int32)
-    rc = load_library().gr_tree_walk(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), paths.ctypes.data, uniforms.ctypes.data,
+    rc = load_library().gr_tree_walk(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), tptr, paths.ctypes.data, uniforms.ctypes.data,
                                      S, K, L, V, k, tol, tokens.ctypes.data, length.ctypes.data, accepted.ctypes.data,
                                      fallbacks.ctypes.data, _stream(stream))
     _solved_shape.pop(handle, None)

@@ -38,7 +38,7 @@ struct gr_handle_s {
     FullParams full = {};
     bool full_mode = false;
     // staging of gr_tree_walk (allocated by its first call): gathered rows, drafts, uniforms, results, row offsets
-    float* tw_p = nullptr; float* tw_q = nullptr; int* tw_drafts = nullptr; float* tw_u = nullptr; int* tw_tok = nullptr;
+    float* tw_p = nullptr; float* tw_q = nullptr; int* tw_drafts = nullptr; float* tw_u = nullptr; float* tw_temp = nullptr; int* tw_tok = nullptr;
     unsigned char* tw_ok = nullptr; long long* tw_idx = nullptr; float* tw_acc = nullptr; int* tw_status = nullptr;
     // last solve
     bool solved = false;
@@ -59,7 +59,7 @@ bool dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(gr_handle h) {
-    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status, h->sweep_mass, h->newton_ws, h->order, h->block,
+    void* ptrs[] = {h->cand, h->cand_count, h->part_psum, h->part_qsum, h->part_bad, h->piece_psum, h->piece_pref, h->part_pref, h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_temp, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status, h->sweep_mass, h->newton_ws, h->order, h->block,
                     h->weight, h->rho, h->pnorm, h->info};
     for (void* ptr : ptrs) (void)hipFree(ptr);
     (void)hipFree(h->full_ws);
@@ -416,8 +416,8 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const float* __re
 
 }  // namespace
 
-extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const int* paths, const float* uniforms,
-                            int S, int K, int L, int V, int k, float tol,
+extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const float* temperature, const int* paths,
+                            const float* uniforms, int S, int K, int L, int V, int k, float tol,
                             int* out_tokens, int* out_len, int* out_accepted, int* out_fallbacks, void* hip_stream) {
     if (!h || !p || !q || !paths || !uniforms || !out_tokens || !out_len || !out_accepted) return GR_EINVAL;
     if (S <= 0 || K < 1 || L < 1 || V <= 0 || S > h->max_B || V > h->max_V || K > h->max_n) return GR_EINVAL;
@@ -426,12 +426,12 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
     if (!h->tw_p) {
         const size_t rows = static_cast<size_t>(h->max_B), cols = static_cast<size_t>(h->max_V);
         const bool ok = dev_alloc(&h->tw_p, rows * cols) && dev_alloc(&h->tw_q, rows * cols) && dev_alloc(&h->tw_drafts, rows * GR_MAX_N) &&
-                        dev_alloc(&h->tw_u, rows) && dev_alloc(&h->tw_tok, rows) && dev_alloc(&h->tw_ok, rows) && dev_alloc(&h->tw_idx, rows) &&
+                        dev_alloc(&h->tw_u, rows) && dev_alloc(&h->tw_temp, rows) && dev_alloc(&h->tw_tok, rows) && dev_alloc(&h->tw_ok, rows) && dev_alloc(&h->tw_idx, rows) &&
                         dev_alloc(&h->tw_acc, rows) && dev_alloc(&h->tw_status, rows);
         if (!ok) {
-            void* ptrs[] = {h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status};
+            void* ptrs[] = {h->tw_p, h->tw_q, h->tw_drafts, h->tw_u, h->tw_temp, h->tw_tok, h->tw_ok, h->tw_idx, h->tw_acc, h->tw_status};
             for (void* ptr : ptrs) (void)hipFree(ptr);
-            h->tw_p = h->tw_q = h->tw_u = h->tw_acc = nullptr; h->tw_drafts = h->tw_tok = h->tw_status = nullptr; h->tw_ok = nullptr; h->tw_idx = nullptr;
+            h->tw_p = h->tw_q = h->tw_u = h->tw_temp = h->tw_acc = nullptr; h->tw_drafts = h->tw_tok = h->tw_status = nullptr; h->tw_ok = nullptr; h->tw_idx = nullptr;
             (void)hipGetLastError();
             return GR_ENOMEM;
         }
@@ -442,10 +442,10 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
     std::vector<char> alive(S, 1);
     for (int s = 0; s < S; ++s) { out_len[s] = 0; out_accepted[s] = 0; if (out_fallbacks) out_fallbacks[s] = 0; }
     for (int i = 0; i < S * L; ++i) out_tokens[i] = -1;
-    std::vector<int> seqs, drafts, tok, st; std::vector<long long> idx; std::vector<float> us; std::vector<unsigned char> okv;
+    std::vector<int> seqs, drafts, tok, st; std::vector<long long> idx; std::vector<float> us, ts; std::vector<unsigned char> okv;
     for (int l = 0; l < L; ++l) {
         for (int n = 1; n <= K; ++n) {
-            seqs.clear(); drafts.clear(); idx.clear(); us.clear();
+            seqs.clear(); drafts.clear(); idx.clear(); us.clear(); ts.clear();
             for (int s = 0; s < S; ++s) {
                 if (!alive[s] || __builtin_popcount(active[s]) != n) continue;
                 const int a0 = __builtin_ctz(active[s]);
@@ -453,15 +453,18 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const i
                 idx.push_back(((static_cast<long long>(s) * K + a0) * L + l) * V);
                 for (int a = 0; a < K; ++a) if (active[s] >> a & 1u) drafts.push_back(paths[(static_cast<size_t>(s) * K + a) * L + l]);
                 us.push_back(uniforms[static_cast<size_t>(s) * L + l]);
+                if (temperature) ts.push_back(temperature[s]);
             }
             const int cnt = static_cast<int>(seqs.size());
             if (cnt == 0) continue;
             if (hipMemcpyAsync(h->tw_idx, idx.data(), sizeof(long long) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess ||
                 hipMemcpyAsync(h->tw_drafts, drafts.data(), sizeof(int) * cnt * n, hipMemcpyHostToDevice, stream) != hipSuccess ||
-                hipMemcpyAsync(h->tw_u, us.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess) return GR_EHIP;
+                hipMemcpyAsync(h->tw_u, us.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess ||
+                (temperature && hipMemcpyAsync(h->tw_temp, ts.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess)) return GR_EHIP;
             hipLaunchKernelGGL(gather_rows_kernel, dim3(cnt), dim3(kThreads), 0, stream, p, q, h->tw_idx, h->tw_p, h->tw_q, V);
             if (hipGetLastError() != hipSuccess) return GR_EHIP;
-            int rc = gr_solve(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
+            int rc = temperature ? gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream)
+                                 : gr_solve(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
             if (rc != GR_OK) return rc;
             rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);
             if (rc != GR_OK) return rc;

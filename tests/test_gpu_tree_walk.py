@@ -65,3 +65,48 @@ def test_fallback_levels_sample_from_p_and_more_paths_go_further():
         _, length, _, _ = _walk_gpu(np.ascontiguousarray(p[:, :K]), np.ascontiguousarray(q[:, :K]), np.ascontiguousarray(paths[:, :K]), u, 64, 1e-4)
         eff.append(float(length.mean()))
     assert eff[0] <= eff[1] + 0.25 and eff[1] <= eff[2] + 0.25 and eff[2] > eff[0], eff
+
+
+def test_tree_walk_on_logits():
+    """The same walk when the node rows are the models' logits and every sequence has its own temperature: each level
+    goes through gr_solve_logits; the checker does the same with its logits entry."""
+    from oracle import gr_oracle as G, tree_walk as TW
+    S, K, L, V, k, tol = 10, 3, 4, 1500, 24, 1e-6
+    temps = np.random.default_rng(31).uniform(0.6, 1.4, size=S).astype(np.float32)
+    tl = np.empty((S, K, L, V), np.float32); dl = np.empty((S, K, L, V), np.float32)
+    paths = np.empty((S, K, L), np.int32)
+    for s in range(S):
+        T = float(temps[s])
+        for a in range(K):
+            prefix = []
+            for l in range(L):
+                node = np.random.default_rng([W.BASE_SEED, 7100, s] + prefix)           # rows are a function of the prefix
+                t = (4.0 * node.gumbel(0.0, 1.0, size=V)).astype(np.float32)
+                d = (0.8 * t + node.standard_normal(V)).astype(np.float32)
+                tl[s, a, l] = t; dl[s, a, l] = d
+                d64 = d.astype(np.float64)
+                top = np.argsort(-d64, kind="stable")[:k]
+                w = np.exp((d64[top] - d64[top].max()) / T)
+                draw = np.random.default_rng([W.BASE_SEED, 8100, s, a, l])
+                tok = int(top[min(int(np.searchsorted(np.cumsum(w), draw.random() * w.sum(), side="right")), k - 1)])
+                paths[s, a, l] = tok
+                prefix.append(tok)
+    u = np.random.default_rng(32).random((S, L)).astype(np.float32)
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    dev = torch.device("cuda:0")
+    h = gr.gr_create(S, V, max_k=k, max_n=K)
+    try:
+        tokens, length, accepted, fallbacks = gr.gr_tree_walk(h, torch.from_numpy(tl).to(dev), torch.from_numpy(dl).to(dev), paths, u, k, tol,
+                                                              temperature=temps)
+    finally:
+        gr.gr_destroy(h)
+    compared = 0
+    for s in range(S):
+        out, nacc, fb, edge = TW.tree_walk([[tl[s, a, l] for l in range(L)] for a in range(K)], [[dl[s, a, l] for l in range(L)] for a in range(K)],
+                                           paths[s], u[s], k, tol, max_T=128, temperature=float(temps[s]))
+        if edge < 1e-5:
+            continue
+        compared += 1
+        assert list(tokens[s, :length[s]]) == out and accepted[s] == nacc and fallbacks[s] == fb, (s, tokens[s], out)
+    assert compared >= S - 2 and accepted.sum() > 0
