@@ -112,7 +112,11 @@ int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float to
  * themselves: decreasing q/p is decreasing (draft - target) logit, exact for float32 logits.
  *
  * target_logits, draft_logits [B, V] float32 row-major, finite (a NaN or infinite entry gives GR_ROW_BAD).
- * temperature [B] float32, positive and finite (GR_ROW_BAD otherwise).
+ * temperature [B] float32, positive and finite (GR_ROW_BAD otherwise): the target's, and the draft's too when
+ *             draft_temperature is NULL.
+ * draft_temperature [B] float32 or NULL: the draft's own temperature (the paper's temperature study cools the target
+ *             and leaves the draft at 1).  q/p is then proportional to exp(d / Td - t / Tt); its order is taken on that
+ *             value in float64 (two rounded products, one subtraction).
  * k           top-k on the draft, as in gr_solve (a support above GR_MAX_SUPPORT runs on the HBM-resident path, where
  *             the orders are sorts on the draft logit and on draft minus target logit, and needs a handle created
  *             with max_k at least that large).  A handle with tail_mass > 0 gives GR_EUNSUPPORTED.
@@ -120,7 +124,8 @@ int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float to
  * gr_policy_slice on this solve: they stand in for the p row there.
  */
 int gr_solve_logits(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
-                    int n, int k, float tol, int B, int V, float* accept_prob, int* status, void* hip_stream);
+                    const float* draft_temperature, int n, int k, float tol, int B, int V, float* accept_prob,
+                    int* status, void* hip_stream);
 
 /*
  * Acceptance-only sweep: alpha*(k, n) = 1 + min_H psi(H) (Thm 3.1; by the order of decreasing q/p

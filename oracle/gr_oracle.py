@@ -555,17 +555,22 @@ def softmax_from_logits(logits, temperature=1.0):
     return e / e.sum()
 
 
-def solve_row_from_logits(target_logits, draft_logits, temperature, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11):
-    """Alg. 1 for a decode position given by its target and draft logits and one sampling temperature: p and q are
-    the float64 softmaxes.  Every order the method needs is decided on the logits themselves, where it is exact
-    for float32 logits: q/p is proportional to exp((d - t) / T), so decreasing q/p is decreasing d - t (Sec. 5.1),
-    and decreasing q is decreasing d (top-k support, truncation sets); ties go to the lower token id.
+def solve_row_from_logits(target_logits, draft_logits, temperature, n, k=0, tol=1e-6, max_T=0, max_iter=4000, rtol=1e-11,
+                          draft_temperature=None):
+    """Alg. 1 for a decode position given by its target and draft logits and the sampling temperatures (one for both
+    models, or the draft's own in draft_temperature: the paper's temperature study cools the target and leaves the
+    draft at 1): p and q are the float64 softmaxes.  Every order the method needs is decided on the logits
+    themselves: q/p is proportional to exp(d / Td - t / Tt), so decreasing q/p (Sec. 5.1) is decreasing d - t with one
+    temperature (exact for float32 logits) and decreasing d / Td - t / Tt with two (two rounded float64 products, one
+    subtraction); decreasing q is decreasing d (top-k support, truncation sets); ties go to the lower token id.
     Returns (RowSolution, p, q)."""
+    td = temperature if draft_temperature is None else draft_temperature
     p = softmax_from_logits(target_logits, temperature)
-    q = softmax_from_logits(draft_logits, temperature)
-    d64 = np.asarray(draft_logits, np.float64)
-    return solve_row(p, q, n, k, tol=tol, max_T=max_T, max_iter=max_iter, rtol=rtol,
-                     ratio_key=d64 - np.asarray(target_logits, np.float64), q_key=d64), p, q
+    q = softmax_from_logits(draft_logits, td)
+    d64 = np.asarray(draft_logits, np.float64); t64 = np.asarray(target_logits, np.float64)
+    inv_tt = 1.0 / float(temperature); inv_td = 1.0 / float(td)
+    ratio_key = d64 - t64 if inv_td == inv_tt else d64 * inv_td - t64 * inv_tt
+    return solve_row(p, q, n, k, tol=tol, max_T=max_T, max_iter=max_iter, rtol=rtol, ratio_key=ratio_key, q_key=d64), p, q
 
 
 # ----------------------------------------------------------------- slice and sampling

@@ -52,7 +52,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ctypes.POINTER(GrConfig)]
     lib.gr_destroy.argtypes = [vp]
     lib.gr_solve.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
-    lib.gr_solve_logits.argtypes = [vp, vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
+    lib.gr_solve_logits.argtypes = [vp, vp, vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -128,21 +128,27 @@ def gr_solve(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: int, tol:
 
 
 def gr_solve_logits(handle: int, target_logits: torch.Tensor, draft_logits: torch.Tensor, temperature: torch.Tensor, n: int, k: int,
-                    tol: float, accept_prob: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None):
-    """target_logits, draft_logits: [B, V] float32 CUDA tensors; temperature: [B] float32.  Returns (accept_prob, status).
+                    tol: float, accept_prob: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None,
+                    draft_temperature: torch.Tensor | None = None):
+    """target_logits, draft_logits: [B, V] float32 CUDA tensors; temperature: [B] float32 (draft_temperature: the draft's
+    own, default the same).  Returns (accept_prob, status).
     The target logits and the temperatures stand in for p until the last gr_verify / gr_policy_slice of this solve."""
     if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape:
         raise TypeError("gr_solve_logits: target_logits and draft_logits must both be [B, V]")
     B, V = target_logits.shape
     if temperature.dim() != 1 or temperature.shape[0] != B:
         raise TypeError("gr_solve_logits: temperature must be [B]")
+    if draft_temperature is not None and (draft_temperature.dim() != 1 or draft_temperature.shape[0] != B):
+        raise TypeError("gr_solve_logits: draft_temperature must be [B]")
     if accept_prob is None:
         accept_prob = torch.empty(B, dtype=torch.float32, device=target_logits.device)
     if status is None:
         status = torch.empty(B, dtype=torch.int32, device=target_logits.device)
     rc = load_library().gr_solve_logits(handle, _ptr(target_logits, torch.float32, "target_logits"),
                                         _ptr(draft_logits, torch.float32, "draft_logits"),
-                                        _ptr(temperature, torch.float32, "temperature"), n, k, tol, B, V,
+                                        _ptr(temperature, torch.float32, "temperature"),
+                                        None if draft_temperature is None else _ptr(draft_temperature, torch.float32, "draft_temperature"),
+                                        n, k, tol, B, V,
                                         _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
                                         _stream(stream))
     if rc != GR_OK:

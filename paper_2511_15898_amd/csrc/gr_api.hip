@@ -170,7 +170,7 @@ int fill_sweep(SweepParams& sw, const int* ks, int nk, const int* ns, int nn, in
 
 // The HBM-resident path (a support above GR_MAX_SUPPORT: no top-k, or a large one) of gr_solve (temperature == nullptr)
 // and of gr_solve_logits.
-int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* temperature, int n, int k_eff, float tol, int B, int V,
+int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* temperature, const float* draft_temperature, int n, int k_eff, float tol, int B, int V,
                  float* accept_prob, int* status, hipStream_t stream) {
     if (V >= (1 << 24)) return GR_EUNSUPPORTED;
     h->solved = false;
@@ -179,7 +179,7 @@ int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* tempe
     FullParams& f = h->full;
     f.p = p; f.q = q; f.B = B; f.V = V; f.n = n; f.k = k_eff; f.max_T = h->max_T; f.max_iter = h->max_iter;
     f.tau = static_cast<double>(tol); f.rel_tol = h->rel_tol; f.tail_mass = h->tail_mass;
-    f.logits = temperature ? 1 : 0; f.temperature = temperature;
+    f.logits = temperature ? 1 : 0; f.temperature = temperature; f.draft_temperature = draft_temperature;
     f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
     mark(h, 0, stream);
     launch_full_prologue(f, stream);
@@ -192,7 +192,7 @@ int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* tempe
 }
 
 // The LDS-resident path of gr_solve (temperature == nullptr: p and q are probabilities) and of gr_solve_logits.
-int solve_in_lds(gr_handle h, const float* p, const float* q, const float* temperature, int n, int k_eff, float tol, int B, int V,
+int solve_in_lds(gr_handle h, const float* p, const float* q, const float* temperature, const float* draft_temperature, int n, int k_eff, float tol, int B, int V,
                  float* accept_prob, int* status, hipStream_t stream) {
     h->full_mode = false;
     const int splits = choose_splits(B, V);
@@ -214,7 +214,7 @@ int solve_in_lds(gr_handle h, const float* p, const float* q, const float* tempe
     sp.tail_mass = temperature ? 0.0 : h->tail_mass;
     sp.cand = h->cand; sp.cand_count = h->cand_count; sp.part_psum = h->part_psum; sp.part_qsum = h->part_qsum;
     sp.part_bad = h->part_bad;
-    sp.logits = temperature ? 1 : 0; sp.temperature = temperature; sp.part_pref = h->part_pref;
+    sp.logits = temperature ? 1 : 0; sp.temperature = temperature; sp.part_pref = h->part_pref; sp.draft_temperature = draft_temperature;
     sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
     sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status; sp.newton_ws = h->newton_ws;
     if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
@@ -288,13 +288,14 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     const int k_eff = (k <= 0 || k >= V) ? V : k;
     if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
-    return solve_in_lds(h, p, q, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+    if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+    return solve_in_lds(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
 }
 
 /* Rows given as logits: see gr_verify.h. */
 extern "C" int gr_solve_logits(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
-                               int n, int k, float tol, int B, int V, float* accept_prob, int* status, void* hip_stream) {
+                               const float* draft_temperature, int n, int k, float tol, int B, int V, float* accept_prob,
+                               int* status, void* hip_stream) {
     if (!h || !target_logits || !draft_logits || !temperature || !accept_prob || !status) return GR_EINVAL;
     if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
     if (n < 1 || n > h->max_n) return GR_EINVAL;
@@ -303,9 +304,9 @@ extern "C" int gr_solve_logits(gr_handle h, const float* target_logits, const fl
     if (h->tail_mass > 0.0) return GR_EUNSUPPORTED;                         // the nucleus cut is defined on probabilities
     if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;          // the handle holds no workspace for such a support
     if (k_eff > kMaxSupport)
-        return solve_in_hbm(h, target_logits, draft_logits, temperature, n, k_eff, tol, B, V, accept_prob, status,
+        return solve_in_hbm(h, target_logits, draft_logits, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status,
                             static_cast<hipStream_t>(hip_stream));
-    return solve_in_lds(h, target_logits, draft_logits, temperature, n, k_eff, tol, B, V, accept_prob, status,
+    return solve_in_lds(h, target_logits, draft_logits, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -335,7 +336,7 @@ extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, cons
             if (rc != GR_OK) return rc;
             FullParams& f = h->full;
             f.p = p; f.q = q; f.B = B; f.V = V; f.n = 1; f.k = kmax; f.max_T = h->max_T; f.max_iter = h->max_iter;
-            f.tau = 0.0; f.rel_tol = h->rel_tol; f.tail_mass = 0.0; f.logits = 0; f.temperature = nullptr;
+            f.tau = 0.0; f.rel_tol = h->rel_tol; f.tail_mass = 0.0; f.logits = 0; f.temperature = nullptr; f.draft_temperature = nullptr;
             f.info = h->info; f.accept_prob = accept_prob; f.status = status; f.newton_ws = h->newton_ws;
             fs.mass = h->sweep_mass; fs.accept_prob = accept_prob; fs.status = status;
             launch_full_sweep(f, fs, stream);
@@ -463,7 +464,7 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const f
                 (temperature && hipMemcpyAsync(h->tw_temp, ts.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess)) return GR_EHIP;
             hipLaunchKernelGGL(gather_rows_kernel, dim3(cnt), dim3(kThreads), 0, stream, p, q, h->tw_idx, h->tw_p, h->tw_q, V);
             if (hipGetLastError() != hipSuccess) return GR_EHIP;
-            int rc = temperature ? gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream)
+            int rc = temperature ? gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, nullptr, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream)
                                  : gr_solve(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
             if (rc != GR_OK) return rc;
             rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);

@@ -256,13 +256,14 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
     int* v0 = fp.val0 + row * vs; int* v1 = fp.val1 + row * vs;
 
     double ptot, qtot;
-    double p_ref = 0.0, q_ref = 0.0, inv_temp = 0.0;
+    double p_ref = 0.0, q_ref = 0.0, inv_temp = 0.0, inv_temp_q = 0.0;
     if (fp.logits) {
         // rows given as logits: the largest target and draft logit, then the target's softmax sum relative to it;
         // q needs no sum (it is renormalised over the support).  A NaN or +inf anywhere, or a temperature that is not
         // positive and finite, marks the row bad; -inf is a masked token.
         const float T = fp.temperature[row];
-        float tm = -__builtin_inff(), dm = -__builtin_inff(); int bad = !(T > 0.f) || !(T <= 3.0e38f);
+        const float Td = fp.draft_temperature ? fp.draft_temperature[row] : T;
+        float tm = -__builtin_inff(), dm = -__builtin_inff(); int bad = !(T > 0.f) || !(T <= 3.0e38f) || !(Td > 0.f) || !(Td <= 3.0e38f);
         for (int i = tid; i < V; i += kThreads) {
             const float pv = pr[i], qv = qr[i];
             bad |= !(pv + qv < 3.0e38f);
@@ -272,6 +273,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
         q_ref = block_max(static_cast<double>(dm), red);
         const int anybad = block_sum_i(bad, red);
         inv_temp = anybad ? 0.0 : 1.0 / static_cast<double>(T);
+        inv_temp_q = anybad ? 0.0 : 1.0 / static_cast<double>(Td);
         double ps = 0.0;
         if (!anybad && p_ref > -3.0e38 && q_ref > -3.0e38)
             for (int i = tid; i < V; i += kThreads) ps += exp((static_cast<double>(pr[i]) - p_ref) * inv_temp);
@@ -416,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void full_order_kernel(FullParams fp) {
                 const int off = kk + offs[j] + __popcll(mask[j] & ((1ull << lane) - 1ull));
                 // rows given as logits: q/p is proportional to exp((d - t) / T), so the order is that of d - t (exact in
                 // float64 for float32 logits; a masked target gives +inf: first)
-                const double ratio = lg ? static_cast<double>(qv[j]) - static_cast<double>(pv[j])
+                const double ratio = lg ? logit_ratio_key(static_cast<double>(qv[j]), static_cast<double>(pv[j]), inv_temp_q, inv_temp)
                                         : static_cast<double>(qv[j]) / static_cast<double>(pv[j]);   // p = 0 gives +inf: first
                 k0[off] = lg ? ~mono64(ratio) : ~static_cast<unsigned long long>(__double_as_longlong(ratio));
                 v0[off] = t0 + j * kThreads + tid;
@@ -457,6 +459,7 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
     RowInfo info = fp.info[row];
     if (info.status == GR_ROW_BAD) return;
     const int kk = info.support;
+    const double inv_temp_q = fp.logits ? 1.0 / static_cast<double>(fp.draft_temperature ? fp.draft_temperature[row] : fp.temperature[row]) : 0.0;
     const float* pr = fp.p + static_cast<size_t>(row) * V;
     const float* qr = fp.q + static_cast<size_t>(row) * V;
     const int* order = fp.order + row * vs;
@@ -478,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void full_scan_kernel(FullParams fp) {
             if (r < kk) {
                 if (fp.logits) {
                     pn[r] = exp((static_cast<double>(pv[j]) - info.p_ref) * info.inv_temp) / info.p_total;
-                    qn[r] = exp((static_cast<double>(qv[j]) - info.q_ref) * info.inv_temp);
+                    qn[r] = exp((static_cast<double>(qv[j]) - info.q_ref) * inv_temp_q);
                 } else {
                     pn[r] = static_cast<double>(pv[j]) / info.p_total;
                     qn[r] = static_cast<double>(qv[j]);          // raw q for now

@@ -51,6 +51,7 @@ struct SolveParams {
     const int* part_bad;              // [B, splits]
     // rows given as logits (p = target logits, q unused): temperature [B], the slices' softmax references [B, splits]
     int logits; const float* temperature; const float* part_pref;
+    const float* draft_temperature;   // [B] the draft's own temperature, or nullptr: the row's temperature serves both models
     // policy object
     int* order; int* block; double* weight; double* rho; double* pnorm;   // [B, kMaxSupport]
     RowInfo* info;                    // [B]
@@ -67,6 +68,7 @@ struct FullParams {
     double tau, rel_tol;
     double tail_mass;  // nucleus cut of the draft: share of the draw mass that may be left out (0: none)
     int logits; const float* temperature;   // rows given as logits (p = target logits, q = draft logits), one temperature per row
+    const float* draft_temperature;         // [B] the draft's own temperature, or nullptr
     unsigned long long* key0; unsigned long long* key1; int* val0; int* val1;   // sort buffers
     int* order;        // token ids by decreasing q/p
     int* byq;          // ranks by (inside H* first, decreasing q, token id)
@@ -333,6 +335,12 @@ __device__ __forceinline__ unsigned long long mono64(double x) {
 __device__ __forceinline__ unsigned mono32(float x) {
     const unsigned b = __float_as_uint(x);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+// The value whose decreasing order is that of q/p for rows given as logits: q/p is proportional to
+// exp(d / Td - t / Tt).  With one temperature that is the order of d - t, exact in float64 for float32 logits; with
+// two, the two products are rounded and then subtracted (no fused operation: the checker does the same three steps).
+__device__ __forceinline__ double logit_ratio_key(double d, double t, double inv_td, double inv_tt) {
+    return inv_td == inv_tt ? d - t : __dsub_rn(__dmul_rn(d, inv_td), __dmul_rn(t, inv_tt));
 }
 __device__ __forceinline__ float key_logit(unsigned long long key) {
     const unsigned mono = static_cast<unsigned>(key >> 32);

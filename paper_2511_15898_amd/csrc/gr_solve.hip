@@ -1036,12 +1036,15 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
     // ---- merge the slices
     int total = 0, bad = 0;
     double ptot = 0.0, qtot = 0.0;
-    double p_ref = 0.0, inv_temp = 0.0;
+    double p_ref = 0.0, inv_temp = 0.0, inv_temp_q = 0.0;
     if (sp.logits) {
         // rows given as logits: the slices' softmax sums are brought to the row's largest reference; q needs no
         // normaliser (it is renormalised over the support)
         const float T = sp.temperature[row];
         inv_temp = 1.0 / static_cast<double>(T);
+        const float Td = sp.draft_temperature ? sp.draft_temperature[row] : T;
+        inv_temp_q = 1.0 / static_cast<double>(Td);
+        if (!(Td > 0.f) || !(Td <= 3.0e38f)) bad = 1;
         float m = -__builtin_inff();
         for (int s = 0; s < sp.splits; ++s) m = fmaxf(m, sp.part_pref[row * sp.splits + s]);
         p_ref = static_cast<double>(m);
@@ -1134,8 +1137,8 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
         if (tid < kk) {
             const double t = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
             L.G0[tid] = exp((t - p_ref) * inv_temp);
-            L.dlt[tid] = d - t; L.dval[tid] = d;
-            L.accb[tid] = exp((d - dmax) * inv_temp);
+            L.dlt[tid] = logit_ratio_key(d, t, inv_temp_q, inv_temp); L.dval[tid] = d;
+            L.accb[tid] = exp((d - dmax) * inv_temp_q);
         }
     } else if (tid < kk) L.G0[tid] = static_cast<double>(sp.p[static_cast<size_t>(row) * V + L.ids[tid]]);
     if (tid < kk) { L.cnt0[tid] = 0; L.cnt1[tid] = 0; }

@@ -20,9 +20,9 @@ def _drafts_from_logits(wl, rows, seed):
         dl = wl.meta["draft_logits"][b].astype(np.float64)
         top = np.argsort(-dl, kind="stable")[: (wl.k if 0 < wl.k < wl.V else wl.V)]
         if b in rows:
-            q = G.softmax_from_logits(wl.meta["draft_logits"][b], float(np.float32(wl.meta["temps"][b])))
+            q = G.softmax_from_logits(wl.meta["draft_logits"][b], float(np.float32(wl.meta.get("draft_temps", wl.meta["temps"])[b])))
             assert sorted(int(t) for t in top) == G.topk_support(q, wl.k, key=dl)
-        w = np.exp((dl[top] - dl[top].max()) / float(np.float32(wl.meta["temps"][b])))
+        w = np.exp((dl[top] - dl[top].max()) / float(np.float32(wl.meta.get("draft_temps", wl.meta["temps"])[b])))
         drafts[b] = top[np.minimum(np.searchsorted(np.cumsum(w), rng.random(wl.n) * w.sum(), side="right"), top.size - 1)]
     return drafts
 
@@ -35,10 +35,11 @@ def _run_logits(wl, tol, drafts, export_rows=None):
     full = (wl.V if (wl.k <= 0 or wl.k >= wl.V) else wl.k) > gr.GR_MAX_SUPPORT
     tl = torch.from_numpy(wl.meta["target_logits"]).to(dev); dl = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
     T = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
+    Td = torch.from_numpy(wl.meta["draft_temps"].astype(np.float32)).to(dev) if "draft_temps" in wl.meta else None
     d = torch.from_numpy(drafts).to(dev); u = torch.from_numpy(wl.uniforms).to(dev)
     h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n)
     try:
-        acc, st = gr.gr_solve_logits(h, tl, dl, T, wl.n, wl.k, tol)
+        acc, st = gr.gr_solve_logits(h, tl, dl, T, wl.n, wl.k, tol, draft_temperature=Td)
         tok, ok = gr.gr_verify(h, d, u)
         out = {"accept_prob": acc, "status": st, "token": tok, "accepted": ok}
         out["pi"], out["accept_given"] = gr.gr_policy_slice(h, d, wl.V)
@@ -69,7 +70,9 @@ def _compare(wl, out, rows, tol, drafts):
     stats = {"rows": 0, "fragile": 0, "edge": 0, "programs": 0, "max_dpi": 0.0}
     for b in rows:
         T = float(np.float32(wl.meta["temps"][b]))
-        sol, p, q = G.solve_row_from_logits(wl.meta["target_logits"][b], wl.meta["draft_logits"][b], T, wl.n, wl.k, tol=tol, max_T=128)
+        Td = float(np.float32(wl.meta["draft_temps"][b])) if "draft_temps" in wl.meta else None
+        sol, p, q = G.solve_row_from_logits(wl.meta["target_logits"][b], wl.meta["draft_logits"][b], T, wl.n, wl.k, tol=tol, max_T=128,
+                                            draft_temperature=Td)
         tok, accepted, pi, acc_given, edge = G.verify_row(sol, p, drafts[b], wl.uniforms[b])
         stats["rows"] += 1
         assert abs(out["accept_prob"][b] - sol.alpha_star) < ABS_TOL, (b, out["accept_prob"][b], sol.alpha_star)
@@ -176,3 +179,18 @@ def test_logits_with_supports_above_the_lds_capacity(V, n, k, tol):
     st = _compare(wl, out, range(wl.B), tol, drafts)
     assert st["rows"] == wl.B and st["fragile"] < wl.B
     assert np.any(out["status"] == 0)
+
+
+@pytest.mark.parametrize("V,n,k,tol", [(8000, 4, 64, 1e-6), (3000, 3, 0, 1e-4)])
+def test_a_cooled_target_with_the_draft_left_at_its_own_temperature(V, n, k, tol):
+    """The paper's temperature study cools the target (0.2 ... 0.8) and leaves the draft at 1: two temperatures per row.
+    One case on the LDS-resident path, one on the HBM-resident path; every row against the checker."""
+    import dataclasses
+    wl = W.llm_shaped(B=12, V=V, n=n, k=k, temperature=1.0, seed_sub=410 + n, keep_logits=True)
+    rng = np.random.default_rng(17)
+    meta = dict(wl.meta); meta["temps"] = rng.choice([0.4, 0.6, 0.8], size=wl.B); meta["draft_temps"] = np.ones(wl.B)
+    wl = dataclasses.replace(wl, meta=meta)
+    drafts = _drafts_from_logits(wl, set(range(wl.B)), 16)
+    out = _run_logits(wl, tol, drafts, export_rows=range(wl.B))
+    st = _compare(wl, out, range(wl.B), tol, drafts)
+    assert st["rows"] == wl.B and st["fragile"] < wl.B and np.any(out["status"] == 0)

@@ -480,6 +480,13 @@ def test_orders_taken_on_the_logits_are_the_orders_of_the_softmaxed_rows():
         k = V // 2
         want_k = sorted(sorted(range(V), key=lambda i: (-qd[i], i))[:k])
         assert G.topk_support(q, k, key=dl.astype(np.float64)) == want_k
+        # the draft at its own temperature: q/p = exp(d / Td - t / Tt)
+        Td = float(rng.uniform(0.4, 1.6))
+        sol2, p2, q2 = G.solve_row_from_logits(tl, dl, T, 3, 0, tol=0.0, max_T=1, draft_temperature=Td)
+        ratio2 = [(Decimal(float(dl[i])) / Decimal(Td) - Decimal(float(tl[i])) / Decimal(T)).exp() for i in range(V)]
+        assert [int(t) for t in sol2.order] == sorted(range(V), key=lambda i: (-ratio2[i], i))
+        e = np.exp((dl.astype(np.float64) - float(dl.max())) / Td)
+        assert np.abs(q2 - e / e.sum()).max() < 1e-15 and np.abs(p2 - p).max() == 0.0
 
 
 # ------------------------------------------------------------------ nucleus cut of the draft
