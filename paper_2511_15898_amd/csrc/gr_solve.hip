@@ -92,7 +92,7 @@ struct Lds {
             double rpart[kSW][kMaxT];   // per wave: sum over its nodes of the integrand of each token
             double spart[kSW][kMaxT];   // the same weighted by t
             NodeRec<D> nrec[kSW][kNPW];
-            TokRec<D> trec[kMaxT + 4];  // active tokens; the 4 beyond the last have aw = 1e300 (x = 0)
+            TokRec<D> trec[kMaxT + 4];  // active tokens; every record beyond the last has aw = 1e300 (x = 0), e = 0
         };
     };
     double Ha[kHist][kMaxT]; double Hf[kHist][kMaxT]; double aBest[kMaxT]; double fBest[kMaxT]; double rBest[kMaxT];
@@ -378,6 +378,37 @@ __device__ __forceinline__ void phase3_range(LdsT& L, int first, int last, int p
     }
 }
 
+// The evaluator for up to eight drafts takes phase 3 in two parts: the first CL terms, which every token needs, and
+// the terms CL + 1 .. D of a token that needs them all.
+// Phase 3: the sum of phase3_pair by Horner's rule in q = e[0], with Tp[k-1] = T_{n-k} / k!, so that only q is read:
+//   cn = q (Tp_1 + q (g_2 Tp_2 + ... + q (g_CL Tp_CL + q top))),  top = g_{CL+1} Tp_{CL+1} + q (... + q g_D Tp_D)
+// for a token that needs all terms, top = 0 otherwise.
+template <int D, int CL>
+__device__ __forceinline__ double loo_top(const double (&Tp)[D], double q, double v, double s) {
+    if constexpr (D > CL) {
+        double g[D];
+        cum_g_from<CL + 1, D>(v, s, g);
+        double h = g[D - 1] * Tp[D - 1];
+#pragma unroll
+        for (int k = D - 1; k > CL; --k) h = fma(q, h, g[k - 1] * Tp[k - 1]);
+        return h;
+    } else {
+        return 0.0;
+    }
+}
+template <int D, int CL>
+__device__ __forceinline__ double loo_low(const double (&Tp)[D], double q, double v, double s, double top) {
+    double h = top;
+    if constexpr (CL >= 2) {
+        double g[CL];
+        cum_g_from<1, CL>(v, s, g);
+#pragma unroll
+        for (int k = CL; k >= 2; --k) h = fma(q, h, g[k - 1] * Tp[k - 1]);
+    }
+    h = fma(q, h, Tp[0]);
+    return q * h;
+}
+
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -416,7 +447,11 @@ __device__ __forceinline__ Grid make_grid(int slack, double ctx, double wsum, do
 // Out: every wave's partial sums in L.rpart / L.spart / L.r0part.  All waves call it behind a barrier that made
 // the weights visible; it contains no workgroup barrier itself.
 template <int D>
+__device__ __forceinline__ void eval_core_rows(Lds<D>& L, const Grid& gr, int m, int n, double ctx, int slack);
+
+template <int D>
 __device__ __forceinline__ void eval_core(Lds<D>& L, const Grid& gr, int m, int n, double ctx, int slack) {
+    if constexpr (D <= 8) { eval_core_rows<D>(L, gr, m, n, ctx, slack); return; }
     constexpr int kSW = Lds<D>::kSW, NPW = Lds<D>::kNPW, NS = 64 / NPW;
     constexpr int CL = D < 4 ? D : 4;                          // cumulants of a light token
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -504,6 +539,134 @@ __device__ __forceinline__ void eval_core(Lds<D>& L, const Grid& gr, int m, int 
             const double a = wave_sum(hacc[hv]), b = wave_sum(hacct[hv]);
             if (lane == 0) { L.rpart[wv][hv] = a; L.spart[wv][hv] = b; }
         }
+    }
+    {
+        const double r0w = wave_sum(r0);
+        if (lane == 0) L.r0part[wv] = r0w;
+    }
+    if (tid == 0) L.work += static_cast<double>(N) * m;
+}
+
+// The same evaluation for up to eight drafts (no heavy tokens there), both phases in ONE lane layout: lane = (node j
+// of the wave, token subset tsub), token row i of a lane = token NS i + tsub.  The factor x = e^{-t w} of a (node,
+// token) pair is computed once, in phase 1, and stays in a register until phase 3 uses it again (NT = kMaxT / NS rows
+// per lane; the row loops are unrolled so that the array is indexed by constants).  Phase 3 then needs the node's
+// series, which this lane already holds, and the token's q; it ends with a sum over the NPW neighbouring lanes that
+// hold the nodes of a subset.  No node records in LDS and no exchange between the phases.
+// Rows whose first token is below L.nfull take all D cumulants, the others four.
+template <int D>
+__device__ __forceinline__ void eval_core_rows(Lds<D>& L, const Grid& gr, int m_, int n_, double ctx, int slack_) {
+    constexpr int kSW = Lds<D>::kSW, NPW = Lds<D>::kNPW, NS = 64 / NPW, NT = kMaxT / NS;
+    constexpr int CL = D < 4 ? D : 4;
+    static_assert(D <= 8 && NPW == 8 && NT % 2 == 0, "rows are taken two at a time; eight node lanes per subset");
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    // the sizes are the same in every lane; said so, the row guards below are scalar branches, not lane masks
+    const int m = __builtin_amdgcn_readfirstlane(m_), n = __builtin_amdgcn_readfirstlane(n_);
+    const int slack = __builtin_amdgcn_readfirstlane(slack_);
+    const int nfull = (D > 4) ? __builtin_amdgcn_readfirstlane(L.nfull) : 0;
+    const double t_lo = gr.t_lo, step = gr.step;
+    const int N = __builtin_amdgcn_readfirstlane(gr.N);
+    const int j = lane & (NPW - 1), tsub = lane / NPW;
+    for (int i = lane; i < kMaxT; i += 64) { L.rpart[wv][i] = 0.0; L.spart[wv][i] = 0.0; }
+    double r0 = 0.0;                                       // slack integrand, lanes of token subset 0
+    GR_CLK(L, 6);
+
+    for (int c0 = 0; c0 < N; c0 += 64) {
+        const int nn = min(64, N - c0);
+        const int npw = (nn - wv + kSW - 1) / kSW;          // nodes of this wave in the chunk: c0 + wv + kSW j
+        const double t = t_lo * exp(step * static_cast<double>(c0 + wv + kSW * j));
+        const double qw = j < npw ? step * t * exp_neg(slack * t, L.e2tab) : 0.0;
+        // ---- phase 1: cumulant sums at this lane's node over the tokens of its subset
+        double K[D], xs[NT];
+#pragma unroll
+        for (int k = 0; k < D; ++k) K[k] = 0.0;
+        // the weights of a pair of rows are requested one pair ahead: they head the longest chain (the exponential)
+        double awa = L.trec[tsub].aw, awb = L.trec[tsub + NS].aw;
+#pragma unroll
+        for (int i = 0; i < NT; i += 2) {
+            xs[i] = 0.0; xs[i + 1] = 0.0;
+            if (NS * i < m) {
+                const int a = NS * i + tsub, b = a + NS;
+                const TokRec<D>& ra = L.trec[a];               // the records behind the last token have x = 0
+                const TokRec<D>& rb = L.trec[b];
+                const double ya = t * awa, yb = t * awb;
+                if (i + 2 < NT) {
+                    awa = L.trec[b + NS].aw;
+                    awb = L.trec[b + 2 * NS].aw;
+                }
+                double x0, x1;
+                exp_neg2(ya, yb, L.e2tab, x0, x1);
+                if (D > 4 && NS * i < nfull) { phase1_token<D, D>(K, ra, x0); phase1_token<D, D>(K, rb, x1); }
+                else { phase1_token<D, CL>(K, ra, x0); phase1_token<D, CL>(K, rb, x1); }
+                xs[i] = x0; xs[i + 1] = x1;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+            if (NS >= 8) K[k] += __shfl_xor(K[k], 8);
+            K[k] += __shfl_xor(K[k], 16);
+            K[k] += __shfl_xor(K[k], 32);
+        }
+        GR_CLK(L, 7);
+        // ---- phase 2: the node's series T = exp(z ctx + sum_k K_k z^k), every lane of the node alike
+        K[0] += ctx;
+        double T[D + 1];
+        T[0] = 1.0;
+        {
+            double kK[D];
+#pragma unroll
+            for (int k = 1; k <= D; ++k) kK[k - 1] = static_cast<double>(k) * K[k - 1];
+#pragma unroll
+            for (int d = 1; d <= D; ++d) {
+                double acc = kK[0] * T[d - 1];
+#pragma unroll
+                for (int k = 2; k <= d; ++k) acc = fma(kK[k - 1], T[d - k], acc);
+                T[d] = acc * (1.0 / d);
+            }
+        }
+        double Tp[D];                                      // quadrature weight x T_{n-k} / k!
+        {
+            NodeRec<D> rec;
+            const double tn = pick_series<D, D>(rec, T, n);
+            if (tsub == 0) r0 = fma(qw, tn, r0);
+            double invf = qw;
+#pragma unroll
+            for (int k = 1; k <= D; ++k) { invf *= 1.0 / k; Tp[k - 1] = rec.Tr[k - 1] * invf; }
+        }
+        GR_CLK(L, 8);
+        // ---- phase 3: the leave-one-out coefficient of every pair, summed over the nodes of the wave.  The sums over
+        // the eight node lanes of a subset: the first step (lane k with lane 7 - k) also parts the two sums, R to
+        // lanes 0-3 and its t-weighted companion S to lanes 4-7, so that the other two steps move one value, not two.
+        double qna = L.trec[tsub].e[0], qnb = L.trec[tsub + NS].e[0];
+        const bool upper = (NPW == 8) && j >= 4;
+        double* const part = upper ? &L.spart[wv][0] : &L.rpart[wv][0];
+#pragma unroll
+        for (int i = 0; i < NT; i += 2) {
+            if (NS * i < m) {
+                const int a = NS * i + tsub, b = a + NS;            // b <= kMaxT - 1: sums of rows past the last token are 0
+                double olda = 0.0, oldb = 0.0;
+                if ((j & 3) == 0) { olda = part[a]; oldb = part[b]; }
+                const double qa = qna, qb = qnb;
+                if (i + 2 < NT) {
+                    qna = L.trec[b + NS].e[0];
+                    qnb = L.trec[b + 2 * NS].e[0];
+                }
+                const double x0 = xs[i], x1 = xs[i + 1];
+                const double v0 = fma(-x0, x0, x0), s0 = fma(-2.0, x0, 1.0), v1 = fma(-x1, x1, x1), s1 = fma(-2.0, x1, 1.0);
+                double ta = 0.0, tb = 0.0;
+                if (D > CL && NS * i < nfull) { ta = loo_top<D, CL>(Tp, qa, v0, s0); tb = loo_top<D, CL>(Tp, qb, v1, s1); }
+                const double ca = loo_low<D, CL>(Tp, qa, v0, s0, ta), cb = loo_low<D, CL>(Tp, qb, v1, s1, tb);
+                const double ra_ = xs[i] * ca, rb_ = xs[i + 1] * cb;
+                const double sa_ = ra_ * t, sb_ = rb_ * t;
+                double ka = upper ? sa_ : ra_, kb = upper ? sb_ : rb_;
+                ka += dpp_move<kDppHalfMirror>(upper ? ra_ : sa_);
+                kb += dpp_move<kDppHalfMirror>(upper ? rb_ : sb_);
+                ka += dpp_move<kDppXor1>(ka); kb += dpp_move<kDppXor1>(kb);
+                ka += dpp_move<kDppXor2>(ka); kb += dpp_move<kDppXor2>(kb);
+                if ((j & 3) == 0) { part[a] = olda + ka; part[b] = oldb + kb; }
+            }
+        }
+        GR_CLK(L, 9);
     }
     {
         const double r0w = wave_sum(r0);
@@ -928,8 +1091,8 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, int& par, double* newton
         full = (D > 4 && !(binom * r * r * r * r / 5.0 < 1e-11)) ? 1 : 0;
     }
     if (tid < 32) L.e2tab[tid] = exp2(-static_cast<double>(tid) / 32.0);
-    if (tid < 4) {
-        TokRec<D>& z = L.trec[m + tid];
+    if (tid >= m && tid < kMaxT + 4) {                     // every record behind the last token: x = 0, no mass
+        TokRec<D>& z = L.trec[tid];
         z.aw = 1e300; z.pad = 0.0;
 #pragma unroll
         for (int a = 0; a < D; ++a) z.e[a] = 0.0;
