@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the Global Resolution verifier on one MI355X.
 
-One "step" = the whole hot path over one batch of synthetic input already resident in HBM:
-gr_solve (streaming support selection + per-row solve) followed by gr_verify.  Default workload:
-the large-vocabulary configuration (B=256 rows, V=128256, n=8 drafts, top-k 128).
+One "step" = the whole hot path over one batch of synthetic input already resident in HBM: streaming support
+selection, per-row solve, verification of every row -- one gr_solve_verify call (the workgroup that solved a row
+verifies it in the same launch); --two-calls times gr_solve followed by gr_verify instead, and rows given as logits
+(--logits) always take the two calls.  Default workload: the large-vocabulary configuration (B=256 rows, V=128256,
+n=8 drafts, top-k 128).
 
 The timed region: K steps on ONE stream, one batch at a time, between two device synchronisations, with HIP
 events around every step and around every kernel launch; `value` = B K / wall time of that region, the
@@ -150,6 +152,8 @@ def main():
                     help="workload sweep: run the top-k sizes up to the whole vocabulary (HBM-resident ordering)")
     ap.add_argument("--tail-mass", type=float, default=0.0,
                     help="nucleus cut of the draft (gr_config.tail_mass) for workloads without a top-k; 0: none")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="time gr_solve followed by gr_verify (two launches after the selection pass) instead of gr_solve_verify")
     ap.add_argument("--streams", type=int, default=3,
                     help="handles / HIP streams the steps of the second timed region are dealt to (1: skip that region); "
                          "three of them plus the default stream fill the four hardware queues of a process")
@@ -188,7 +192,12 @@ def main():
         p = torch.from_numpy(wl.meta["target_logits"]).to(dev); q = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
         temps = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
 
+    fused = not (args.logits or args.two_calls)
+
     def step():
+        if fused:
+            gr.gr_solve_verify(h, p, q, wl.n, wl.k, args.tol, d, u, acc, st, tok, ok)
+            return
         if args.logits:
             gr.gr_solve_logits(h, p, q, temps, wl.n, wl.k, args.tol, acc, st)
         else:
@@ -244,6 +253,9 @@ def main():
         def pstep(i):
             j = i % ns
             a, s_, t_, o_ = outs[j]
+            if fused:
+                gr.gr_solve_verify(hs[j], ins[j][0], ins[j][1], wl.n, wl.k, args.tol, d, u, a, s_, t_, o_, stream=ss[j])
+                return
             if args.logits:
                 gr.gr_solve_logits(hs[j], ins[j][0], ins[j][1], temps, wl.n, wl.k, args.tol, a, s_, stream=ss[j])
             else:
@@ -292,7 +304,9 @@ def main():
         hbm_path = k_eff > 256                         # support kept in HBM: other kernels behind the same three events
         first, second = (("full_order+full_scan+full_trunc kernels", "full_programs_kernel") if hbm_path
                          else ("select_kernel", "solve_kernel"))
-        kernels = {first: prof["select_ms"], second: prof["solve_ms"], "verify_kernel": prof["verify_ms"]}
+        kernels = {first: prof["select_ms"], second: prof["solve_ms"]}
+        if not (fused and not hbm_path):               # one launch solves and verifies: no verify kernel of its own
+            kernels["verify_kernel"] = prof["verify_ms"]
         dom = max(kernels, key=kernels.get)
         if dom == first:
             achieved = algo_bytes / (kernels[dom] * 1e-3) / 1e9
@@ -330,7 +344,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
-                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "rows_given_as": "logits" if args.logits else "probabilities", "streams": 1},
+                   "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "rows_given_as": "logits" if args.logits else "probabilities", "streams": 1,
+                   "calls_per_step": "gr_solve_verify" if fused else ("gr_solve_logits" if args.logits else "gr_solve") + " + gr_verify"},
         "step_events": step_events,
         "pipelined": pipelined,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],

@@ -180,6 +180,19 @@ int gr_accept_sweep_noalloc(const float* p, const float* q, const int* ks, int n
 int gr_verify(gr_handle h, const int* drafts, const float* uniforms,
               int* token, unsigned char* accepted, void* hip_stream);
 
+/*
+ * gr_solve followed by gr_verify as one call, for callers that hold the drafts when they ask for the solve (the
+ * verification step of Sec. 3.1: the drafts are drawn before the verifier runs).  Arguments, outputs, order of the
+ * sampled tokens and error codes are those of the two calls (all device pointers; drafts [B, n], uniforms [B]); the
+ * results are identical to theirs.  With a support of at most GR_MAX_SUPPORT tokens the workgroup that solved a row
+ * verifies it in the same launch, as soon as the row's policy is written, so that the verification of the rows that
+ * finish early hides behind the rows that still iterate; larger supports run the two steps one after the other.  The
+ * handle keeps the policy as after gr_solve (gr_verify, gr_policy_* may follow).
+ */
+int gr_solve_verify(gr_handle h, const float* p, const float* q, int n, int k, float tol, int B, int V,
+                    const int* drafts, const float* uniforms, float* accept_prob, int* status,
+                    int* token, unsigned char* accepted, void* hip_stream);
+
 /* Test / inspection entry points --------------------------------------------------- */
 
 /*

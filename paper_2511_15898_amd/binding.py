@@ -19,7 +19,7 @@ GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED, GR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 GR_NOALLOC_MAX_B = 256
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_profile_stride", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_profile_stride", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_solve_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -56,6 +56,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_accept_sweep.argtypes = [vp, vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.gr_solve_verify.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.gr_tree_walk.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
@@ -253,6 +254,33 @@ def gr_verify(handle: int, drafts: torch.Tensor, uniforms: torch.Tensor, token: 
     if rc != GR_OK:
         raise GrError(rc, "gr_verify")
     return token, accepted
+
+
+def gr_solve_verify(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: int, tol: float, drafts: torch.Tensor,
+                    uniforms: torch.Tensor, accept_prob: torch.Tensor | None = None, status: torch.Tensor | None = None,
+                    token: torch.Tensor | None = None, accepted: torch.Tensor | None = None, stream=None):
+    """gr_solve and gr_verify in one call.  Returns (accept_prob, status, token, accepted)."""
+    if p.dim() != 2 or p.shape != q.shape:
+        raise TypeError("gr_solve_verify: p and q must both be [B, V]")
+    B, V = p.shape
+    if drafts.dim() != 2 or tuple(drafts.shape) != (B, n):
+        raise TypeError(f"gr_solve_verify: drafts must be [B, n] = {(B, n)}, got {tuple(drafts.shape)}")
+    if uniforms.dim() != 1 or uniforms.shape[0] != B:
+        raise TypeError("gr_solve_verify: uniforms must be [B]")
+    dev = p.device
+    accept_prob = torch.empty(B, dtype=torch.float32, device=dev) if accept_prob is None else accept_prob
+    status = torch.empty(B, dtype=torch.int32, device=dev) if status is None else status
+    token = torch.empty(B, dtype=torch.int32, device=dev) if token is None else token
+    accepted = torch.empty(B, dtype=torch.uint8, device=dev) if accepted is None else accepted
+    rc = load_library().gr_solve_verify(handle, _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), n, k, tol, B, V,
+                                        _ptr(drafts, torch.int32, "drafts"), _ptr(uniforms, torch.float32, "uniforms"),
+                                        _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
+                                        _ptr(token, torch.int32, "token"), _ptr(accepted, torch.uint8, "accepted"), _stream(stream))
+    if rc != GR_OK:
+        _solved_shape.pop(handle, None)
+        raise GrError(rc, "gr_solve_verify")
+    _solved_shape[handle] = (B, n, V)
+    return accept_prob, status, token, accepted
 
 
 def gr_policy_slice(handle: int, drafts: torch.Tensor, V: int, stream=None):

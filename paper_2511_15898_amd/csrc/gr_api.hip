@@ -192,8 +192,10 @@ int solve_in_hbm(gr_handle h, const float* p, const float* q, const float* tempe
 }
 
 // The LDS-resident path of gr_solve (temperature == nullptr: p and q are probabilities) and of gr_solve_logits.
+// With drafts (and uniforms, token, accepted) the solve kernel also verifies every row; otherwise all four are nullptr.
 int solve_in_lds(gr_handle h, const float* p, const float* q, const float* temperature, const float* draft_temperature, int n, int k_eff, float tol, int B, int V,
-                 float* accept_prob, int* status, hipStream_t stream) {
+                 float* accept_prob, int* status, hipStream_t stream, const int* drafts = nullptr, const float* uniforms = nullptr,
+                 int* token = nullptr, unsigned char* accepted = nullptr) {
     h->full_mode = false;
     const int splits = choose_splits(B, V);
     int slice_len = (V + splits - 1) / splits;
@@ -217,6 +219,8 @@ int solve_in_lds(gr_handle h, const float* p, const float* q, const float* tempe
     sp.logits = temperature ? 1 : 0; sp.temperature = temperature; sp.part_pref = h->part_pref; sp.draft_temperature = draft_temperature;
     sp.order = h->order; sp.block = h->block; sp.weight = h->weight; sp.rho = h->rho; sp.pnorm = h->pnorm;
     sp.info = h->info; sp.accept_prob = accept_prob; sp.status = status; sp.newton_ws = h->newton_ws;
+    sp.v_drafts = drafts; sp.v_uniforms = uniforms; sp.v_token = token; sp.v_accepted = accepted;
+    sp.piece_psum = h->piece_psum; sp.piece_stride = h->piece_stride; sp.piece_pref = h->piece_pref;
     if (launch_solve(sp, stream) != hipSuccess) return GR_EHIP;
     mark(h, 2, stream);
     h->solved = true; h->p = p; h->B = B; h->V = V; h->n = n;
@@ -290,6 +294,30 @@ extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
     return solve_in_lds(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+}
+
+/* gr_solve and gr_verify in one call: see gr_verify.h. */
+extern "C" int gr_solve_verify(gr_handle h, const float* p, const float* q, int n, int k, float tol, int B, int V,
+                               const int* drafts, const float* uniforms, float* accept_prob, int* status, int* token,
+                               unsigned char* accepted, void* hip_stream) {
+    if (!h || !p || !q || !accept_prob || !status || !drafts || !uniforms || !token || !accepted) return GR_EINVAL;
+    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
+    if (n < 1 || n > h->max_n) return GR_EINVAL;
+    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
+    const int k_eff = (k <= 0 || k >= V) ? V : k;
+    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (k_eff > kMaxSupport) {                       // the HBM-resident path keeps its two steps
+        const int rc = solve_in_hbm(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+        return rc != GR_OK ? rc : gr_verify(h, drafts, uniforms, token, accepted, hip_stream);
+    }
+    const int rc = solve_in_lds(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream, drafts, uniforms, token, accepted);
+    if (rc != GR_OK) return rc;
+    mark(h, 3, stream);
+    mark(h, 4, stream);
+    if (h->prof_now && h->prof_count < kProfSlots) ++h->prof_count;
+    h->prof_now = false;
+    return GR_OK;
 }
 
 /* Rows given as logits: see gr_verify.h. */

@@ -57,6 +57,10 @@ struct SolveParams {
     RowInfo* info;                    // [B]
     float* accept_prob; int* status;  // caller's outputs [B]
     double* newton_ws;                // [B, kMaxT * (kMaxT + 1)] Jacobian scratch of the Newton fallback
+    // verification in the same launch (v_drafts == nullptr: none): drafts [B, n], uniforms [B] -> token [B], accepted [B];
+    // the sums of p over pieces of 256 tokens that the select pass left, as in PolicyView
+    const int* v_drafts; const float* v_uniforms; int* v_token; unsigned char* v_accepted;
+    const double* piece_psum; int piece_stride; const float* piece_pref;
 };
 
 // Workspace and arguments of the full-vocabulary path (no top-k).  Per-token arrays are row-major with

@@ -19,6 +19,7 @@
 // Bernoulli(x) variable, and only k <= n can reach the z^n coefficient, so n cumulant sums per
 // quadrature node describe all tokens exactly; the series exponential is taken once per node.
 #include "gr_internal.h"
+#include "gr_verify_row.h"
 
 namespace gr {
 
@@ -866,6 +867,7 @@ __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int
         if (!(g[u] == g[u])) g[u] = 1e301;
         al[u] = L.aal[tk[u]];
     }
+    GR_CLK(L, 18);
     const double R0 = slack_mass<D>(L, gr, n, atot, fact, slack);
     // stopping measure: max_i | log(target_i / routed_i) - common term |, the common term log(slack_target / slack
     // mass) with slack, log(sum target / sum routed) without (zero in exact arithmetic: it removes the common
@@ -873,6 +875,7 @@ __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int
     double rd[3] = {(on[0] ? R[0] : 0.0) + (on[1] ? R[1] : 0.0), fmax(on[0] ? g[0] : -1e300, on[1] ? g[1] : -1e300),
                     fmin(on[0] ? g[0] : 1e300, on[1] ? g[1] : 1e300)};
     wave_reduce_many<3>(rd, {kOpSum, kOpMax, kOpMin});
+    GR_CLK(L, 19);
     const double lc = fast_log(slack ? R0 * fast_rcp(slack_target) : rd[0] * fast_rcp(tsum));
     double err = fmax(fabs(rd[1] + lc), fabs(rd[2] + lc));
     if (!(err == err) || !(rd[1] < 1e300) || !(rd[2] > -1e300)) err = 1e301;      // NaN or infinite: "no finite point"
@@ -1236,6 +1239,7 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
             sp.info[row] = info;
             sp.accept_prob[row] = __uint_as_float(0x7fc00000u);
             sp.status[row] = GR_ROW_BAD;
+            if (sp.v_drafts) { sp.v_token[row] = -1; sp.v_accepted[row] = 0; }
         }
         return;
     }
@@ -1531,17 +1535,31 @@ __global__ __launch_bounds__(kThreadsOf<D>) void solve_kernel(SolveParams sp) {
         o_order[tid] = L.tok[tid]; o_block[tid] = L.blk[tid]; o_w[tid] = L.wgt[tid];
         o_rho[tid] = L.rho[tid]; o_pn[tid] = L.pn[tid];
     }
+    info.support = kk; info.h = h; info.status = status; info.iterations = evals;
+    info.alpha_star = 1.0 + L.F[h];
+    info.res_total = -L.F[h];
+    info.node_tokens = L.work;
     if (tid == 0) {
-        info.support = kk; info.h = h; info.status = status; info.iterations = evals;
-        info.alpha_star = 1.0 + L.F[h];
-        info.res_total = -L.F[h];
-        info.node_tokens = L.work;
 #ifdef GR_PHASE_CLOCKS
         { const long long now_ = clock64(); L.clk[14] += now_ - L.clk_last; for (int i = 0; i < 24; ++i) { info.clk[i] = L.clk[i]; info.errlog[i] = i < evals ? L.errlog[i] : 0.0; } }
 #endif
         sp.info[row] = info;
         sp.accept_prob[row] = static_cast<float>(1.0 + L.F[h]);
         sp.status[row] = status;
+    }
+    // ---- the row's verification, when the drafts came with the call: the same routine as verify_kernel, run by the
+    // first kThreads threads on the policy this workgroup has just written (visible to it behind the barrier).  The
+    // other waves end here; a workgroup barrier waits for the waves that are still alive only.
+    if (sp.v_drafts) {
+        __syncthreads();
+        if (tid >= kThreads) __builtin_amdgcn_endpgm();
+        RowPolicy rp;
+        rp.o = o_order; rp.bl = o_block; rp.wt = o_w; rp.rh = o_rho; rp.rk = nullptr; rp.rid = nullptr;
+        rp.pieces = sp.piece_psum ? sp.piece_psum + static_cast<size_t>(row) * sp.piece_stride : nullptr;
+        rp.prefs = sp.piece_pref ? sp.piece_pref + static_cast<size_t>(row) * sp.piece_stride : nullptr;
+        static_assert(sizeof(VerifyLds) <= sizeof(Lds<D>), "the verification reuses the solve's LDS");
+        verify_row(*reinterpret_cast<VerifyLds*>(gr_lds_raw), sp.p + static_cast<size_t>(row) * sp.V, sp.V, sp.n, rp, info,
+                   sp.v_drafts + static_cast<size_t>(row) * sp.n, sp.v_uniforms[row], sp.v_token + row, sp.v_accepted + row);
     }
 }
 
