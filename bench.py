@@ -35,7 +35,7 @@ FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) on the default
 # workload, scaled by what the same counters read for the device copy of 8 V B bytes that this script runs itself
 # (profiles/hbm_traffic_large_vocab.md).  Only valid for that workload at the default tau.
-MEASURED_TRAFFIC_BYTES = {"select_kernel": 266580000, "solve_kernel": 27911000, "verify_kernel": 637000}
+MEASURED_TRAFFIC_BYTES = {"select_kernel": 266582000, "solve_kernel": 40973000, "verify_kernel": 636000}
 
 
 def _oracle_row(job):
@@ -324,6 +324,8 @@ def main():
                         "frac": None, "traffic": None}
         if args.workload == "large" and abs(args.tol - 1e-4) < 1e-12:
             roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(dom)
+            if fused and dom == "solve_kernel":        # the launch that also verifies the rows moves the verify kernel's bytes too
+                roofline["traffic"] += MEASURED_TRAFFIC_BYTES["verify_kernel"]
             roofline["traffic_all_kernels"] = MEASURED_TRAFFIC_BYTES or None
         roofline["region"] = "the timed region: one stream, one batch at a time (launch durations from HIP events)"
         roofline["kernel_ms"] = {k: round(v, 5) for k, v in kernels.items()}
