@@ -492,10 +492,13 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const f
                 (temperature && hipMemcpyAsync(h->tw_temp, ts.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess)) return GR_EHIP;
             hipLaunchKernelGGL(gather_rows_kernel, dim3(cnt), dim3(kThreads), 0, stream, p, q, h->tw_idx, h->tw_p, h->tw_q, V);
             if (hipGetLastError() != hipSuccess) return GR_EHIP;
-            int rc = temperature ? gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, nullptr, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream)
-                                 : gr_solve(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
-            if (rc != GR_OK) return rc;
-            rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);
+            int rc;
+            if (temperature) {
+                rc = gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, nullptr, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
+                if (rc == GR_OK) rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);
+            } else {
+                rc = gr_solve_verify(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_drafts, h->tw_u, h->tw_acc, h->tw_status, h->tw_tok, h->tw_ok, stream);
+            }
             if (rc != GR_OK) return rc;
             tok.resize(cnt); st.resize(cnt); okv.resize(cnt);
             if (hipMemcpyAsync(tok.data(), h->tw_tok, sizeof(int) * cnt, hipMemcpyDeviceToHost, stream) != hipSuccess ||
