@@ -76,6 +76,9 @@ struct Lds {
     double Q[KS + 1]; double F[KS + 2];
     // one convex program (tokens by decreasing q)
     double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aR[kMaxT];
+    double aS[kMaxT]; double ag[kMaxT];   // with aR: what one evaluation hands to the mixing step (see solve_program)
+    double aR0, alc;                      // ... the slack mass and, with slack, log(slack mass / its target)
+    double ared[2][3];                    // ... and the first two waves' sum of R, max and min of log(target / R)
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
     double aw[kMaxT]; double af[kMaxT]; int adeg[kMaxT];   // staging of the HBM-path programs kernel
     // Newton fallback (its Jacobian lives in a per-row HBM scratch)
@@ -862,21 +865,16 @@ __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int
     double R[2] = {0.0, 0.0}, S[2] = {0.0, 0.0}, g[2] = {0.0, 0.0}, al[2] = {0.0, 0.0};
 #pragma unroll
     for (int u = 0; u < 2; ++u) if (on[u]) {
-        token_sums<D>(L, gr, tk[u], fact, R[u], S[u]);
-        g[u] = fast_log(L.at[tk[u]] * fast_rcp(R[u]));
-        if (!(g[u] == g[u])) g[u] = 1e301;
+        R[u] = L.aR[tk[u]]; S[u] = L.aS[tk[u]]; g[u] = L.ag[tk[u]];
         al[u] = L.aal[tk[u]];
     }
     GR_CLK(L, 18);
-    const double R0 = slack_mass<D>(L, gr, n, atot, fact, slack);
     // stopping measure: max_i | log(target_i / routed_i) - common term |, the common term log(slack_target / slack
     // mass) with slack, log(sum target / sum routed) without (zero in exact arithmetic: it removes the common
     // quadrature error)
-    double rd[3] = {(on[0] ? R[0] : 0.0) + (on[1] ? R[1] : 0.0), fmax(on[0] ? g[0] : -1e300, on[1] ? g[1] : -1e300),
-                    fmin(on[0] ? g[0] : 1e300, on[1] ? g[1] : 1e300)};
-    wave_reduce_many<3>(rd, {kOpSum, kOpMax, kOpMin});
+    const double rd[3] = {L.ared[0][0] + L.ared[1][0], fmax(L.ared[0][1], L.ared[1][1]), fmin(L.ared[0][2], L.ared[1][2])};
     GR_CLK(L, 19);
-    const double lc = fast_log(slack ? R0 * fast_rcp(slack_target) : rd[0] * fast_rcp(tsum));
+    const double lc = slack ? L.alc : fast_log(rd[0] * fast_rcp(tsum));
     double err = fmax(fabs(rd[1] + lc), fabs(rd[2] + lc));
     if (!(err == err) || !(rd[1] < 1e300) || !(rd[2] > -1e300)) err = 1e301;      // NaN or infinite: "no finite point"
 #ifdef GR_PHASE_CLOCKS
@@ -1147,6 +1145,25 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, int& par, double* newton
         *evals += 1;
         __syncthreads();                                   // every wave's partial sums are in place
         GR_CLK(L, 10);
+        // one token per thread: its routed mass R, the companion S and log(target / R); one thread the slack mass.
+        // Done here by the first waves side by side, not by the mixing wave for two tokens per lane.
+        if (tid < kMaxT) {                                 // the first two waves, whole
+            double R = 0.0, S = 0.0, g = 0.0;
+            if (tid < m) {
+                token_sums<D>(L, gr, tid, fact, R, S);
+                g = fast_log(L.at[tid] * fast_rcp(R));
+                if (!(g == g)) g = 1e301;
+                L.aR[tid] = R; L.aS[tid] = S; L.ag[tid] = g;
+            }
+            double a3[3] = {tid < m ? R : 0.0, tid < m ? g : -1e300, tid < m ? g : 1e300};
+            wave_reduce_many<3>(a3, {kOpSum, kOpMax, kOpMin});
+            if (lane == 0) { L.ared[wvi][0] = a3[0]; L.ared[wvi][1] = a3[1]; L.ared[wvi][2] = a3[2]; }
+        } else if (tid == kMaxT) {
+            const double R0 = slack_mass<D>(L, gr, n, atot, fact, slack);
+            L.aR0 = R0;
+            if (slack) L.alc = fast_log(R0 * fast_rcp(slack_target));
+        }
+        __syncthreads();
         if (wvi != 0) continue;
         st = mix_step<D>(st, gr, it, m, n, slack, ctx, slack_target, tsum, atot, fact, rel_tol, *evals);
     }
