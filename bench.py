@@ -3,8 +3,8 @@
 
 One "step" = the whole hot path over one batch of synthetic input already resident in HBM: streaming support
 selection, per-row solve, verification of every row -- one gr_solve_verify call (the workgroup that solved a row
-verifies it in the same launch); --two-calls times gr_solve followed by gr_verify instead, and rows given as logits
-(--logits) always take the two calls.  Default workload: the large-vocabulary configuration (B=256 rows, V=128256,
+verifies it in the same launch; gr_solve_logits_verify with --logits); --two-calls times gr_solve (gr_solve_logits)
+followed by gr_verify instead.  Default workload: the large-vocabulary configuration (B=256 rows, V=128256,
 n=8 drafts, top-k 128).
 
 The timed region: K steps on ONE stream, one batch at a time, between two device synchronisations, with HIP
@@ -192,9 +192,12 @@ def main():
         p = torch.from_numpy(wl.meta["target_logits"]).to(dev); q = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
         temps = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
 
-    fused = not (args.logits or args.two_calls)
+    fused = not args.two_calls
 
     def step():
+        if fused and args.logits:
+            gr.gr_solve_logits_verify(h, p, q, temps, wl.n, wl.k, args.tol, d, u, acc, st, tok, ok)
+            return
         if fused:
             gr.gr_solve_verify(h, p, q, wl.n, wl.k, args.tol, d, u, acc, st, tok, ok)
             return
@@ -253,6 +256,9 @@ def main():
         def pstep(i):
             j = i % ns
             a, s_, t_, o_ = outs[j]
+            if fused and args.logits:
+                gr.gr_solve_logits_verify(hs[j], ins[j][0], ins[j][1], temps, wl.n, wl.k, args.tol, d, u, a, s_, t_, o_, stream=ss[j])
+                return
             if fused:
                 gr.gr_solve_verify(hs[j], ins[j][0], ins[j][1], wl.n, wl.k, args.tol, d, u, a, s_, t_, o_, stream=ss[j])
                 return
@@ -347,7 +353,8 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} rows x V={wl.V} vocab, n={wl.n} drafts, top-k={wl.k}, tau={args.tol:g}",
                    "B": wl.B, "V": wl.V, "n": wl.n, "k": wl.k, "tau": args.tol, "tail_mass": args.tail_mass, "rows_given_as": "logits" if args.logits else "probabilities", "streams": 1,
-                   "calls_per_step": "gr_solve_verify" if fused else ("gr_solve_logits" if args.logits else "gr_solve") + " + gr_verify"},
+                   "calls_per_step": ("gr_solve_logits_verify" if args.logits else "gr_solve_verify") if fused
+                                     else ("gr_solve_logits" if args.logits else "gr_solve") + " + gr_verify"},
         "step_events": step_events,
         "pipelined": pipelined,
         "status_histogram": [int(x) for x in np.bincount(status, minlength=4)],

@@ -193,6 +193,12 @@ int gr_solve_verify(gr_handle h, const float* p, const float* q, int n, int k, f
                     const int* drafts, const float* uniforms, float* accept_prob, int* status,
                     int* token, unsigned char* accepted, void* hip_stream);
 
+/* The same for rows given as logits: gr_solve_logits followed by gr_verify as one call (arguments of the two). */
+int gr_solve_logits_verify(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
+                           const float* draft_temperature, int n, int k, float tol, int B, int V,
+                           const int* drafts, const float* uniforms, float* accept_prob, int* status,
+                           int* token, unsigned char* accepted, void* hip_stream);
+
 /* Test / inspection entry points --------------------------------------------------- */
 
 /*

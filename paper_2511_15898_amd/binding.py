@@ -19,7 +19,7 @@ GR_ROW_OK, GR_ROW_TRUNC_CAP, GR_ROW_ITER_CAP, GR_ROW_BAD = 0, 1, 2, 3
 GR_OK, GR_EINVAL, GR_ENOMEM, GR_ESTATE, GR_EHIP, GR_EUNSUPPORTED, GR_ECAPACITY = 0, -1, -2, -3, -4, -5, -6
 GR_NOALLOC_MAX_B = 256
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_profile_stride", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_solve_verify", "gr_policy_slice", "gr_policy_export",
+EXPORTS = ("gr_create", "gr_destroy", "gr_solve", "gr_solve_logits", "gr_tree_walk", "gr_profile_stride", "gr_accept_sweep", "gr_accept_sweep_noalloc", "gr_verify", "gr_solve_verify", "gr_solve_logits_verify", "gr_policy_slice", "gr_policy_export",
            "gr_policy_export_row", "gr_solve_stats", "gr_profile_read", "gr_strerror")
 GR_FLAG_PROFILE = 1
 
@@ -57,6 +57,7 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.gr_accept_sweep_noalloc.argtypes = [vp, vp, ctypes.POINTER(ci), ci, ctypes.POINTER(ci), ci, ci, ci, vp, vp, vp]
     lib.gr_verify.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.gr_solve_verify.argtypes = [vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+    lib.gr_solve_logits_verify.argtypes = [vp, vp, vp, vp, vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.gr_tree_walk.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
     lib.gr_policy_slice.argtypes = [vp, vp, vp, vp, vp]
     lib.gr_policy_export.argtypes = [vp] * 9
@@ -279,6 +280,41 @@ def gr_solve_verify(handle: int, p: torch.Tensor, q: torch.Tensor, n: int, k: in
     if rc != GR_OK:
         _solved_shape.pop(handle, None)
         raise GrError(rc, "gr_solve_verify")
+    _solved_shape[handle] = (B, n, V)
+    return accept_prob, status, token, accepted
+
+
+def gr_solve_logits_verify(handle: int, target_logits: torch.Tensor, draft_logits: torch.Tensor, temperature: torch.Tensor, n: int,
+                           k: int, tol: float, drafts: torch.Tensor, uniforms: torch.Tensor, accept_prob: torch.Tensor | None = None,
+                           status: torch.Tensor | None = None, token: torch.Tensor | None = None,
+                           accepted: torch.Tensor | None = None, stream=None, draft_temperature: torch.Tensor | None = None):
+    """gr_solve_logits and gr_verify in one call.  Returns (accept_prob, status, token, accepted)."""
+    if target_logits.dim() != 2 or target_logits.shape != draft_logits.shape:
+        raise TypeError("gr_solve_logits_verify: target_logits and draft_logits must both be [B, V]")
+    B, V = target_logits.shape
+    if temperature.dim() != 1 or temperature.shape[0] != B:
+        raise TypeError("gr_solve_logits_verify: temperature must be [B]")
+    if draft_temperature is not None and (draft_temperature.dim() != 1 or draft_temperature.shape[0] != B):
+        raise TypeError("gr_solve_logits_verify: draft_temperature must be [B]")
+    if drafts.dim() != 2 or tuple(drafts.shape) != (B, n):
+        raise TypeError(f"gr_solve_logits_verify: drafts must be [B, n] = {(B, n)}, got {tuple(drafts.shape)}")
+    if uniforms.dim() != 1 or uniforms.shape[0] != B:
+        raise TypeError("gr_solve_logits_verify: uniforms must be [B]")
+    dev = target_logits.device
+    accept_prob = torch.empty(B, dtype=torch.float32, device=dev) if accept_prob is None else accept_prob
+    status = torch.empty(B, dtype=torch.int32, device=dev) if status is None else status
+    token = torch.empty(B, dtype=torch.int32, device=dev) if token is None else token
+    accepted = torch.empty(B, dtype=torch.uint8, device=dev) if accepted is None else accepted
+    rc = load_library().gr_solve_logits_verify(
+        handle, _ptr(target_logits, torch.float32, "target_logits"), _ptr(draft_logits, torch.float32, "draft_logits"),
+        _ptr(temperature, torch.float32, "temperature"),
+        None if draft_temperature is None else _ptr(draft_temperature, torch.float32, "draft_temperature"), n, k, tol, B, V,
+        _ptr(drafts, torch.int32, "drafts"), _ptr(uniforms, torch.float32, "uniforms"),
+        _ptr(accept_prob, torch.float32, "accept_prob"), _ptr(status, torch.int32, "status"),
+        _ptr(token, torch.int32, "token"), _ptr(accepted, torch.uint8, "accepted"), _stream(stream))
+    if rc != GR_OK:
+        _solved_shape.pop(handle, None)
+        raise GrError(rc, "gr_solve_logits_verify")
     _solved_shape[handle] = (B, n, V)
     return accept_prob, status, token, accepted
 

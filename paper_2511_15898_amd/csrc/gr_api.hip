@@ -283,17 +283,41 @@ extern "C" int gr_destroy(gr_handle h) {
     return GR_OK;
 }
 
-extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float tol,
-                        int B, int V, float* accept_prob, int* status, void* hip_stream) {
-    if (!h || !p || !q || !accept_prob || !status) return GR_EINVAL;
+namespace {
+
+// The four solve entry points: rows as probabilities (temperature == nullptr) or logits, with or without the rows'
+// verification (drafts == nullptr: without).  A support of at most kMaxSupport tokens runs select + solve, the solve
+// launch verifying its rows when asked to; a larger one the HBM-resident kernels, then the verify kernel.
+int solve_entry(gr_handle h, const float* p, const float* q, const float* temperature, const float* draft_temperature, int n, int k,
+                float tol, int B, int V, const int* drafts, const float* uniforms, float* accept_prob, int* status, int* token,
+                unsigned char* accepted, void* hip_stream) {
     if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
     if (n < 1 || n > h->max_n) return GR_EINVAL;
     if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
     const int k_eff = (k <= 0 || k >= V) ? V : k;
-    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;     // the handle holds no workspace for such a support
+    if (temperature && h->tail_mass > 0.0) return GR_EUNSUPPORTED;          // the nucleus cut is defined on probabilities
+    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;          // the handle holds no workspace for such a support
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (k_eff > kMaxSupport) return solve_in_hbm(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
-    return solve_in_lds(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
+    if (k_eff > kMaxSupport) {
+        const int rc = solve_in_hbm(h, p, q, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status, stream);
+        return (rc != GR_OK || !drafts) ? rc : gr_verify(h, drafts, uniforms, token, accepted, hip_stream);
+    }
+    const int rc = solve_in_lds(h, p, q, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status, stream, drafts, uniforms,
+                                token, accepted);
+    if (rc != GR_OK || !drafts) return rc;
+    mark(h, 3, stream);                              // no verify launch of its own: an empty interval in the profile
+    mark(h, 4, stream);
+    if (h->prof_now && h->prof_count < kProfSlots) ++h->prof_count;
+    h->prof_now = false;
+    return GR_OK;
+}
+
+}  // namespace
+
+extern "C" int gr_solve(gr_handle h, const float* p, const float* q, int n, int k, float tol,
+                        int B, int V, float* accept_prob, int* status, void* hip_stream) {
+    if (!h || !p || !q || !accept_prob || !status) return GR_EINVAL;
+    return solve_entry(h, p, q, nullptr, nullptr, n, k, tol, B, V, nullptr, nullptr, accept_prob, status, nullptr, nullptr, hip_stream);
 }
 
 /* gr_solve and gr_verify in one call: see gr_verify.h. */
@@ -301,23 +325,7 @@ extern "C" int gr_solve_verify(gr_handle h, const float* p, const float* q, int 
                                const int* drafts, const float* uniforms, float* accept_prob, int* status, int* token,
                                unsigned char* accepted, void* hip_stream) {
     if (!h || !p || !q || !accept_prob || !status || !drafts || !uniforms || !token || !accepted) return GR_EINVAL;
-    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
-    if (n < 1 || n > h->max_n) return GR_EINVAL;
-    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
-    const int k_eff = (k <= 0 || k >= V) ? V : k;
-    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (k_eff > kMaxSupport) {                       // the HBM-resident path keeps its two steps
-        const int rc = solve_in_hbm(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream);
-        return rc != GR_OK ? rc : gr_verify(h, drafts, uniforms, token, accepted, hip_stream);
-    }
-    const int rc = solve_in_lds(h, p, q, nullptr, nullptr, n, k_eff, tol, B, V, accept_prob, status, stream, drafts, uniforms, token, accepted);
-    if (rc != GR_OK) return rc;
-    mark(h, 3, stream);
-    mark(h, 4, stream);
-    if (h->prof_now && h->prof_count < kProfSlots) ++h->prof_count;
-    h->prof_now = false;
-    return GR_OK;
+    return solve_entry(h, p, q, nullptr, nullptr, n, k, tol, B, V, drafts, uniforms, accept_prob, status, token, accepted, hip_stream);
 }
 
 /* Rows given as logits: see gr_verify.h. */
@@ -325,17 +333,19 @@ extern "C" int gr_solve_logits(gr_handle h, const float* target_logits, const fl
                                const float* draft_temperature, int n, int k, float tol, int B, int V, float* accept_prob,
                                int* status, void* hip_stream) {
     if (!h || !target_logits || !draft_logits || !temperature || !accept_prob || !status) return GR_EINVAL;
-    if (B <= 0 || V <= 0 || B > h->max_B || V > h->max_V) return GR_EINVAL;
-    if (n < 1 || n > h->max_n) return GR_EINVAL;
-    if (!(tol >= 0.f) || !(tol < 1.f)) return GR_EINVAL;
-    const int k_eff = (k <= 0 || k >= V) ? V : k;
-    if (h->tail_mass > 0.0) return GR_EUNSUPPORTED;                         // the nucleus cut is defined on probabilities
-    if (k_eff > kMaxSupport && k_eff > h->k_cap) return GR_EINVAL;          // the handle holds no workspace for such a support
-    if (k_eff > kMaxSupport)
-        return solve_in_hbm(h, target_logits, draft_logits, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status,
-                            static_cast<hipStream_t>(hip_stream));
-    return solve_in_lds(h, target_logits, draft_logits, temperature, draft_temperature, n, k_eff, tol, B, V, accept_prob, status,
-                        static_cast<hipStream_t>(hip_stream));
+    return solve_entry(h, target_logits, draft_logits, temperature, draft_temperature, n, k, tol, B, V, nullptr, nullptr, accept_prob, status,
+                       nullptr, nullptr, hip_stream);
+}
+
+/* gr_solve_logits and gr_verify in one call: see gr_verify.h. */
+extern "C" int gr_solve_logits_verify(gr_handle h, const float* target_logits, const float* draft_logits, const float* temperature,
+                                      const float* draft_temperature, int n, int k, float tol, int B, int V, const int* drafts,
+                                      const float* uniforms, float* accept_prob, int* status, int* token, unsigned char* accepted,
+                                      void* hip_stream) {
+    if (!h || !target_logits || !draft_logits || !temperature || !accept_prob || !status || !drafts || !uniforms || !token || !accepted)
+        return GR_EINVAL;
+    return solve_entry(h, target_logits, draft_logits, temperature, draft_temperature, n, k, tol, B, V, drafts, uniforms, accept_prob, status,
+                       token, accepted, hip_stream);
 }
 
 extern "C" int gr_accept_sweep(gr_handle h, const float* p, const float* q, const int* ks, int nk, const int* ns, int nn,
@@ -492,13 +502,10 @@ extern "C" int gr_tree_walk(gr_handle h, const float* p, const float* q, const f
                 (temperature && hipMemcpyAsync(h->tw_temp, ts.data(), sizeof(float) * cnt, hipMemcpyHostToDevice, stream) != hipSuccess)) return GR_EHIP;
             hipLaunchKernelGGL(gather_rows_kernel, dim3(cnt), dim3(kThreads), 0, stream, p, q, h->tw_idx, h->tw_p, h->tw_q, V);
             if (hipGetLastError() != hipSuccess) return GR_EHIP;
-            int rc;
-            if (temperature) {
-                rc = gr_solve_logits(h, h->tw_p, h->tw_q, h->tw_temp, nullptr, n, k, tol, cnt, V, h->tw_acc, h->tw_status, stream);
-                if (rc == GR_OK) rc = gr_verify(h, h->tw_drafts, h->tw_u, h->tw_tok, h->tw_ok, stream);
-            } else {
-                rc = gr_solve_verify(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_drafts, h->tw_u, h->tw_acc, h->tw_status, h->tw_tok, h->tw_ok, stream);
-            }
+            const int rc = temperature
+                ? gr_solve_logits_verify(h, h->tw_p, h->tw_q, h->tw_temp, nullptr, n, k, tol, cnt, V, h->tw_drafts, h->tw_u, h->tw_acc, h->tw_status,
+                                         h->tw_tok, h->tw_ok, stream)
+                : gr_solve_verify(h, h->tw_p, h->tw_q, n, k, tol, cnt, V, h->tw_drafts, h->tw_u, h->tw_acc, h->tw_status, h->tw_tok, h->tw_ok, stream);
             if (rc != GR_OK) return rc;
             tok.resize(cnt); st.resize(cnt); okv.resize(cnt);
             if (hipMemcpyAsync(tok.data(), h->tw_tok, sizeof(int) * cnt, hipMemcpyDeviceToHost, stream) != hipSuccess ||

@@ -3,7 +3,8 @@ the same kernels' arithmetic on the same policy, so acceptance probability, stat
 compared bit for bit.  The two-call path is the one the other GPU tests hold against the CPU checker.  Cases: every
 configuration that fits the LDS-resident path, rows that fall back to sampling from p (cap on |T|, iteration cap),
 bad rows, draws that leave the drafts (uniforms near 1 walk the residual tokens), a support above GR_MAX_SUPPORT
-(which keeps the two steps inside the call), a ragged tiny vocabulary, and nine to sixteen drafts."""
+(which keeps the two steps inside the call), a ragged tiny vocabulary, nine to sixteen drafts, and rows given as
+logits (gr_solve_logits_verify against gr_solve_logits + gr_verify)."""
 import numpy as np
 import pytest
 
@@ -82,3 +83,28 @@ def test_large_support_keeps_two_steps_and_many_drafts():
     wl = W.llm_shaped(B=24, V=4096, n=12, k=48, seed_sub=13)              # the kernel for nine to sixteen drafts
     out = _both(wl, 1e-5)
     assert np.all(out["status"] == 0)
+
+
+def test_rows_given_as_logits():
+    import torch
+    from paper_2511_15898_amd import binding as gr
+    dev = torch.device("cuda:0")
+    for wl, tol, two_temps in ((W.small(keep_logits=True), 1e-6, False), (W.large_vocab(B=64, seed_sub=21, keep_logits=True), 1e-4, True),
+                               (W.llm_shaped(B=6, V=3000, n=3, k=500, seed_sub=22, keep_logits=True), 1e-4, False)):   # the last: HBM-resident support
+        tl = torch.from_numpy(wl.meta["target_logits"]).to(dev); dl = torch.from_numpy(wl.meta["draft_logits"]).to(dev)
+        T = torch.from_numpy(wl.meta["temps"].astype(np.float32)).to(dev)
+        Td = (T * 1.25) if two_temps else None
+        d = torch.from_numpy(wl.drafts).to(dev)                 # drawn from the float32 q: a draft that the logits' top-k does not
+        u = torch.from_numpy(wl.uniforms).to(dev)               # hold gives token -1 on both paths alike
+        h = gr.gr_create(wl.B, wl.V, max_k=wl.k, max_n=wl.n)
+        try:
+            acc, st = gr.gr_solve_logits(h, tl, dl, T, wl.n, wl.k, tol, draft_temperature=Td)
+            tok, ok = gr.gr_verify(h, d, u)
+            two = [x.clone() for x in (acc, st, tok, ok)]
+            one = [x.clone() for x in gr.gr_solve_logits_verify(h, tl, dl, T, wl.n, wl.k, tol, d, u, draft_temperature=Td)]
+            torch.cuda.synchronize()
+        finally:
+            gr.gr_destroy(h)
+        for name, a, b in zip(("accept_prob", "status", "token", "accepted"), two, one):
+            assert torch.equal(a.view(torch.int32) if name == "accept_prob" else a, b.view(torch.int32) if name == "accept_prob" else b), name
+        assert int((one[1] == 0).sum()) >= wl.B // 2 and int((one[2] >= 0).sum()) >= wl.B // 2
