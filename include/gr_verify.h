@@ -14,6 +14,7 @@
  *   gr_accept_sweep  alpha* alone over a grid of top-k sizes and draft counts (Thm 3.1, Sec. 5.1).
  *   gr_verify  the transport slice pi(.|drafts) (Eq. "cases" / Eq. "approx-c") and one
  *              inverse-CDF draw from it (App. A, multi-draft procedure, step 3).
+ *   gr_solve_verify, gr_solve_logits_verify  the two steps in one call.
  *
  * Conventions
  *   - every pointer argument except `out`, `cfg` and host-side scalars is a DEVICE pointer

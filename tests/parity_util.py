@@ -23,6 +23,10 @@ def run_gpu(wl, tol, max_iter=0, max_T=0, rel_tol=0.0, want_slice=True, drafts=N
         acc, st = gr.gr_solve(h, p, q, wl.n, wl.k, tol)
         tok, ok = gr.gr_verify(h, d, u)
         out = {"accept_prob": acc, "status": st, "token": tok, "accepted": ok}
+        # the one-call form must give the same bits (and leaves the same policy in the handle for what follows)
+        one = gr.gr_solve_verify(h, p, q, wl.n, wl.k, tol, d, u)
+        assert torch.equal(one[0].view(torch.int32), acc.view(torch.int32)) and torch.equal(one[1], st), "gr_solve_verify: solve outputs differ"
+        assert torch.equal(one[2], tok) and torch.equal(one[3], ok), "gr_solve_verify: token / accepted differ"
         if want_slice:
             out["pi"], out["accept_given"] = gr.gr_policy_slice(h, d, wl.V)
         rows = {}
