@@ -50,6 +50,9 @@ constexpr double kQuadLo = 1e-4;     // t_lo * (slack + sum w): the part below t
 constexpr double kQuadHi = 25.0;     // t_hi * (slowest decay rate)
 constexpr double kStretch = 4.0;     // first cap on the per-coordinate stretch of the fixed-point step
 constexpr int kStall = 3;            // iterations without a better point before the cap is halved
+constexpr double kOddsFrom = 0.9, kOddsTo = 0.999;    // targets within these shares of Pr[token drawn] ...
+constexpr double kOddsFirst = 0.5;                    // ... that start further than this from their routed mass (in log) step on the log odds ...
+constexpr double kOddsUntil = 1e-5;                   // ... while the stopping measure is above this
 constexpr int kMixBudget = 60;       // the mixed fixed-point iteration gets kMixBudget + m evaluations before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kMaxHeavy = 3;         // tokens that keep their exact factor (only with more than 8 drafts)
@@ -77,6 +80,7 @@ struct Lds {
     // one convex program (tokens by decreasing q)
     double aq[kMaxT]; double at[kMaxT]; double aal[kMaxT]; double aR[kMaxT];
     double aS[kMaxT]; double ag[kMaxT];   // with aR: what one evaluation hands to the mixing step (see solve_program)
+    int aodds[kMaxT];                     // tokens that step on their log odds (chosen at a program's first evaluation)
     double aR0, alc;                      // ... the slack mass and, with slack, log(slack mass / its target)
     double ared[2][3];                    // ... and the first two waves' sum of R, max and min of log(target / R)
     double apd[kMaxT];              // Pr[token drawn within the program] = atot^n - (atot - q)^n
@@ -852,7 +856,7 @@ __device__ int newton_program(Lds<D>& L, int& par, double* J, int m, int n, doub
 // The mixing step of one iteration, by wave 0 alone behind the barrier that follows the evaluation.  Compiled as a
 // function of its own (not inlined) so that its values do not compete for registers with the evaluator's series.
 // The uniform solver state travels in MixState; per-token values live in LDS (see solve_program).
-struct MixState { int hcount, plain, since; double best_err, cap; };
+struct MixState { int hcount, plain, since, odds; double best_err, cap; };
 template <int D>
 __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int it, int m, int n, int slack, double ctx, double slack_target,
                                                       double tsum, double atot, double fact, double rel_tol, int evals) {
@@ -893,6 +897,36 @@ __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int
         f[u] = on[u] ? g[u] + lc : 0.0;
         const double d = R[u] - S[u];
         ratio[u] = (on[u] && d > 0.0) ? fmin(R[u] * fast_rcp(d), 1e30) : (on[u] ? 1e30 : 1.0);
+    }
+    // A token whose target nearly exhausts P = Pr[token drawn] (in the targets' units) can saturate: its routed mass
+    // hardly answers to its weight, log(target / R) flattens out and the stretched step crawls (the start weights
+    // leave such a token at log 2 from its target, and every other token has settled long before it has).  What is
+    // linear in its log weight there is the log odds R / (P - R) (the single-draft rule is their fixed point), so
+    // while the iteration is far from its end such a token steps by the difference of the log odds instead, the
+    // stretch changing with it: d log(R / (P - R)) = (R - S) / R * P / (P - R) d log w.  The tokens are chosen once,
+    // at the program's first evaluation (a token that starts near its target is better off with the plain form,
+    // and a form that changes from one iteration to the next spoils the mixing); below kOddsUntil the plain form
+    // takes over for good: the factor P / (P - R) would amplify the error of the quadrature.
+    int odds = st.odds;                                // 0: off, 1: on, 2: on and some token of this program steps on its odds
+    if (odds && err < kOddsUntil) odds = 0;
+    if (odds) {
+        bool sel[2]; double P[2] = {1.0, 1.0}, tg[2] = {0.0, 0.0};
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (on[u]) { P[u] = L.apd[tk[u]]; tg[u] = L.at[tk[u]]; }
+            if (it == 1 && on[u]) L.aodds[tk[u]] = (tg[u] > kOddsFrom * P[u] && tg[u] < kOddsTo * P[u] && fabs(f[u]) > kOddsFirst) ? 1 : 0;
+            sel[u] = on[u] && L.aodds[on[u] ? tk[u] : 0] != 0 && R[u] < P[u];
+        }
+        const bool some = __any(sel[0] || sel[1]);
+        if (it == 1) odds = some ? 2 : 0;              // a program without such a token never looks again
+        if (some) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) if (sel[u]) {
+                const double room = P[u] - R[u];
+                f[u] += fast_log(room * fast_rcp(P[u] - tg[u]));
+                ratio[u] = fmax(ratio[u] * room * fast_rcp(P[u]), 1.0);
+            }
+        }
     }
     bool stop = false;
     if (err <= rel_tol) {
@@ -1039,7 +1073,7 @@ __device__ __attribute__((noinline)) MixState mix_step(MixState st, Grid gr, int
         L.ctl_grid = make_grid(slack, ctx, ws, wm, kQuadStep); L.ctl_bestok = best_err < 1e300 ? 1 : 0;
     }
     ++hcount;
-    st.hcount = hcount; st.plain = plain; st.since = since; st.best_err = best_err; st.cap = cap;
+    st.hcount = hcount; st.plain = plain; st.since = since; st.odds = odds; st.best_err = best_err; st.cap = cap;
     GR_CLK(L, 12);
     return st;
 }
@@ -1118,7 +1152,7 @@ __device__ __forceinline__ int solve_program(Lds<D>& L, int& par, double* newton
     // Wave-0 state: uniform scalars in registers, per-token values in LDS (L.aal, L.at, the best point, the last
     // kHist iterates and stretched residuals by slot, L.pm = inner products of the stored residual vectors).
     MixState st;
-    st.hcount = 0; st.plain = 0; st.since = 0; st.best_err = 1e300; st.cap = kStretch;
+    st.hcount = 0; st.plain = 0; st.since = 0; st.odds = 1; st.best_err = 1e300; st.cap = kStretch;
     const int tk[2] = {lane, lane + 64};
     const bool on[2] = {wvi == 0 && tk[0] < m, wvi == 0 && tk[1] < m};
     if (wvi == 0) {
