@@ -52,7 +52,7 @@ constexpr double kStretch = 4.0;     // first cap on the per-coordinate stretch 
 constexpr int kStall = 3;            // iterations without a better point before the cap is halved
 constexpr double kOddsFrom = 0.9, kOddsTo = 0.999;    // targets within these shares of Pr[token drawn] ...
 constexpr double kOddsFirst = 0.5;                    // ... that start further than this from their routed mass (in log) step on the log odds ...
-constexpr double kOddsUntil = 1e-5;                   // ... while the stopping measure is above this
+constexpr double kOddsUntil = 1e-6;                   // ... while the stopping measure is above this
 constexpr int kMixBudget = 60;       // the mixed fixed-point iteration gets kMixBudget + m evaluations before Newton takes over
 constexpr int kCols = kHist - 1;                       // Anderson columns
 constexpr int kMaxHeavy = 3;         // tokens that keep their exact factor (only with more than 8 drafts)

@@ -66,11 +66,12 @@ def _gpu_policy_as_solution(wl, out, b):
                          np.asarray(weight, float), int(out["status"][b]))
 
 
-def check_row_validity(wl, out, b, drafts, alpha_star):
+def check_row_validity(wl, out, b, drafts, alpha_star, tol=0.0):
     """What must hold for ANY correct result of row b, whichever optimal H* was taken (Sec. 3.1: the slice
     is a distribution; Eq. (cases): its mass sits on the drafts and, for drafts inside H*, on tokens outside
     H*; App. A: accepted iff the token is a draft).  On rows small enough to enumerate every draft tuple
-    the coupling is rebuilt from the GPU's exported policy: marginal = p and acceptance = alpha*."""
+    the coupling is rebuilt from the GPU's exported policy: marginal = p and acceptance = alpha*, both to within the
+    truncated solver's bound when tol > 0 (App. "Truncated Solver Details": at most 15 tol in total variation)."""
     from oracle import brute, gr_oracle as G
     dset = set(int(t) for t in drafts[b])
     if "pi" in out:
@@ -94,8 +95,9 @@ def check_row_validity(wl, out, b, drafts, alpha_star):
         if all(int(t) in sol.pos_of for t in sup):
             marg, acc, norm = brute.coupling_marginals(lambda t: G.policy_slice(sol, wl.p[b], t), qq, wl.n)
             p64 = wl.p[b].astype(np.float64); p64 /= p64.sum()
-            assert norm < 1e-9 and np.abs(marg - p64).max() < ABS_TOL, (b, "marginal of the GPU's coupling", np.abs(marg - p64).max())
-            assert abs(acc - alpha_star) < ABS_TOL, (b, acc, alpha_star)
+            slack = ABS_TOL + 15.0 * tol
+            assert norm < 1e-9 and np.abs(marg - p64).max() < slack, (b, "marginal of the GPU's coupling", np.abs(marg - p64).max())
+            assert abs(acc - alpha_star) < slack, (b, acc, alpha_star)
 
 
 def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None, max_edge_frac=0.05, tail_mass=0.0):
@@ -121,7 +123,7 @@ def compare_rows(wl, out, rows, tol, max_iter=4000, max_T=0, drafts=None, max_ed
         if sol.fragile:                       # several optimal H*: compare what is unique, check that the rest is valid
             stats["fragile"] += 1
             if in_support and out["status"][b] != 3:
-                check_row_validity(wl, out, b, drafts, sol.alpha_star)
+                check_row_validity(wl, out, b, drafts, sol.alpha_star, tol)
             continue
         assert out["status"][b] == sol.status, (b, out["status"][b], sol.status)
         kk = len(sol.order)
