@@ -35,7 +35,7 @@ FP64_PEAK_TFLOPS = 78.6        # MI355X published vector fp64 rate (256 CUs x 64
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) on the default
 # workload, scaled by what the same counters read for the device copy of 8 V B bytes that this script runs itself
 # (profiles/hbm_traffic_large_vocab.md).  Only valid for that workload at the default tau.
-MEASURED_TRAFFIC_BYTES = {"select_kernel": 266589000, "solve_kernel": 42426000, "verify_kernel": 636000}
+MEASURED_TRAFFIC_BYTES = {"select_kernel": 266583000, "solve_kernel": 41623000, "verify_kernel": 636000}
 
 
 def _oracle_row(job):
